@@ -1,0 +1,196 @@
+"""Python access to the CPU oracle (oracle/mcsd_oracle.c).
+
+TEST INFRASTRUCTURE ONLY: imported by tests/, by the smoke check and by the benchmark's CPU-baseline
+leg.  The product package never imports this module, and this module never imports the product.
+It only marshals numpy arrays into the plain-C oracle; all arithmetic lives in the C file.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+from typing import Optional, Sequence
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "mcsd_oracle.c")
+_LIB = os.path.join(_HERE, "libmcsd_oracle.so")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc: -O2, contraction off (explicit fma only), OpenMP over sequences/heads."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-std=c11", "-ffp-contract=off", "-fno-fast-math", "-fopenmp", "-fPIC", "-shared",
+               "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        L = C.CDLL(_LIB)
+        vp, i32, i64, f64 = C.c_void_p, C.c_int32, C.c_int64, C.c_double
+        L.mcsd_oracle_level_sizes.restype = i64
+        L.mcsd_oracle_level_sizes.argtypes = [vp, i32, vp]
+        L.mcsd_oracle_tree_tables.restype = C.c_int
+        L.mcsd_oracle_tree_tables.argtypes = [vp, i32, vp, vp]
+        L.mcsd_oracle_build_mask.restype = C.c_int
+        L.mcsd_oracle_build_mask.argtypes = [vp, i32, vp]
+        L.mcsd_oracle_slice_mask.restype = None
+        L.mcsd_oracle_slice_mask.argtypes = [vp, i64, i64, vp]
+        L.mcsd_oracle_tree_attention.restype = None
+        L.mcsd_oracle_tree_attention.argtypes = [i32, i32, i32, i32, i32, i64, vp, vp, vp, vp, vp, vp, vp, i64,
+                                                 f64, vp, i64, vp]
+        L.mcsd_oracle_tree_attention_row.restype = None
+        L.mcsd_oracle_tree_attention_row.argtypes = [i32, i32, i32, i32, i64, vp, vp, vp, vp, vp, vp, vp, i64,
+                                                     f64, vp, i64, i32, i32, i32, vp]
+        L.mcsd_oracle_verify_tree.restype = C.c_int
+        L.mcsd_oracle_verify_tree.argtypes = [i32, vp, i32, i32, i32, vp, vp, vp, i64, i64, vp, vp, i32, vp, vp, vp]
+        L.mcsd_oracle_tree_sum.restype = f64
+        L.mcsd_oracle_tree_sum.argtypes = [vp, i64]
+        L.mcsd_oracle_tree_sample.restype = i32
+        L.mcsd_oracle_tree_sample.argtypes = [vp, i64, C.c_float]
+        L.mcsd_oracle_improvement_factor.restype = f64
+        L.mcsd_oracle_improvement_factor.argtypes = [f64, f64, f64]
+        _lib = L
+    return _lib
+
+
+def _ptr(a: np.ndarray) -> int:
+    assert a.flags["C_CONTIGUOUS"]
+    return a.ctypes.data
+
+
+def _branching(b: Sequence[int]) -> np.ndarray:
+    return np.ascontiguousarray(np.asarray(b, dtype=np.int32))
+
+
+def level_sizes(branching: Sequence[int]) -> np.ndarray:
+    b = _branching(branching)
+    sizes = np.zeros(len(b), dtype=np.int64)
+    n = _load().mcsd_oracle_level_sizes(_ptr(b), len(b), _ptr(sizes))
+    if n < 0:
+        raise ValueError("bad branching")
+    return sizes
+
+
+def n_nodes(branching: Sequence[int]) -> int:
+    return int(level_sizes(branching).sum())
+
+
+def tree_tables(branching: Sequence[int]):
+    b = _branching(branching)
+    n = n_nodes(b)
+    parent = np.zeros(n, dtype=np.int32)
+    level = np.zeros(n, dtype=np.int32)
+    if _load().mcsd_oracle_tree_tables(_ptr(b), len(b), _ptr(parent), _ptr(level)) != 0:
+        raise ValueError("bad branching")
+    return parent, level
+
+
+def build_mask(branching: Sequence[int]) -> np.ndarray:
+    """Dense uint8 [N][N] topology-aware causal mask of the whole tree."""
+    b = _branching(branching)
+    n = n_nodes(b)
+    M = np.zeros((n, n), dtype=np.uint8)
+    if _load().mcsd_oracle_build_mask(_ptr(b), len(b), _ptr(M)) != 0:
+        raise ValueError("bad branching")
+    return M
+
+
+def slice_mask(M: np.ndarray, n: int) -> np.ndarray:
+    M = np.ascontiguousarray(M, dtype=np.uint8)
+    out = np.zeros((n, n), dtype=np.uint8)
+    _load().mcsd_oracle_slice_mask(_ptr(M), M.shape[0], n, _ptr(out))
+    return out
+
+
+def _dtype_code(dtype: str) -> int:
+    return {"f32": 0, "bf16": 1}[dtype]
+
+
+def _check_store(a: np.ndarray, dtype: str) -> np.ndarray:
+    want = np.float32 if dtype == "f32" else np.uint16
+    assert a.dtype == want, (a.dtype, want)
+    return np.ascontiguousarray(a)
+
+
+def tree_attention(inp: dict, M: np.ndarray, n: int) -> np.ndarray:
+    """All outputs, binary64 [B][H][n][d], for an input dict as made by workloads.attention_inputs."""
+    dt = inp["dtype"]
+    q, kt, vt = (_check_store(inp[k], dt) for k in ("q", "k_tree", "v_tree"))
+    kp, vp = (_check_store(inp[k], dt) for k in ("k_prefix", "v_prefix"))
+    B, H, _, d = q.shape
+    M = np.ascontiguousarray(M, dtype=np.uint8)
+    lens = np.ascontiguousarray(inp["lens"], dtype=np.int32)
+    base = np.ascontiguousarray(inp["seq_base"], dtype=np.int64)
+    out = np.zeros((B, H, n, d), dtype=np.float64)
+    _load().mcsd_oracle_tree_attention(_dtype_code(dt), B, H, d, n, int(inp["node_stride"]), _ptr(q), _ptr(kt),
+                                       _ptr(vt), _ptr(kp), _ptr(vp), _ptr(base), _ptr(lens),
+                                       int(inp["head_stride"]), float(np.float32(inp["scale"])), _ptr(M),
+                                       M.shape[1], _ptr(out))
+    return out
+
+
+def tree_attention_row(inp: dict, M: np.ndarray, n: int, b: int, h: int, i: int) -> np.ndarray:
+    """One output row (d values, binary64) for sequence b, head h, tree node i."""
+    dt = inp["dtype"]
+    q, kt, vt = (_check_store(inp[k], dt) for k in ("q", "k_tree", "v_tree"))
+    kp, vp = (_check_store(inp[k], dt) for k in ("k_prefix", "v_prefix"))
+    _, H, _, d = q.shape
+    M = np.ascontiguousarray(M, dtype=np.uint8)
+    lens = np.ascontiguousarray(inp["lens"], dtype=np.int32)
+    base = np.ascontiguousarray(inp["seq_base"], dtype=np.int64)
+    out = np.zeros(d, dtype=np.float64)
+    _load().mcsd_oracle_tree_attention_row(_dtype_code(dt), H, d, n, int(inp["node_stride"]), _ptr(q), _ptr(kt),
+                                           _ptr(vt), _ptr(kp), _ptr(vp), _ptr(base), _ptr(lens),
+                                           int(inp["head_stride"]), float(np.float32(inp["scale"])), _ptr(M),
+                                           M.shape[1], b, h, i, _ptr(out))
+    return out
+
+
+def verify_tree(mode: int, branching: Sequence[int], tokens: np.ndarray, p: np.ndarray, q: np.ndarray,
+                u_accept: np.ndarray, u_sample: np.ndarray):
+    """Returns (path int32 [B][G] padded with -1, accept_len int32 [B], new_tokens int32 [B][n_new])."""
+    b = _branching(branching)
+    G = len(b)
+    tokens = np.ascontiguousarray(tokens, dtype=np.int32)
+    p = np.ascontiguousarray(p, dtype=np.float32)
+    q = np.ascontiguousarray(q, dtype=np.float32)
+    ua = np.ascontiguousarray(u_accept, dtype=np.float32)
+    us = np.ascontiguousarray(u_sample, dtype=np.float32)
+    B, N = tokens.shape
+    V = p.shape[-1]
+    sizes = level_sizes(b)
+    assert N == int(sizes.sum()), (N, sizes)
+    assert p.shape == (B, 1 + N, V), p.shape
+    assert q.shape == (B, 1 + N - int(sizes[-1]), V), q.shape
+    assert ua.shape == (B, N)
+    n_new = us.shape[1]
+    path = np.zeros((B, G), dtype=np.int32)
+    alen = np.zeros(B, dtype=np.int32)
+    new = np.zeros((B, n_new), dtype=np.int32)
+    rc = _load().mcsd_oracle_verify_tree(int(mode), _ptr(b), G, B, V, _ptr(tokens), _ptr(p), _ptr(q),
+                                         p.shape[1] * V, q.shape[1] * V, _ptr(ua), _ptr(us), n_new,
+                                         _ptr(path), _ptr(alen), _ptr(new))
+    if rc != 0:
+        raise ValueError(f"oracle verify_tree failed: {rc}")
+    return path, alen, new
+
+
+def tree_sum(a: np.ndarray) -> float:
+    a = np.ascontiguousarray(a, dtype=np.float64)
+    return float(_load().mcsd_oracle_tree_sum(_ptr(a), a.size))
+
+
+def tree_sample(a: np.ndarray, u: float) -> int:
+    a = np.ascontiguousarray(a, dtype=np.float64)
+    return int(_load().mcsd_oracle_tree_sample(_ptr(a), a.size, float(np.float32(u))))
+
+
+def improvement_factor(alpha: float, gamma: float, c: float) -> float:
+    return float(_load().mcsd_oracle_improvement_factor(alpha, gamma, c))
