@@ -1,0 +1,159 @@
+/*
+ * libmcsd -- verification hot path of multi-candidate speculative decoding on AMD MI355X (gfx950).
+ *
+ * Implements, for "Improving Multi-candidate Speculative Decoding" (arXiv 2409.10644):
+ *   - the topology-aware causal mask of a candidate token tree, built once for the longest draft length
+ *     and sliced for every shorter one without rebuilding (Sec. 2.2, Sec. 3.2 and Fig. 2);
+ *   - the target model's tree-attention pass: every tree node attends to the prefix KV cache and to its
+ *     own ancestors in the tree (Sec. 2.2);
+ *   - multi-candidate acceptance by recursive rejection sampling, longest-path selection for
+ *     target-initialised trees and sampling of the new token(s) (Sec. 2.1, Sec. 3.1, Fig. 1 steps 4-6).
+ *
+ * Plain C ABI.  Every pointer is marked HOST or DEVICE.  The library owns only mask handles; every
+ * tensor and workspace belongs to the caller.  Device work is enqueued on the caller's HIP stream and
+ * the calls return without synchronising (mcsd_build_mask excepted).  Functions return MCSD_OK (0) or a
+ * negative status; they never abort, throw or print.  Arguments are validated on the host before any
+ * launch; on error nothing has been enqueued and no output has been touched.
+ *
+ * Tree convention.  A tree is the tuple of per-level branching factors (b_1 .. b_G), e.g. (4,2,2,1) or the
+ * target-initialised (2,4,3,1,1) of Sec. 4.1.  Level l has N_l = b_1*...*b_l nodes; nodes are numbered
+ * level by level, children of one parent next to each other, so node a of level l > 1 has parent a / b_l
+ * of level l-1.  "gamma" below is the number of tree levels in use; N(gamma) = N_1 + ... + N_gamma.
+ */
+#ifndef MCSD_H
+#define MCSD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    MCSD_OK = 0,
+    MCSD_EINVAL = -1,       /* bad argument (null pointer, size out of range, gamma outside 1..gamma_max, ...) */
+    MCSD_ENOMEM = -2,       /* host or device allocation failed (mcsd_build_mask only) */
+    MCSD_EHIP = -3,         /* a HIP call or kernel launch reported an error */
+    MCSD_EWORKSPACE = -4,   /* workspace missing or smaller than mcsd_*_workspace() says */
+    MCSD_EUNSUPPORTED = -5  /* valid request outside the kernels' limits (see each function) */
+};
+
+enum { MCSD_MAX_LEVELS = 32, MCSD_MAX_NODES = 4096, MCSD_ATTN_MAX_NODES = 128, MCSD_MAX_BRANCH = 64,
+       MCSD_MAX_VOCAB = 262144 };
+
+typedef enum { MCSD_F32 = 0, MCSD_BF16 = 1 } mcsd_dtype_t;
+typedef enum { MCSD_DRAFT_INIT = 0, MCSD_TARGET_INIT = 1 } mcsd_mode_t;
+
+/* Static string for a status code.  HOST.  Never free it. */
+const char *mcsd_strerror(int status);
+
+/* ---------------------------------------------------------------------------------------------------
+ * Mask (Sec. 2.2; Sec. 3.2, Fig. 2)
+ * ------------------------------------------------------------------------------------------------- */
+
+typedef struct mcsd_mask mcsd_mask_t; /* opaque, owned by the library */
+
+/* A borrowed view of (a slice of) a mask.  Valid until mcsd_free_mask() of the handle it came from.
+ * Bit j of row i (word i*words_per_row + j/64, bit j%64) is 1 iff tree node j is node i itself or an
+ * ancestor of node i.  Rows of a slice keep the stride of the full mask. */
+typedef struct {
+    int32_t gamma;            /* levels in this slice */
+    int32_t n_nodes;          /* N(gamma) */
+    int32_t gamma_max;        /* levels of the full mask */
+    int32_t n_nodes_max;      /* N(gamma_max) */
+    int32_t words_per_row;    /* 64-bit words per row, that of the full mask */
+    int32_t device;           /* HIP device that holds the *_dev arrays */
+    const uint64_t *bits_host;      /* HOST   [n_nodes_max][words_per_row] */
+    const uint64_t *bits_dev;       /* DEVICE same layout */
+    const int32_t *parent_host;     /* HOST   [n_nodes_max], -1 for level-1 nodes */
+    const int32_t *parent_dev;      /* DEVICE */
+    const int32_t *level_host;      /* HOST   [n_nodes_max], 1-based */
+    const int32_t *level_off_host;  /* HOST   [gamma_max+1], first node id of each level; last = n_nodes_max */
+    const int32_t *branching_host;  /* HOST   [gamma_max] */
+} mcsd_mask_view_t;
+
+/* Build the mask for the whole tree (all gamma_max levels) on the host and upload it once to the current
+ * HIP device.  Synchronises.  branching: HOST [gamma_max], every entry in 1..MCSD_MAX_BRANCH;
+ * 1 <= gamma_max <= MCSD_MAX_LEVELS; N(gamma_max) <= MCSD_MAX_NODES.  *out receives a handle the caller
+ * releases with mcsd_free_mask().  On a machine without a HIP device the handle holds the host copy only
+ * (views have device = -1 and null *_dev pointers, which the device entry points reject). */
+int mcsd_build_mask(const int32_t *branching, int32_t gamma_max, mcsd_mask_t **out);
+
+/* The mask for draft length gamma (1..gamma_max): the upper-left N(gamma) x N(gamma) block of the full
+ * mask (Sec. 3.2).  Constant time: fills *out (HOST) with pointers into the handle; no allocation, no
+ * copy, no launch. */
+int mcsd_slice_mask(const mcsd_mask_t *full, int32_t gamma, mcsd_mask_view_t *out);
+
+/* Releases the handle's host and device memory.  NULL is allowed.  Views of it become invalid. */
+void mcsd_free_mask(mcsd_mask_t *mask);
+
+/* ---------------------------------------------------------------------------------------------------
+ * Tree attention (Sec. 2.2)
+ *
+ * For every sequence b, head h and tree node i < n_nodes:
+ *     out[b][h][i] = sum_j softmax_j(softmax_scale * <q_i, k_j>) * v_j
+ * over all prefix keys j < prefix_lens[b] and all tree keys j whose mask bit (i, j) is set.
+ *
+ * q, k_tree, v_tree, out : DEVICE [B][H][node_stride][d]; the first n_nodes rows of each (b,h) are used /
+ *                          written (node_stride >= n_nodes lets a gamma-slice be a view of gamma_max tensors).
+ * k_prefix, v_prefix     : DEVICE; element (b,h,j,c) at seq_base[b] + h*head_stride + j*d + c.
+ * seq_base_dev           : DEVICE int64 [B], element offsets.   prefix_lens_dev: DEVICE int32 [B], each in
+ *                          0..max_prefix (larger values are clamped to max_prefix).
+ * dtype                  : element type of q/k/v/out.  MCSD_BF16: bf16 in, fp32 accumulate on MFMA, bf16 out.
+ *                          MCSD_F32: fp32 end to end on the vector ALU.
+ * Limits: d in {64, 128}; 1 <= n_nodes <= MCSD_ATTN_MAX_NODES; softmax_scale finite and > 0; all tensor
+ * base addresses 16-byte aligned; node_stride*d and head_stride and seq_base multiples of 8 elements.
+ * workspace: DEVICE, at least mcsd_tree_attention_workspace(...) bytes, 256-byte aligned; holds the partial
+ * results of the key splits; contents need not be initialised and are not meaningful afterwards.
+ * Calls that share a workspace must be ordered on one stream.  Inputs are never modified.
+ * ------------------------------------------------------------------------------------------------- */
+size_t mcsd_tree_attention_workspace(int32_t B, int32_t H, int32_t d, int32_t n_nodes, int32_t max_prefix);
+
+int mcsd_tree_attention(const mcsd_mask_view_t *mask, mcsd_dtype_t dtype, int32_t B, int32_t H, int32_t d,
+                        const void *q, const void *k_tree, const void *v_tree, int64_t node_stride,
+                        const void *k_prefix, const void *v_prefix, const int64_t *seq_base_dev,
+                        const int32_t *prefix_lens_dev, int64_t head_stride, int32_t max_prefix,
+                        float softmax_scale, void *out, void *workspace, size_t workspace_bytes,
+                        void *hip_stream);
+
+/* ---------------------------------------------------------------------------------------------------
+ * Verification (Sec. 2.1; Sec. 3.1; Fig. 1 steps 4-6)
+ *
+ * Recursive rejection sampling down the tree.  At a context with target row p and draft row q the
+ * children are tried in node order: child c with token x is accepted iff  u_accept[c] * q(x) * S < r(x),
+ * where r starts as p with S = 1 and after every rejection r <- max(r - S*q, 0), S <- sum(r) (the
+ * unnormalised form of p <- norm(max(p - q, 0))).  The first accepted child becomes the context.  The walk
+ * ends when all children of a context are rejected (new tokens come from r, or from p if r vanished) or
+ * when level gamma is reached (new tokens come from the target row after the last node).
+ * MCSD_DRAFT_INIT : one walk from the context that ends the prefix.
+ * MCSD_TARGET_INIT: level-1 nodes were sampled from the target and are accepted untested; one walk per
+ *                   level-1 node, the longest path wins (lowest node id on ties).
+ * All arithmetic is binary64 with vocabulary sums taken as a balanced binary tree over the index space
+ * padded with zeros to a power of two, and new tokens are drawn by descending that tree with threshold
+ * u_sample * S; results are therefore reproducible bit for bit on any machine.
+ *
+ * tokens         : DEVICE int32 [B][n_nodes], each in 0..V-1
+ * p_target       : DEVICE fp32; row r of sequence b at b*p_batch_stride + r*V; row 0 is the context that
+ *                  ends the prefix, row 1+i the context after node i; rows 0..n_nodes
+ * q_draft        : DEVICE fp32; same addressing with q_batch_stride; rows 0..N(gamma-1)
+ * u_accept       : DEVICE fp32 [B][n_nodes] in [0,1), indexed by node
+ * u_sample       : DEVICE fp32 [B][n_new] in [0,1);   0 <= n_new <= 64
+ * out_path       : DEVICE int32 [B][gamma], accepted node ids from level 1 down, padded with -1
+ * out_accept_len : DEVICE int32 [B]
+ * out_new_tokens : DEVICE int32 [B][n_new], i.i.d. draws from the terminal distribution
+ * workspace      : DEVICE, mcsd_verify_tree_workspace(...) bytes (0 for MCSD_DRAFT_INIT: may be NULL)
+ * Limits: 1 <= V <= MCSD_MAX_VOCAB.
+ * ------------------------------------------------------------------------------------------------- */
+size_t mcsd_verify_tree_workspace(const mcsd_mask_view_t *mask, mcsd_mode_t mode, int32_t B, int32_t n_new);
+
+int mcsd_verify_tree(const mcsd_mask_view_t *mask, mcsd_mode_t mode, int32_t B, int32_t V,
+                     const int32_t *tokens, const float *p_target, const float *q_draft,
+                     int64_t p_batch_stride, int64_t q_batch_stride, const float *u_accept,
+                     const float *u_sample, int32_t n_new, int32_t *out_path, int32_t *out_accept_len,
+                     int32_t *out_new_tokens, void *workspace, size_t workspace_bytes, void *hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MCSD_H */

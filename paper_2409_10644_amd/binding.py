@@ -1,0 +1,170 @@
+"""ctypes binding of libmcsd.so: same names and argument order as include/mcsd.h, marshalling only."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Sequence
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libmcsd.so")
+
+MCSD_OK, MCSD_EINVAL, MCSD_ENOMEM, MCSD_EHIP, MCSD_EWORKSPACE, MCSD_EUNSUPPORTED = 0, -1, -2, -3, -4, -5
+MCSD_F32, MCSD_BF16 = 0, 1
+MCSD_DRAFT_INIT, MCSD_TARGET_INIT = 0, 1
+
+EXPORTS = ["mcsd_strerror", "mcsd_build_mask", "mcsd_slice_mask", "mcsd_free_mask",
+           "mcsd_tree_attention_workspace", "mcsd_tree_attention",
+           "mcsd_verify_tree_workspace", "mcsd_verify_tree"]
+
+
+class MaskView(C.Structure):
+    """mcsd_mask_view_t"""
+    _fields_ = [("gamma", C.c_int32), ("n_nodes", C.c_int32), ("gamma_max", C.c_int32),
+                ("n_nodes_max", C.c_int32), ("words_per_row", C.c_int32), ("device", C.c_int32),
+                ("bits_host", C.POINTER(C.c_uint64)), ("bits_dev", C.c_void_p),
+                ("parent_host", C.POINTER(C.c_int32)), ("parent_dev", C.c_void_p),
+                ("level_host", C.POINTER(C.c_int32)), ("level_off_host", C.POINTER(C.c_int32)),
+                ("branching_host", C.POINTER(C.c_int32))]
+
+
+class McsdError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {strerror(status)} ({status})")
+
+
+def _load() -> C.CDLL:
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2409_10644_amd.build` "
+                          "(there is no CPU fallback)")
+    lib = C.CDLL(LIB_PATH)
+    # The library must share the HIP runtime that PyTorch loaded (streams and allocations cross the boundary).
+    with open("/proc/self/maps") as f:
+        runtimes = {line.split()[-1] for line in f if "libamdhip64" in line}
+    if len(runtimes) > 1:
+        raise ImportError(f"two HIP runtimes in one process: {sorted(runtimes)}")
+    vp, i32, i64, sz = C.c_void_p, C.c_int32, C.c_int64, C.c_size_t
+    lib.mcsd_strerror.restype = C.c_char_p
+    lib.mcsd_strerror.argtypes = [C.c_int]
+    lib.mcsd_build_mask.restype = C.c_int
+    lib.mcsd_build_mask.argtypes = [C.POINTER(i32), i32, C.POINTER(vp)]
+    lib.mcsd_slice_mask.restype = C.c_int
+    lib.mcsd_slice_mask.argtypes = [vp, i32, C.POINTER(MaskView)]
+    lib.mcsd_free_mask.restype = None
+    lib.mcsd_free_mask.argtypes = [vp]
+    lib.mcsd_tree_attention_workspace.restype = sz
+    lib.mcsd_tree_attention_workspace.argtypes = [i32, i32, i32, i32, i32]
+    lib.mcsd_tree_attention.restype = C.c_int
+    lib.mcsd_tree_attention.argtypes = [C.POINTER(MaskView), C.c_int, i32, i32, i32, vp, vp, vp, i64, vp, vp, vp,
+                                        vp, i64, i32, C.c_float, vp, vp, sz, vp]
+    lib.mcsd_verify_tree_workspace.restype = sz
+    lib.mcsd_verify_tree_workspace.argtypes = [C.POINTER(MaskView), C.c_int, i32, i32]
+    lib.mcsd_verify_tree.restype = C.c_int
+    lib.mcsd_verify_tree.argtypes = [C.POINTER(MaskView), C.c_int, i32, i32, vp, vp, vp, i64, i64, vp, vp, i32,
+                                     vp, vp, vp, vp, sz, vp]
+    return lib
+
+
+lib = _load()
+
+
+def strerror(status: int) -> str:
+    return lib.mcsd_strerror(int(status)).decode()
+
+
+def _check(status: int, where: str) -> None:
+    if status != MCSD_OK:
+        raise McsdError(status, where)
+
+
+def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+def _stream(stream=None) -> int:
+    s = torch.cuda.current_stream() if stream is None else stream
+    return s.cuda_stream
+
+
+class Mask:
+    """Owner of an mcsd_mask_t handle (built once at gamma_max)."""
+
+    def __init__(self, handle: int, gamma_max: int):
+        self.handle = handle
+        self.gamma_max = gamma_max
+        self._free = lib.mcsd_free_mask      # bound here: module globals may be gone at interpreter exit
+
+    def close(self) -> None:
+        if self.handle:
+            self._free(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def build_mask(branching: Sequence[int], gamma_max: Optional[int] = None) -> Mask:
+    g = len(branching) if gamma_max is None else int(gamma_max)
+    arr = (C.c_int32 * max(len(branching), 1))(*[int(x) for x in branching])
+    handle = C.c_void_p()
+    _check(lib.mcsd_build_mask(arr, g, C.byref(handle)), "mcsd_build_mask")
+    return Mask(handle.value, g)
+
+
+def slice_mask(mask: Mask, gamma: int) -> MaskView:
+    view = MaskView()
+    _check(lib.mcsd_slice_mask(mask.handle, int(gamma), C.byref(view)), "mcsd_slice_mask")
+    view._owner = mask          # keep the handle alive as long as the view
+    return view
+
+
+def free_mask(mask: Mask) -> None:
+    mask.close()
+
+
+def tree_attention_workspace(B: int, H: int, d: int, n_nodes: int, max_prefix: int) -> int:
+    return int(lib.mcsd_tree_attention_workspace(B, H, d, n_nodes, max_prefix))
+
+
+def tree_attention(view: MaskView, dtype: int, B: int, H: int, d: int, q: torch.Tensor, k_tree: torch.Tensor,
+                   v_tree: torch.Tensor, node_stride: int, k_prefix: Optional[torch.Tensor],
+                   v_prefix: Optional[torch.Tensor], seq_base_dev: torch.Tensor, prefix_lens_dev: torch.Tensor,
+                   head_stride: int, max_prefix: int, softmax_scale: float, out: torch.Tensor,
+                   workspace: Optional[torch.Tensor], stream=None) -> None:
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    st = lib.mcsd_tree_attention(C.byref(view), dtype, B, H, d, _ptr(q), _ptr(k_tree), _ptr(v_tree), node_stride,
+                                 _ptr(k_prefix), _ptr(v_prefix), _ptr(seq_base_dev), _ptr(prefix_lens_dev),
+                                 head_stride, max_prefix, softmax_scale, _ptr(out), _ptr(workspace), ws_bytes,
+                                 _stream(stream))
+    _check(st, "mcsd_tree_attention")
+
+
+def verify_tree_workspace(view: MaskView, mode: int, B: int, n_new: int) -> int:
+    return int(lib.mcsd_verify_tree_workspace(C.byref(view), mode, B, n_new))
+
+
+def verify_tree(view: MaskView, mode: int, B: int, V: int, tokens: torch.Tensor, p_target: torch.Tensor,
+                q_draft: Optional[torch.Tensor], p_batch_stride: int, q_batch_stride: int, u_accept: torch.Tensor,
+                u_sample: Optional[torch.Tensor], n_new: int, out_path: torch.Tensor, out_accept_len: torch.Tensor,
+                out_new_tokens: Optional[torch.Tensor], workspace: Optional[torch.Tensor], stream=None) -> None:
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    st = lib.mcsd_verify_tree(C.byref(view), mode, B, V, _ptr(tokens), _ptr(p_target), _ptr(q_draft), p_batch_stride,
+                              q_batch_stride, _ptr(u_accept), _ptr(u_sample), n_new, _ptr(out_path),
+                              _ptr(out_accept_len), _ptr(out_new_tokens), _ptr(workspace), ws_bytes, _stream(stream))
+    _check(st, "mcsd_verify_tree")
+
+
+def mask_bits_host(view: MaskView):
+    """The slice as a dense uint8 [n][n] numpy array, unpacked from the handle's host copy (for checks)."""
+    import numpy as np
+    n, W = view.n_nodes, view.words_per_row
+    words = np.ctypeslib.as_array(view.bits_host, shape=(view.n_nodes_max * W,)).reshape(view.n_nodes_max, W)
+    out = np.zeros((n, n), dtype=np.uint8)
+    for j in range(n):
+        out[:, j] = (words[:n, j >> 6] >> np.uint64(j & 63)) & np.uint64(1)
+    return out

@@ -1,0 +1,29 @@
+// Internal declarations shared by the library's translation units (not part of the public ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include "mcsd.h"
+
+struct mcsd_mask {
+    int32_t gamma_max;
+    int32_t n_nodes_max;
+    int32_t words_per_row;
+    int32_t device;
+    int32_t branching[MCSD_MAX_LEVELS];
+    int32_t level_off[MCSD_MAX_LEVELS + 1];
+    uint64_t *bits_host;
+    int32_t *parent_host;
+    int32_t *level_host;
+    void *dev_block;       // one device allocation: bits, then parent
+    uint64_t *bits_dev;
+    int32_t *parent_dev;
+};
+
+// Tree shape passed to kernels by value.
+struct McsdTreeDesc {
+    int32_t gamma;
+    int32_t b[MCSD_MAX_LEVELS];
+    int32_t off[MCSD_MAX_LEVELS + 1];
+};
+
+static inline int mcsd_hip_status(hipError_t e) { return e == hipSuccess ? MCSD_OK : MCSD_EHIP; }

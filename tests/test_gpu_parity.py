@@ -1,0 +1,343 @@
+"""GPU parity: libmcsd.so (through the C ABI) against the CPU oracle on the same seeded inputs.
+
+Masks, accepted paths, lengths and sampled tokens must match bit for bit; attention within 2e-2 relative /
+1e-2 absolute (bf16 path) or 1e-5 (fp32 path) of the binary64 oracle.
+"""
+import ctypes
+
+import numpy as np
+import pytest
+import torch
+
+from workloads import DRAFT_INIT, TARGET_INIT, WORKLOADS, attention_inputs, prefix_lens, scaled, verify_inputs
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def binding():
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    from paper_2409_10644_amd import binding as b
+    return b
+
+
+@pytest.fixture(scope="module")
+def H():
+    import gpu_helpers
+    return gpu_helpers
+
+
+def _sample_rows(rng, B, Hh, n, count):
+    rows = {(0, 0, 0), (B - 1, Hh - 1, n - 1)}
+    while len(rows) < count:
+        rows.add((int(rng.integers(B)), int(rng.integers(Hh)), int(rng.integers(n))))
+    return sorted(rows)
+
+
+# ------------------------------------------------------------------------------------------------
+# masks on the device
+# ------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("name", ["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
+def test_device_mask_bits_match_oracle_for_every_gamma(binding, oracle, name):
+    w = WORKLOADS[name]
+    m = binding.build_mask(w.branching)
+    full = oracle.build_mask(w.branching)
+    for g in range(1, w.gamma_max + 1):
+        v = binding.slice_mask(m, g)
+        assert v.device >= 0 and v.bits_dev
+        n, W = v.n_nodes, v.words_per_row
+        host = np.empty(v.n_nodes_max * W, dtype=np.uint64)
+        torch.cuda.synchronize()
+        hip = ctypes.CDLL("libamdhip64.so")               # plain device-to-host copy of the library's buffer
+        assert hip.hipMemcpy(ctypes.c_void_p(host.ctypes.data), ctypes.c_void_p(v.bits_dev), host.nbytes, 2) == 0
+        host = host.reshape(v.n_nodes_max, W)
+        got = np.zeros((n, n), dtype=np.uint8)
+        for j in range(n):
+            got[:, j] = (host[:n, j >> 6] >> np.uint64(j & 63)) & np.uint64(1)
+        assert np.array_equal(got, oracle.build_mask(w.branching[:g]))
+        assert np.array_equal(got, oracle.slice_mask(full, n))
+
+
+# ------------------------------------------------------------------------------------------------
+# attention: the five configurations
+# ------------------------------------------------------------------------------------------------
+def test_cfg1_fp32_every_gamma(binding, oracle, H):
+    w = WORKLOADS["cfg1"]
+    inp = attention_inputs(w, seed=0)
+    ad = H.AttnDevice(inp)
+    m = binding.build_mask(w.branching)
+    M = oracle.build_mask(w.branching)
+    for g in (1, 2, 3):
+        v = binding.slice_mask(m, g)
+        got = H.run_attention(binding, v, ad)
+        want = oracle.tree_attention(inp, M, v.n_nodes)
+        H.assert_close(got, want, "f32", f"cfg1 gamma={g}")
+
+
+def test_cfg2_full(binding, oracle, H):
+    w = WORKLOADS["cfg2"]
+    inp = attention_inputs(w, seed=0)
+    ad = H.AttnDevice(inp)
+    m = binding.build_mask(w.branching)
+    v = binding.slice_mask(m, w.gamma_max)
+    got = H.run_attention(binding, v, ad, fill=float("nan"))
+    want = oracle.tree_attention(inp, oracle.build_mask(w.branching), v.n_nodes)
+    H.assert_close(got, want, "bf16", "cfg2")
+    # rows beyond n_nodes of the output buffer are not touched (node_stride == n here, so nothing to check);
+    # determinism: a second call gives the same bits
+    again = H.run_attention(binding, v, ad)
+    assert np.array_equal(got, again)
+
+
+def test_cfg2_tensors_scaled_variant(binding, oracle, H):
+    """Second reading of the recipe: tensors themselves scaled by 1/sqrt(128) (flat softmax)."""
+    w = WORKLOADS["cfg2"]
+    inp = attention_inputs(w, seed=1, tensor_mult=float(1 / np.sqrt(128)))
+    ad = H.AttnDevice(inp)
+    m = binding.build_mask(w.branching)
+    v = binding.slice_mask(m, w.gamma_max)
+    got = H.run_attention(binding, v, ad)
+    want = oracle.tree_attention(inp, oracle.build_mask(w.branching), v.n_nodes)
+    H.assert_close(got, want, "bf16", "cfg2 scaled tensors")
+
+
+def test_cfg3_gamma_sweep_by_slicing_only(binding, oracle, H):
+    w = WORKLOADS["cfg3"]
+    inp = attention_inputs(w, seed=0)
+    ad = H.AttnDevice(inp)
+    m = binding.build_mask(w.branching)           # built once at gamma_max = 8
+    M = oracle.build_mask(w.branching)
+    for g in range(1, 9):
+        v = binding.slice_mask(m, g)
+        got = H.run_attention(binding, v, ad, fill=123.0)
+        want = oracle.tree_attention(inp, M, v.n_nodes)
+        H.assert_close(got, want, "bf16", f"cfg3 gamma={g}")
+        # rows of the gamma_max-sized output beyond N(gamma) keep the fill value: padded queries are never stored
+        rest = ad.out[:, :, v.n_nodes:].float().cpu().numpy()
+        assert np.all(rest == 123.0)
+
+
+def test_cfg4_ragged_batch_sampled_rows(binding, oracle, H):
+    w = WORKLOADS["cfg4"]
+    lens = prefix_lens(w, 0)
+    assert lens.min() >= 512 and lens.max() <= 4096 and len(set(lens.tolist())) > 8
+    inp = attention_inputs(w, seed=0, kv_capacity=4096)
+    ad = H.AttnDevice(inp)
+    m = binding.build_mask(w.branching)
+    v = binding.slice_mask(m, w.gamma_max)
+    got = H.run_attention(binding, v, ad, max_prefix=4096)
+    M = oracle.build_mask(w.branching)
+    rng = np.random.default_rng(4)
+    assert np.all(np.isfinite(got))
+    for (b, h, i) in _sample_rows(rng, w.B, w.H, v.n_nodes, 160):
+        want = oracle.tree_attention_row(inp, M, v.n_nodes, b, h, i)
+        H.assert_close(got[b, h, i], want, "bf16", f"cfg4 row {(b, h, i)}")
+
+
+def test_cfg5_long_context_sampled_rows(binding, oracle, H):
+    """gamma = 5 (120 nodes) and its gamma = 4 slice (88 nodes) over the same buffers."""
+    w = WORKLOADS["cfg5"]
+    inp = attention_inputs(w, seed=0)
+    ad = H.AttnDevice(inp)
+    m = binding.build_mask(w.branching)
+    M = oracle.build_mask(w.branching)
+    for g in (5, 4):
+        v = binding.slice_mask(m, g)
+        assert v.n_nodes == (120 if g == 5 else 88)
+        got = H.run_attention(binding, v, ad)
+        rng = np.random.default_rng(5)
+        assert np.all(np.isfinite(got))
+        for (b, h, i) in _sample_rows(rng, w.B, w.H, v.n_nodes, 48):
+            want = oracle.tree_attention_row(inp, M, v.n_nodes, b, h, i)
+            H.assert_close(got[b, h, i], want, "bf16", f"cfg5 gamma={g} row {(b, h, i)}")
+    del ad
+    torch.cuda.empty_cache()
+
+
+# ------------------------------------------------------------------------------------------------
+# attention: edge cases, every topology with short / empty prefixes (mask errors are visible there)
+# ------------------------------------------------------------------------------------------------
+TOPOLOGIES = [(2, 2, 2), (4, 2, 2, 1), (3, 2, 2, 1, 1, 1, 1, 1), (4, 2, 2, 2), (8, 2, 2, 1, 1), (2, 4, 3, 1, 1),
+              (16, 1, 1, 1, 1), (1,), (1, 1, 1), (8, 3, 4), (33,), (5, 5)]
+
+
+@pytest.mark.parametrize("dtype,d", [("bf16", 128), ("bf16", 64), ("f32", 64), ("f32", 128)])
+@pytest.mark.parametrize("br", TOPOLOGIES)
+def test_short_and_empty_prefix_every_topology(binding, oracle, H, br, dtype, d):
+    w = scaled(WORKLOADS["cfg2"], B=3, H=2, d=d, dtype=dtype, branching=tuple(br), cfg_id=50)
+    inp = attention_inputs(w, seed=7, lens=(0, 1, 5), kv_capacity=8)
+    ad = H.AttnDevice(inp)
+    m = binding.build_mask(br)
+    M = oracle.build_mask(br)
+    for g in sorted({1, len(br)}):
+        v = binding.slice_mask(m, g)
+        got = H.run_attention(binding, v, ad, max_prefix=8)
+        want = oracle.tree_attention(inp, M, v.n_nodes)
+        H.assert_close(got, want, dtype, f"tree {br} gamma={g}")
+
+
+@pytest.mark.parametrize("L", [63, 64, 65, 127, 128, 129, 200, 1000])
+@pytest.mark.parametrize("br", [(4, 2, 2, 1), (8, 2, 2, 1, 1), (3, 2)])
+def test_ragged_tails_and_split_boundaries(binding, oracle, H, br, L):
+    """Prefix lengths around the tile size; with B*H small the sweep is split over several workgroups."""
+    w = scaled(WORKLOADS["cfg2"], B=2, H=2, branching=tuple(br), cfg_id=51)
+    inp = attention_inputs(w, seed=L, lens=(L, max(L - 37, 0)), kv_capacity=L + 3)
+    ad = H.AttnDevice(inp)
+    m = binding.build_mask(br)
+    v = binding.slice_mask(m, len(br))
+    got = H.run_attention(binding, v, ad, max_prefix=L + 3)
+    want = oracle.tree_attention(inp, oracle.build_mask(br), v.n_nodes)
+    H.assert_close(got, want, "bf16", f"L={L} tree {br}")
+
+
+def test_boosted_tree_keys_make_mask_errors_visible(binding, oracle, H):
+    """Long prefix, but every tree key is aligned with every query, so the visible tree keys share most of the
+    softmax weight equally: one wrong mask bit moves the output far beyond the tolerance."""
+    br = (4, 2, 2, 1)
+    w = scaled(WORKLOADS["cfg2"], B=1, H=4, branching=br, cfg_id=52)
+    inp = attention_inputs(w, seed=9, lens=(777,))
+    from workloads import bf16_bits_to_f32, f32_to_bf16_bits
+    q0 = bf16_bits_to_f32(inp["q"])[:, :, :1]                       # one query vector per head
+    inp["q"] = f32_to_bf16_bits(np.broadcast_to(q0, inp["q"].shape).copy())
+    inp["k_tree"] = f32_to_bf16_bits(np.broadcast_to(0.7 * q0, inp["q"].shape).copy())
+    ad = H.AttnDevice(inp)
+    m = binding.build_mask(br)
+    v = binding.slice_mask(m, 4)
+    got = H.run_attention(binding, v, ad)
+    M = oracle.build_mask(br)
+    want = oracle.tree_attention(inp, M, v.n_nodes)
+    H.assert_close(got, want, "bf16", "boosted tree keys")
+    # the same inputs under a wrong mask (plain causal over node ids) differ by far more than the tolerance
+    wrong = oracle.tree_attention(inp, np.tril(np.ones_like(M)), v.n_nodes)
+    assert np.max(np.abs(wrong - want)) > 0.2
+    # ... and so does a single flipped bit
+    M1 = M.copy()
+    M1[5, 1] ^= 1
+    assert np.max(np.abs(oracle.tree_attention(inp, M1, v.n_nodes) - want)) > 0.1
+
+
+def test_maximum_node_count_and_limits(binding, oracle, H):
+    br = (8, 3, 4)                                     # 8 + 24 + 96 = 128 nodes: the kernel's maximum
+    w = scaled(WORKLOADS["cfg2"], B=1, H=3, branching=br, cfg_id=53)
+    inp = attention_inputs(w, seed=3, lens=(300,))
+    ad = H.AttnDevice(inp)
+    m = binding.build_mask(br)
+    v = binding.slice_mask(m, 3)
+    assert v.n_nodes == 128
+    got = H.run_attention(binding, v, ad)
+    H.assert_close(got, oracle.tree_attention(inp, oracle.build_mask(br), 128), "bf16", "128 nodes")
+    big = binding.build_mask((8, 3, 4, 2))             # 320 nodes: mask is fine, attention refuses
+    vb = binding.slice_mask(big, 4)
+    with pytest.raises(binding.McsdError) as e:
+        H.run_attention(binding, vb, ad)
+    assert e.value.status in (binding.MCSD_EUNSUPPORTED, binding.MCSD_EINVAL)
+
+
+def test_workspace_too_small_is_an_error_not_a_fault(binding, H):
+    w = WORKLOADS["cfg2"]
+    inp = attention_inputs(w, seed=0)
+    ad = H.AttnDevice(inp)
+    m = binding.build_mask(w.branching)
+    v = binding.slice_mask(m, 4)
+    need = binding.tree_attention_workspace(ad.B, ad.H, ad.d, v.n_nodes, ad.max_prefix)
+    assert need > 0
+    ws = torch.empty(need - 256, dtype=torch.uint8, device="cuda")
+    with pytest.raises(binding.McsdError) as e:
+        binding.tree_attention(v, 1, ad.B, ad.H, ad.d, ad.q, ad.kt, ad.vt, ad.node_stride, ad.kp, ad.vp, ad.base,
+                               ad.lens, ad.head_stride, ad.max_prefix, ad.scale, ad.out, ws)
+    assert e.value.status == binding.MCSD_EWORKSPACE
+
+
+# ------------------------------------------------------------------------------------------------
+# verification: bit-exact paths, lengths and tokens
+# ------------------------------------------------------------------------------------------------
+def _check_verify(binding, oracle, H, w, mode, gamma=None, seed=0, n_new=None):
+    g = w.gamma_max if gamma is None else gamma
+    vi = verify_inputs(w, seed=seed, gamma=g, mode=mode, n_new=n_new)
+    m = binding.build_mask(w.branching)
+    v = binding.slice_mask(m, g)
+    path, alen, new = H.run_verify(binding, v, mode, vi)
+    want_path, want_len, want_new = oracle.verify_tree(mode, w.branching[:g], vi["tokens"], vi["p_target"],
+                                                       vi["q_draft"], vi["u_accept"], vi["u_sample"])
+    assert np.array_equal(alen, want_len), (alen, want_len)
+    assert np.array_equal(path, want_path)
+    assert np.array_equal(new, want_new), (new, want_new)
+    return alen
+
+
+@pytest.mark.parametrize("mode", [DRAFT_INIT, TARGET_INIT])
+@pytest.mark.parametrize("name", ["cfg1", "cfg2", "cfg4", "cfg5"])
+def test_verify_configs_bit_exact(binding, oracle, H, name, mode):
+    w = WORKLOADS[name]
+    alen = _check_verify(binding, oracle, H, w, mode)
+    assert alen.min() >= (1 if mode == TARGET_INIT else 0)
+
+
+@pytest.mark.parametrize("mode", [DRAFT_INIT, TARGET_INIT])
+def test_verify_cfg3_every_gamma(binding, oracle, H, mode):
+    w = WORKLOADS["cfg3"]
+    for g in range(1, 9):
+        _check_verify(binding, oracle, H, w, mode, gamma=g)
+
+
+@pytest.mark.parametrize("mode", [DRAFT_INIT, TARGET_INIT])
+def test_verify_cfg5_gamma4_slice(binding, oracle, H, mode):
+    _check_verify(binding, oracle, H, WORKLOADS["cfg5"], mode, gamma=4)
+
+
+@pytest.mark.parametrize("V", [1, 2, 3, 5, 255, 256, 257, 1000, 1023, 4099, 50001])
+@pytest.mark.parametrize("mode", [DRAFT_INIT, TARGET_INIT])
+def test_verify_vocabulary_sizes(binding, oracle, H, V, mode):
+    """Sizes around the 256-element blocks, not multiples of 4 (unaligned rows), and a large odd vocabulary."""
+    w = scaled(WORKLOADS["cfg1"], B=6, V=V, branching=(3, 2, 2), cfg_id=60, target_sigma=1.5)
+    _check_verify(binding, oracle, H, w, mode, seed=V, n_new=3)
+
+
+def test_verify_many_sequences_and_deep_rejection_chains(binding, oracle, H):
+    """Independent draft and target (low acceptance) with wide levels: long chains of residual updates."""
+    w = scaled(WORKLOADS["cfg1"], B=64, V=777, branching=(8, 6), cfg_id=61, target_sigma=3.0)
+    alen = _check_verify(binding, oracle, H, w, DRAFT_INIT, n_new=2)
+    assert (alen == 0).any() and (alen > 0).any()
+    _check_verify(binding, oracle, H, w, TARGET_INIT, n_new=5)
+
+
+def test_verify_special_rows(binding, oracle, H):
+    """p == q (everything accepted, bonus from the leaf's row), disjoint supports (everything rejected,
+    residual == p), vanished residual (fallback to the target row), all on the device."""
+    rng = np.random.default_rng(8)
+    br, V, B = (2, 2), 64, 5
+    N, Nin = 6, 2
+    m = binding.build_mask(br)
+    v = binding.slice_mask(m, 2)
+    p = rng.random((B, 1 + N, V)).astype(np.float32)
+    p /= p.sum(-1, keepdims=True)
+    p = p.astype(np.float32)
+    ua = rng.random((B, N), dtype=np.float32)
+    us = rng.random((B, 2), dtype=np.float32)
+    tokens = rng.integers(0, V, size=(B, N)).astype(np.int32)
+    cases = {"p == q": (p, p[:, :1 + Nin].copy())}
+    pe, qo = np.zeros_like(p), np.zeros((B, 1 + Nin, V), dtype=np.float32)
+    pe[:, :, 0::2] = 1 / 32
+    qo[:, :, 1::2] = 1 / 32
+    cases["disjoint"] = (pe, qo)
+    pz = p.copy()
+    qz = p[:, :1 + Nin].copy()
+    pz[:, :, 0] = 0.0                      # token 0 has p = 0 < q: rejected, then residual is identically zero
+    cases["vanished"] = (pz, qz)
+    for name, (pp, qq) in cases.items():
+        tk = tokens.copy()
+        if name == "disjoint":
+            tk = (tk | 1).astype(np.int32)
+        if name == "vanished":
+            tk[:] = 0
+        vi = dict(p_target=pp, q_draft=qq, tokens=tk, u_accept=ua, u_sample=us)
+        for mode in (DRAFT_INIT, TARGET_INIT):
+            got = H.run_verify(binding, v, mode, vi)
+            want = oracle.verify_tree(mode, br, tk, pp, qq, ua, us)
+            for a, b_ in zip(got, want):
+                assert np.array_equal(a, b_), (name, mode, a, b_)
+
+
+def test_verify_without_new_tokens(binding, oracle, H):
+    w = scaled(WORKLOADS["cfg1"], B=3, cfg_id=62)
+    _check_verify(binding, oracle, H, w, DRAFT_INIT, n_new=0)

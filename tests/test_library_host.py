@@ -1,0 +1,116 @@
+"""No-GPU checks of libmcsd.so: it loads, exports every symbol the header declares, its host-side mask
+logic matches the oracle bit for bit, and argument validation answers with status codes."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+TREES = [(2, 2, 2), (4, 2, 2, 1), (3, 2, 2, 1, 1, 1, 1, 1), (4, 2, 2, 2), (8, 2, 2, 1, 1), (2, 4, 3, 1, 1),
+         (3, 1, 1), (1, 1, 1), (1,), (16, 1, 1, 1, 1), (8, 3, 4), (5, 5, 5)]
+
+
+@pytest.fixture(scope="module")
+def binding():
+    from paper_2409_10644_amd import binding as b
+    return b
+
+
+def test_every_declared_symbol_is_exported(binding):
+    header = open(os.path.join(ROOT, "include", "mcsd.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = sorted(set(re.findall(r"\b(mcsd_[a-z_]+)\s*\(", header)))
+    assert declared == sorted(binding.EXPORTS)
+    lib = C.CDLL(binding.LIB_PATH)
+    for name in declared:
+        assert getattr(lib, name) is not None
+
+
+@pytest.mark.parametrize("br", TREES)
+def test_mask_and_every_slice_match_the_oracle(binding, oracle, br):
+    m = binding.build_mask(br)
+    full = oracle.build_mask(br)
+    parent, level = oracle.tree_tables(br)
+    sizes = oracle.level_sizes(br)
+    for g in range(1, len(br) + 1):
+        v = binding.slice_mask(m, g)
+        n = int(sizes[:g].sum())
+        assert (v.gamma, v.n_nodes, v.gamma_max, v.n_nodes_max) == (g, n, len(br), full.shape[0])
+        assert v.words_per_row == (full.shape[0] + 63) // 64
+        got = binding.mask_bits_host(v)
+        assert np.array_equal(got, oracle.slice_mask(full, n))          # the slice of the big mask ...
+        assert np.array_equal(got, oracle.build_mask(br[:g]))           # ... equals a freshly built mask
+        assert [v.parent_host[i] for i in range(n)] == parent[:n].tolist()
+        assert [v.level_host[i] for i in range(n)] == level[:n].tolist()
+        assert [v.level_off_host[l] for l in range(g + 1)] == [0] + np.cumsum(sizes[:g]).tolist()
+        # a slice is a view: same storage as the full mask, nothing rebuilt
+        assert C.addressof(v.bits_host.contents) == C.addressof(binding.slice_mask(m, len(br)).bits_host.contents)
+    binding.free_mask(m)
+
+
+def test_slice_has_no_bits_outside_itself(binding):
+    m = binding.build_mask((3, 2, 2, 1, 1, 1, 1, 1))
+    v = binding.slice_mask(m, 8)
+    W = v.words_per_row
+    words = np.ctypeslib.as_array(v.bits_host, shape=(v.n_nodes_max * W,)).reshape(v.n_nodes_max, W)
+    for g in range(1, 9):
+        n = binding.slice_mask(m, g).n_nodes
+        for i in range(n):
+            row = int(words[i, 0]) | (int(words[i, 1]) << 64)
+            assert row >> n == 0
+
+
+def test_build_and_slice_validation(binding):
+    with pytest.raises(binding.McsdError) as e:
+        binding.build_mask((2, 0, 2))
+    assert e.value.status == binding.MCSD_EINVAL
+    with pytest.raises(binding.McsdError):
+        binding.build_mask(())
+    with pytest.raises(binding.McsdError):
+        binding.build_mask((1,) * 33)
+    with pytest.raises(binding.McsdError) as e:
+        binding.build_mask((64, 64, 2))                 # 64 + 4096 + ... > MCSD_MAX_NODES
+    assert e.value.status == binding.MCSD_EUNSUPPORTED
+    with pytest.raises(binding.McsdError):
+        binding.build_mask((65,))
+    m = binding.build_mask((2, 2))
+    for g in (0, 3, -1):
+        with pytest.raises(binding.McsdError) as e:
+            binding.slice_mask(m, g)
+        assert e.value.status == binding.MCSD_EINVAL
+    assert binding.strerror(0) == "ok" and "workspace" in binding.strerror(binding.MCSD_EWORKSPACE)
+    binding.lib.mcsd_free_mask(None)                    # NULL is allowed
+
+
+def test_device_entry_points_reject_bad_arguments_before_any_launch(binding):
+    """Null tensors, unsupported sizes and host-only views are turned into status codes on the host."""
+    m = binding.build_mask((4, 2, 2, 1))
+    v = binding.slice_mask(m, 4)
+    lib = binding.lib
+    one = C.c_void_p(256)            # never dereferenced: validation fails first
+    args = dict(dtype=1, B=1, H=32, d=128)
+    st = lib.mcsd_tree_attention(C.byref(v), 1, 1, 32, 128, None, one, one, 44, one, one, one, one, 1024 * 128, 1024,
+                                 0.1, one, None, 0, None)
+    assert st == binding.MCSD_EINVAL
+    if v.device < 0:                 # no GPU here: a host-only view must be refused
+        st = lib.mcsd_tree_attention(C.byref(v), 1, 1, 32, 128, one, one, one, 44, one, one, one, one, 1024 * 128,
+                                     1024, 0.1, one, None, 0, None)
+        assert st == binding.MCSD_EINVAL
+    assert lib.mcsd_tree_attention_workspace(1, 32, 96, 44, 1024) == 0           # d not in {64,128}
+    assert lib.mcsd_tree_attention_workspace(1, 32, 128, 129, 1024) == 0         # too many nodes
+    assert lib.mcsd_tree_attention_workspace(1, 32, 128, 44, 1024) > 0
+    st = lib.mcsd_verify_tree(C.byref(v), 0, 1, 32000, None, one, one, 45 * 32000, 29 * 32000, one, one, 1, one, one,
+                              one, None, 0, None)
+    assert st == binding.MCSD_EINVAL
+    st = lib.mcsd_verify_tree(C.byref(v), 0, 1, 300000, one, one, one, 45 * 300000, 29 * 300000, one, one, 1, one,
+                              one, one, None, 0, None)
+    assert st == binding.MCSD_EUNSUPPORTED
+    st = lib.mcsd_verify_tree(C.byref(v), 0, 1, 32000, one, one, one, 44 * 32000, 29 * 32000, one, one, 1, one, one,
+                              one, None, 0, None)
+    assert st == binding.MCSD_EINVAL                                              # p stride shorter than 1+N rows
+    st = lib.mcsd_verify_tree(C.byref(v), 1, 1, 32000, one, one, one, 45 * 32000, 29 * 32000, one, one, 4, one, one,
+                              one, None, 0, None)
+    assert st == binding.MCSD_EWORKSPACE                                          # target-init needs a workspace
