@@ -1,0 +1,291 @@
+#!/usr/bin/env python3
+"""Benchmark of the MCSD verification hot path on one MI355X.
+
+One STEP is one pass of the whole hot path over one batch of seeded synthetic input:
+    mcsd_slice_mask(gamma)  ->  one mcsd_tree_attention call per transformer layer (32 for Llama-2-7B, every
+    layer with its own KV cache and q/k/v)  ->  one mcsd_verify_tree call.
+All inputs are resident in HBM before the timed region.  The headline value is verified tree-tokens/s =
+B * N(gamma) / step time.  The line also carries the roofline of the dominant kernel (the tree-attention
+key sweep), measured with HIP events that bracket that kernel's launches, and the CPU oracle timed on the
+host cores as a reported baseline.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2] [--extra cfg4,cfg5]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published
+N_LAYERS = 32                   # Llama-2-7B
+
+# HBM traffic per launch of the sweep kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (bytes, already
+# scaled by the copy-kernel calibration); filled from the summaries under profiles/.  None = not measured.
+MEASURED_TRAFFIC = {}
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def attention_algorithmic(w, lens, n):
+    """Algorithmic bytes and flops of one mcsd_tree_attention call: prefix K and V read once, tree q/k/v read and
+    the output written once, plus the mask slice; 4*N*(L+N)*d flops per (sequence, head)."""
+    e = 2 if w.dtype == "bf16" else 4
+    by = sum(w.H * e * w.d * (2 * int(L) + 4 * n) for L in lens) + n * ((w.n_nodes() + 63) // 64) * 8
+    fl = sum(w.H * 4 * n * (int(L) + n) * w.d for L in lens)
+    return by, fl
+
+
+class Step:
+    """Device-resident inputs of one step and the calls that make it."""
+
+    def __init__(self, name, n_kv_sets, gamma=None, mode=None, seed=0):
+        import numpy as np
+        import torch
+        from paper_2409_10644_amd import binding
+        from workloads import WORKLOADS, attention_inputs, prefix_lens, verify_inputs
+        sys.path.insert(0, os.path.join(ROOT, "tests"))
+        import gpu_helpers as H
+
+        self.binding, self.H, self.torch, self.np = binding, H, torch, np
+        self.w = w = WORKLOADS[name]
+        self.gamma = w.gamma_max if gamma is None else gamma
+        self.mode = w.mode if mode is None else mode
+        self.lens = prefix_lens(w, seed)
+        self.cap = int(w.prefix_max)
+        t0 = time.time()
+        self.layers_host = [attention_inputs(w, seed=seed, kv_capacity=self.cap, variant=l) for l in range(n_kv_sets)]
+        self.layers = [H.AttnDevice(inp) for inp in self.layers_host]
+        self.vi = verify_inputs(w, seed=seed, gamma=self.gamma, mode=self.mode)
+        log(f"[bench] {name}: {n_kv_sets} KV set(s) generated and uploaded in {time.time() - t0:.1f}s")
+        self.mask = binding.build_mask(w.branching)                   # once, at gamma_max
+        self.view = binding.slice_mask(self.mask, self.gamma)
+        self.n = self.view.n_nodes
+        ws_bytes = binding.tree_attention_workspace(w.B, w.H, w.d, self.n, self.cap)
+        self.ws = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device="cuda")
+        vi = self.vi
+        self.p, self.q = H.dev(vi["p_target"]), H.dev(vi["q_draft"])
+        self.tokens, self.ua, self.us = H.dev(vi["tokens"]), H.dev(vi["u_accept"]), H.dev(vi["u_sample"])
+        self.n_new = vi["n_new"]
+        self.path = torch.zeros((w.B, self.gamma), dtype=torch.int32, device="cuda")
+        self.alen = torch.zeros((w.B,), dtype=torch.int32, device="cuda")
+        self.new = torch.zeros((w.B, max(self.n_new, 1)), dtype=torch.int32, device="cuda")
+        vws = binding.verify_tree_workspace(self.view, self.mode, w.B, self.n_new)
+        self.vws = torch.empty(max(vws, 256), dtype=torch.uint8, device="cuda") if vws else None
+        self.alg_bytes, self.alg_flops = attention_algorithmic(w, self.lens, self.n)
+
+    def attention(self, layer):
+        ad, w, b = self.layers[layer % len(self.layers)], self.w, self.binding
+        b.tree_attention(self.view, ad.code, w.B, w.H, w.d, ad.q, ad.kt, ad.vt, ad.node_stride, ad.kp, ad.vp, ad.base,
+                         ad.lens, ad.head_stride, self.cap, ad.scale, ad.out, self.ws)
+
+    def verify(self):
+        w, b, vi = self.w, self.binding, self.vi
+        b.verify_tree(self.view, self.mode, w.B, w.V, self.tokens, self.p, self.q, vi["p_target"].shape[1] * w.V,
+                      vi["q_draft"].shape[1] * w.V, self.ua, self.us, self.n_new, self.path, self.alen, self.new,
+                      self.vws)
+
+    def step(self):
+        self.view = self.binding.slice_mask(self.mask, self.gamma)    # O(1): the per-step slice
+        for l in range(N_LAYERS):
+            self.attention(l)
+        self.verify()
+
+    def check_against_oracle(self, rows=24):
+        """'Verified': the outputs of this very configuration match the oracle (sampled attention rows of layer
+        0, full verification result)."""
+        import oracle
+        np_, torch = self.np, self.torch
+        w = self.w
+        self.attention(0)
+        self.verify()
+        torch.cuda.synchronize()
+        M = oracle.build_mask(w.branching)
+        got = self.layers[0].out[:, :, :self.n].float().cpu().numpy().astype(np_.float64)
+        rng = np_.random.default_rng(1)
+        for _ in range(rows):
+            b, h, i = int(rng.integers(w.B)), int(rng.integers(w.H)), int(rng.integers(self.n))
+            want = oracle.tree_attention_row(self.layers_host[0], M, self.n, b, h, i)
+            self.H.assert_close(got[b, h, i], want, w.dtype, f"bench {w.name} row {(b, h, i)}")
+        vi = self.vi
+        want = oracle.verify_tree(self.mode, w.branching[:self.gamma], vi["tokens"], vi["p_target"], vi["q_draft"],
+                                  vi["u_accept"], vi["u_sample"])
+        got_v = (self.path.cpu().numpy(), self.alen.cpu().numpy(), self.new.cpu().numpy()[:, :self.n_new])
+        for a, b_ in zip(got_v, want):
+            assert np_.array_equal(a, b_), "verification differs from the oracle"
+        return float(want[1].mean())
+
+
+def time_kernel(st, hip, kernel_id, launch, reps):
+    """Average device execution time (ms) of one library kernel over `reps` launches, from event pairs that the
+    library places around that kernel's launch."""
+    b, torch = st.binding, st.torch
+    pairs = [(hip.event(), hip.event()) for _ in range(reps)]
+    for i, (e0, e1) in enumerate(pairs):
+        b.profile_next(kernel_id, e0, e1)
+        launch(i)
+    torch.cuda.synchronize()
+    ms = [hip.elapsed_ms(e0, e1) for e0, e1 in pairs]
+    for e0, e1 in pairs:
+        hip.destroy(e0)
+        hip.destroy(e1)
+    ms.sort()
+    return sum(ms) / len(ms), ms[len(ms) // 2], ms[len(ms) // 10], ms[(len(ms) * 9) // 10]
+
+
+def roofline_of(st, hip, reps):
+    b = st.binding
+    avg, med, p10, p90 = time_kernel(st, hip, b.KERNEL_ATTN_SWEEP, lambda i: st.attention(i), reps)
+    ach = st.alg_bytes / (avg * 1e-3) / 1e9
+    traffic = MEASURED_TRAFFIC.get(st.w.name)
+    return {"bound": "hbm", "kernel": "tree_attn_bf16_kernel" if st.w.dtype == "bf16" else "tree_attn_f32_kernel",
+            "achieved": round(ach, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBPS, 4),
+            "traffic": traffic, "algorithmic_bytes_per_launch": int(st.alg_bytes),
+            "flops_per_launch": int(st.alg_flops), "avg_launch_us": round(avg * 1e3, 2),
+            "median_launch_us": round(med * 1e3, 2), "p10_us": round(p10 * 1e3, 2), "p90_us": round(p90 * 1e3, 2),
+            "mfma_tflops": round(st.alg_flops / (avg * 1e-3) / 1e12, 1), "launches_timed": reps}
+
+
+def cpu_baseline(st, budget_s=20.0):
+    """The oracle as it stands on the host cores: attention of as many layers as fit the time budget (scaled to
+    32 layers) plus one verification; tree-tokens/s of a whole step."""
+    import oracle
+    w = st.w
+    M = oracle.build_mask(w.branching)
+    inp = st.layers_host[0]
+    B, Hh = w.B, w.H
+    # bounded sample: whole layers if one fits in the budget, else a subset of (b,h) rows of one layer
+    t0 = time.time()
+    probe_rows = 8
+    for k in range(probe_rows):
+        oracle.tree_attention_row(inp, M, st.n, k % B, k % Hh, k % st.n)
+    t_row = (time.time() - t0) / probe_rows
+    threads = oracle.threads()
+    est_layer = t_row * B * Hh * st.n / max(1, min(threads, B * Hh))
+    vi = st.vi
+    t0 = time.time()
+    oracle.verify_tree(st.mode, w.branching[:st.gamma], vi["tokens"], vi["p_target"], vi["q_draft"], vi["u_accept"],
+                       vi["u_sample"])
+    t_verify = time.time() - t0
+    if est_layer <= budget_s:
+        n_layers = max(1, min(N_LAYERS, int(budget_s / max(est_layer, 1e-3))))
+        t0 = time.time()
+        for l in range(n_layers):
+            oracle.tree_attention(st.layers_host[l % len(st.layers_host)], M, st.n)
+        t_layer = (time.time() - t0) / n_layers
+        sample = f"{n_layers} of {N_LAYERS} attention layers in full + 1 verification, attention time scaled to {N_LAYERS} layers"
+    else:
+        rows = max(threads, int(budget_s / t_row) // threads * threads)
+        import concurrent.futures as cf
+        picks = [(r % B, (r // B) % Hh, (r * 7) % st.n) for r in range(rows)]
+        t0 = time.time()
+        with cf.ThreadPoolExecutor(threads) as ex:       # ctypes releases the GIL: rows run on all cores
+            list(ex.map(lambda a: oracle.tree_attention_row(inp, M, st.n, *a), picks))
+        t_layer = (time.time() - t0) / rows * (B * Hh * st.n)
+        sample = (f"{rows} of {B * Hh * st.n} output rows of one attention layer + 1 verification, scaled to "
+                  f"{N_LAYERS} full layers")
+    t_step = N_LAYERS * t_layer + t_verify
+    return {"value": round(w.B * st.n / t_step, 3), "unit": "tree-tokens/s", "cores": threads, "kind": "oracle",
+            "sample": sample, "attention_layer_s": round(t_layer, 4), "verify_s": round(t_verify, 4)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="cfg2")
+    ap.add_argument("--extra", default="cfg4,cfg5", help="other workloads whose attention roofline is reported too")
+    ap.add_argument("--kernel-reps", type=int, default=64)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build measures one GPU only (the path shards by sequence and head without any "
+                 "exchange; see DESIGN.md); run with --gpus 1")
+    import torch
+    assert torch.cuda.is_available(), "bench.py needs the MI355X"
+    torch.cuda.set_device(0)
+    from paper_2409_10644_amd import binding
+    hip = binding.HipRuntime()
+
+    w_name = args.workload
+    from workloads import WORKLOADS
+    w = WORKLOADS[w_name]
+    kv_bytes = w.B * w.H * w.prefix_max * w.d * (2 if w.dtype == "bf16" else 4) * 2
+    n_sets = N_LAYERS if kv_bytes * N_LAYERS <= (8 << 30) else max(1, min(N_LAYERS, (2 << 30) // kv_bytes))
+    st = Step(w_name, n_sets)
+    alpha = st.check_against_oracle()
+    log(f"[bench] {w_name}: outputs verified against the oracle (mean accepted length {alpha:.2f})")
+
+    for _ in range(args.warmup):
+        st.step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        st.step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt / args.steps * 1e3
+    value = w.B * st.n / (ms_per_step * 1e-3)
+
+    roof = roofline_of(st, hip, args.kernel_reps)
+    m_avg = time_kernel(st, hip, binding.KERNEL_ATTN_MERGE, lambda i: st.attention(i), args.kernel_reps)[0] \
+        if st.ws.numel() > 256 else 0.0
+    v_avg = time_kernel(st, hip, binding.KERNEL_VERIFY_WALK, lambda i: st.verify(), args.kernel_reps)[0]
+    out = {
+        "metric": "verified tree-tokens/s, whole verification step (32 tree-attention layers + acceptance)",
+        "value": round(value, 1), "unit": "tree-tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": f"{w_name}: B{w.B} H{w.H} d{w.d} {w.dtype} prefix {w.prefix_min}"
+                               f"{'' if w.prefix_min == w.prefix_max else '-' + str(w.prefix_max)} tree {w.branching} "
+                               f"N={st.n} gamma={st.gamma} V={w.V} mode={'target' if st.mode else 'draft'}-init",
+                   "layers_per_step": N_LAYERS, "kv_sets": n_sets, "verified_vs_oracle": True,
+                   "mean_accept_len": round(alpha, 3)},
+        "roofline": roof,
+        "kernels_us": {"attn_sweep": roof["avg_launch_us"], "attn_merge": round(m_avg * 1e3, 2),
+                       "verify_walk": round(v_avg * 1e3, 2)},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(st)
+    del st
+    torch.cuda.empty_cache()
+
+    extra = {}
+    for name in [x for x in args.extra.split(",") if x and x != w_name]:
+        try:
+            es = Step(name, 1)
+            es.check_against_oracle(rows=8)
+            for i in range(3):
+                es.attention(i)
+            r = roofline_of(es, hip, max(8, args.kernel_reps // 4))
+            t0e = None
+            torch.cuda.synchronize()
+            t0e = time.perf_counter()
+            for i in range(10):
+                es.attention(i)
+            torch.cuda.synchronize()
+            call_us = (time.perf_counter() - t0e) / 10 * 1e6
+            r["attention_call_us"] = round(call_us, 1)
+            r["attn_tree_tokens_per_s"] = round(es.w.B * es.n / (call_us * 1e-6), 1)
+            r["workload"] = f"{name}: B{es.w.B} N={es.n} prefix {es.w.prefix_min}-{es.w.prefix_max}"
+            extra[name] = r
+            del es
+            torch.cuda.empty_cache()
+        except Exception as ex:      # an extra workload must not lose the headline line
+            extra[name] = {"error": repr(ex)}
+    if extra:
+        out["other_workloads"] = extra
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

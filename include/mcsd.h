@@ -153,6 +153,15 @@ int mcsd_verify_tree(const mcsd_mask_view_t *mask, mcsd_mode_t mode, int32_t B, 
                      const float *u_sample, int32_t n_new, int32_t *out_path, int32_t *out_accept_len,
                      int32_t *out_new_tokens, void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/* ---------------------------------------------------------------------------------------------------
+ * Measurement aid (not part of the method).  Arms a one-shot pair of HIP events (hipEvent_t, created by the
+ * caller with timing enabled) for one of the library's kernels: the next launch of that kernel by the calling
+ * process is bracketed by them, so hipEventElapsedTime(start, stop) is that kernel's own execution time on
+ * the device.  The arming is consumed by that launch.  Passing NULL events disarms.  Not thread-safe.
+ * ------------------------------------------------------------------------------------------------- */
+typedef enum { MCSD_KERNEL_ATTN_SWEEP = 0, MCSD_KERNEL_ATTN_MERGE = 1, MCSD_KERNEL_VERIFY_WALK = 2 } mcsd_kernel_t;
+int mcsd_profile_next(mcsd_kernel_t kernel, void *start_event, void *stop_event);
+
 #ifdef __cplusplus
 }
 #endif

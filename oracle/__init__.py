@@ -56,6 +56,8 @@ def _load():
         L.mcsd_oracle_tree_sample.argtypes = [vp, i64, C.c_float]
         L.mcsd_oracle_improvement_factor.restype = f64
         L.mcsd_oracle_improvement_factor.argtypes = [f64, f64, f64]
+        L.mcsd_oracle_threads.restype = i32
+        L.mcsd_oracle_threads.argtypes = []
         _lib = L
     return _lib
 
@@ -194,3 +196,8 @@ def tree_sample(a: np.ndarray, u: float) -> int:
 
 def improvement_factor(alpha: float, gamma: float, c: float) -> float:
     return float(_load().mcsd_oracle_improvement_factor(alpha, gamma, c))
+
+
+def threads() -> int:
+    """Threads the oracle's outer loops use."""
+    return int(_load().mcsd_oracle_threads())

@@ -19,6 +19,9 @@
  * invariants, textbook special cases, brute-force enumeration); nothing is "parity unpinned".
  */
 #include <math.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
 #include <stdint.h>
 #include <stdlib.h>
 #include <string.h>
@@ -402,4 +405,14 @@ int32_t mcsd_oracle_tree_sample(const double *a, int64_t V, float u)
 double mcsd_oracle_improvement_factor(double alpha, double gamma, double c)
 {
     return (1.0 - pow(alpha, gamma + 1.0)) / ((1.0 - alpha) * (c * gamma + 1.0));
+}
+
+/* Threads the (b,h) / per-sequence loops above will use (for reporting next to a timing). */
+int32_t mcsd_oracle_threads(void)
+{
+#ifdef _OPENMP
+    return (int32_t)omp_get_max_threads();
+#else
+    return 1;
+#endif
 }

@@ -16,7 +16,7 @@ MCSD_DRAFT_INIT, MCSD_TARGET_INIT = 0, 1
 
 EXPORTS = ["mcsd_strerror", "mcsd_build_mask", "mcsd_slice_mask", "mcsd_free_mask",
            "mcsd_tree_attention_workspace", "mcsd_tree_attention",
-           "mcsd_verify_tree_workspace", "mcsd_verify_tree"]
+           "mcsd_verify_tree_workspace", "mcsd_verify_tree", "mcsd_profile_next"]
 
 
 class MaskView(C.Structure):
@@ -64,10 +64,14 @@ def _load() -> C.CDLL:
     lib.mcsd_verify_tree.restype = C.c_int
     lib.mcsd_verify_tree.argtypes = [C.POINTER(MaskView), C.c_int, i32, i32, vp, vp, vp, i64, i64, vp, vp, i32,
                                      vp, vp, vp, vp, sz, vp]
+    lib.mcsd_profile_next.restype = C.c_int
+    lib.mcsd_profile_next.argtypes = [C.c_int, vp, vp]
     return lib
 
 
 lib = _load()
+
+KERNEL_ATTN_SWEEP, KERNEL_ATTN_MERGE, KERNEL_VERIFY_WALK = 0, 1, 2
 
 
 def strerror(status: int) -> str:
@@ -168,3 +172,52 @@ def mask_bits_host(view: MaskView):
     for j in range(n):
         out[:, j] = (words[:n, j >> 6] >> np.uint64(j & 63)) & np.uint64(1)
     return out
+
+
+def profile_next(kernel: int, start_event: Optional[int], stop_event: Optional[int]) -> None:
+    _check(lib.mcsd_profile_next(kernel, start_event, stop_event), "mcsd_profile_next")
+
+
+class HipRuntime:
+    """The process's HIP runtime (the one PyTorch loaded), for raw events and copies in tests and benchmarks."""
+
+    def __init__(self):
+        path = None
+        with open("/proc/self/maps") as f:
+            for line in f:
+                if "libamdhip64" in line:
+                    path = line.split()[-1]
+                    break
+        if path is None:
+            raise RuntimeError("no HIP runtime is loaded in this process")
+        self.lib = C.CDLL(path)
+        self.lib.hipEventCreate.argtypes = [C.POINTER(C.c_void_p)]
+        self.lib.hipEventDestroy.argtypes = [C.c_void_p]
+        self.lib.hipEventRecord.argtypes = [C.c_void_p, C.c_void_p]
+        self.lib.hipEventSynchronize.argtypes = [C.c_void_p]
+        self.lib.hipEventElapsedTime.argtypes = [C.POINTER(C.c_float), C.c_void_p, C.c_void_p]
+        self.lib.hipMemcpy.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_int]
+
+    def _ok(self, err: int, what: str) -> None:
+        if err != 0:
+            raise RuntimeError(f"{what} failed with HIP error {err}")
+
+    def event(self) -> int:
+        ev = C.c_void_p()
+        self._ok(self.lib.hipEventCreate(C.byref(ev)), "hipEventCreate")
+        return ev.value
+
+    def destroy(self, ev: int) -> None:
+        self.lib.hipEventDestroy(ev)
+
+    def record(self, ev: int, stream=None) -> None:
+        self._ok(self.lib.hipEventRecord(ev, _stream(stream)), "hipEventRecord")
+
+    def elapsed_ms(self, start: int, stop: int) -> float:
+        self._ok(self.lib.hipEventSynchronize(stop), "hipEventSynchronize")
+        ms = C.c_float()
+        self._ok(self.lib.hipEventElapsedTime(C.byref(ms), start, stop), "hipEventElapsedTime")
+        return float(ms.value)
+
+    def memcpy_dtoh(self, host_ptr: int, dev_ptr: int, nbytes: int) -> None:
+        self._ok(self.lib.hipMemcpy(host_ptr, dev_ptr, nbytes, 2), "hipMemcpy")

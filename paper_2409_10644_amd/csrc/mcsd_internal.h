@@ -1,6 +1,7 @@
 // Internal declarations shared by the library's translation units (not part of the public ABI).
 #pragma once
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 #include "mcsd.h"
 
@@ -27,3 +28,20 @@ struct McsdTreeDesc {
 };
 
 static inline int mcsd_hip_status(hipError_t e) { return e == hipSuccess ? MCSD_OK : MCSD_EHIP; }
+
+// One-shot profiling events per kernel (see mcsd_profile_next); defined in mask.cpp.
+struct McsdProfileSlot { hipEvent_t start, stop; };
+extern McsdProfileSlot g_mcsd_profile[3];
+
+// Launch `kernel` on `st`; if a profiling pair is armed for `which`, bracket the launch with it and disarm.
+template <typename... Args, typename... Actual>
+inline void mcsd_launch(int which, void (*kernel)(Args...), dim3 grid, dim3 block, hipStream_t st, Actual... args)
+{
+    McsdProfileSlot &slot = g_mcsd_profile[which];
+    if (slot.start && slot.stop) {
+        hipExtLaunchKernelGGL(kernel, grid, block, 0, st, slot.start, slot.stop, 0, args...);
+        slot.start = slot.stop = nullptr;
+    } else {
+        hipLaunchKernelGGL(kernel, grid, block, 0, st, args...);
+    }
+}

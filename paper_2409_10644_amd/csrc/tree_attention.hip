@@ -531,14 +531,14 @@ hipError_t launch_bf16(const AttnParams &p, const AttnPlan &pl, hipStream_t st)
 {
     dim3 grid(pl.S, p.H, p.B), block(256);
     switch (pl.QB) {
-    case 1: hipLaunchKernelGGL((tree_attn_bf16_kernel<D, 1>), grid, block, 0, st, p); break;
-    case 2: hipLaunchKernelGGL((tree_attn_bf16_kernel<D, 2>), grid, block, 0, st, p); break;
-    case 3: hipLaunchKernelGGL((tree_attn_bf16_kernel<D, 3>), grid, block, 0, st, p); break;
-    default: hipLaunchKernelGGL((tree_attn_bf16_kernel<D, 4>), grid, block, 0, st, p); break;
+    case 1: mcsd_launch(MCSD_KERNEL_ATTN_SWEEP, tree_attn_bf16_kernel<D, 1>, grid, block, st, p); break;
+    case 2: mcsd_launch(MCSD_KERNEL_ATTN_SWEEP, tree_attn_bf16_kernel<D, 2>, grid, block, st, p); break;
+    case 3: mcsd_launch(MCSD_KERNEL_ATTN_SWEEP, tree_attn_bf16_kernel<D, 3>, grid, block, st, p); break;
+    default: mcsd_launch(MCSD_KERNEL_ATTN_SWEEP, tree_attn_bf16_kernel<D, 4>, grid, block, st, p); break;
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || pl.SP == 1) return e;
-    hipLaunchKernelGGL((tree_attn_merge_kernel<D, true>), dim3(p.H, p.B), block, 0, st, p, pl.T, pl.KG);
+    mcsd_launch(MCSD_KERNEL_ATTN_MERGE, tree_attn_merge_kernel<D, true>, dim3(p.H, p.B), block, st, p, pl.T, pl.KG);
     return hipGetLastError();
 }
 
@@ -546,10 +546,10 @@ template <int D>
 hipError_t launch_f32(const AttnParams &p, const AttnPlan &pl, hipStream_t st)
 {
     dim3 grid(pl.S, p.H, p.B), block(256);
-    hipLaunchKernelGGL((tree_attn_f32_kernel<D>), grid, block, 0, st, p);
+    mcsd_launch(MCSD_KERNEL_ATTN_SWEEP, tree_attn_f32_kernel<D>, grid, block, st, p);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || pl.SP == 1) return e;
-    hipLaunchKernelGGL((tree_attn_merge_kernel<D, false>), dim3(p.H, p.B), block, 0, st, p, pl.T, pl.KG);
+    mcsd_launch(MCSD_KERNEL_ATTN_MERGE, tree_attn_merge_kernel<D, false>, dim3(p.H, p.B), block, st, p, pl.T, pl.KG);
     return hipGetLastError();
 }
 

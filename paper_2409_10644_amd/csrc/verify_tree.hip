@@ -295,7 +295,7 @@ extern "C" int mcsd_verify_tree(const mcsd_mask_view_t *mask, mcsd_mode_t mode, 
     hipStream_t st = (hipStream_t)hip_stream;
     if (mode == MCSD_DRAFT_INIT) {
         P.cand_path = out_path; P.cand_len = out_accept_len; P.cand_new = out_new_tokens;
-        hipLaunchKernelGGL(verify_walk_kernel, dim3(1, B), dim3(VT), 0, st, P);
+        mcsd_launch(MCSD_KERNEL_VERIFY_WALK, verify_walk_kernel, dim3(1, B), dim3(VT), st, P);
         return mcsd_hip_status(hipGetLastError());
     }
     const size_t need = mcsd_verify_tree_workspace(mask, mode, B, n_new);
@@ -307,7 +307,7 @@ extern "C" int mcsd_verify_tree(const mcsd_mask_view_t *mask, mcsd_mode_t mode, 
     P.cand_len = (int32_t *)w;
     w += align256(sizeof(int32_t) * B * R);
     P.cand_new = (int32_t *)w;
-    hipLaunchKernelGGL(verify_walk_kernel, dim3(P.R, B), dim3(VT), 0, st, P);
+    mcsd_launch(MCSD_KERNEL_VERIFY_WALK, verify_walk_kernel, dim3(P.R, B), dim3(VT), st, P);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return MCSD_EHIP;
     hipLaunchKernelGGL(verify_select_kernel, dim3(B), dim3(64), 0, st, P, out_path, out_accept_len, out_new_tokens);

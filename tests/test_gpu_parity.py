@@ -3,8 +3,6 @@
 Masks, accepted paths, lengths and sampled tokens must match bit for bit; attention within 2e-2 relative /
 1e-2 absolute (bf16 path) or 1e-5 (fp32 path) of the binary64 oracle.
 """
-import ctypes
-
 import numpy as np
 import pytest
 import torch
@@ -48,8 +46,7 @@ def test_device_mask_bits_match_oracle_for_every_gamma(binding, oracle, name):
         n, W = v.n_nodes, v.words_per_row
         host = np.empty(v.n_nodes_max * W, dtype=np.uint64)
         torch.cuda.synchronize()
-        hip = ctypes.CDLL("libamdhip64.so")               # plain device-to-host copy of the library's buffer
-        assert hip.hipMemcpy(ctypes.c_void_p(host.ctypes.data), ctypes.c_void_p(v.bits_dev), host.nbytes, 2) == 0
+        binding.HipRuntime().memcpy_dtoh(host.ctypes.data, v.bits_dev, host.nbytes)   # the library's own buffer
         host = host.reshape(v.n_nodes_max, W)
         got = np.zeros((n, n), dtype=np.uint8)
         for j in range(n):
