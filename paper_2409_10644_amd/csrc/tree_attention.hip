@@ -12,6 +12,7 @@
 //
 // fp32 path: same split / online-softmax structure on the vector ALU (small reference-precision shapes).
 #include <math.h>
+#include <stdlib.h>
 
 #include "mcsd_internal.h"
 
@@ -46,8 +47,8 @@ struct AttnPlan {
     int QB, KG, T, S, SP;
 };
 
-__host__ __device__ inline int key_groups(int QB) { return QB == 1 ? 4 : (QB == 2 ? 2 : 1); }
-__host__ __device__ inline int tile_keys_bf16(int QB) { return QB == 1 ? 128 : 64; }
+__host__ __device__ inline int key_groups(int QB) { return QB <= 2 ? 2 : 1; }
+__host__ __device__ inline int tile_keys_bf16(int) { return 64; }
 
 AttnPlan make_plan(int dtype, int B, int H, int n, int max_prefix)
 {
@@ -68,6 +69,10 @@ AttnPlan make_plan(int dtype, int B, int H, int n, int max_prefix)
     long S = want < cap ? want : cap;
     if (S < 1) S = 1;
     if (S > 64) S = 64;
+    if (const char *ov = getenv("MCSD_ATTN_SPLITS")) {     // tuning override: number of key splits
+        const long v = atol(ov);
+        if (v >= 1 && v <= 64) S = v;
+    }
     pl.S = (int)S;
     pl.SP = pl.S * pl.KG;
     return pl;
@@ -98,8 +103,8 @@ __device__ inline s16x4_t lds_read_tr16(const unsigned char *p)
 // ---------------------------------------------------------------------------------------------------
 template <int D, int QB>
 struct Bf16Cfg {
-    static constexpr int KG = QB == 1 ? 4 : (QB == 2 ? 2 : 1);
-    static constexpr int T = QB == 1 ? 128 : 64;
+    static constexpr int KG = QB <= 2 ? 2 : 1;  // key groups: wavefronts that share a query block split the tile's keys
+    static constexpr int T = 64;                // keys per tile
     static constexpr int KPW = T / 32 / KG;     // 32-key blocks per wavefront per tile
     static constexpr int SK = D * 2 + 16;       // LDS row stride of the K tile (bytes): 4 banks per row
     static constexpr int SV = D * 2 + 64;       // LDS row stride of the V tile (bytes): 16 banks per row
@@ -110,96 +115,107 @@ struct Bf16Cfg {
     static constexpr int CB = D / 32;           // 32-row blocks of O^T
 };
 
-template <int D, int QB, int MODE>   // MODE 0: full prefix tile, 1: prefix tail (key < valid), 2: tree tile
-__device__ inline void attn_tile(const unsigned char *ldsK, const unsigned char *ldsV, const bf16x8_t *qreg,
-                                 f32x16_t *oacc, float &m_run, float &l_run, float c, int kg, int g, int ln,
-                                 int valid, const uint64_t *mrow, int tile_key0)
+// Log2-domain slack of the running reference maximum: the accumulators are rescaled only when a block's maximum
+// exceeds the reference by more than this, so exponentiated scores stay below 2^RESCALE_SLACK.  The result is
+// exact: numerator and denominator always share the same reference.
+constexpr float RESCALE_SLACK = 6.f;
+
+// One block of 32 keys against the wavefront's 32 queries.
+// MODE 0: all keys visible; otherwise bit k of `bits` says whether key k of the block is visible to this lane's query.
+template <int D, int QB, int MODE>
+__device__ inline void attn_block(const unsigned char *ldsK, const unsigned char *ldsV, int kb, const bf16x8_t *qreg,
+                                  f32x16_t *oacc, float &m_ref, float &l_run, float c, int g, int ln, uint32_t bits)
 {
     using C = Bf16Cfg<D, QB>;
-    f32x16_t sacc[C::KPW];
+    // S^T[key][query] = K * Q^T : lane (query = ln, half g) gets keys 8*(r/4) + 4*g + r%4, r = 0..15
+    f32x16_t sacc = {0};
+    const unsigned char *krow = ldsK + (kb * 32 + ln) * C::SK + g * 16;
 #pragma unroll
-    for (int j = 0; j < C::KPW; ++j) {
-        const int kb = kg * C::KPW + j;
-        f32x16_t acc = {0};
-        const unsigned char *krow = ldsK + (kb * 32 + ln) * C::SK + g * 16;
-#pragma unroll
-        for (int ks = 0; ks < C::KS; ++ks) {
-            bf16x8_t a = *(const bf16x8_t *)(krow + ks * 32);
-            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[ks], acc, 0, 0, 0);
-        }
-        sacc[j] = acc;
+    for (int ks = 0; ks < C::KS; ++ks) {
+        bf16x8_t a = *(const bf16x8_t *)(krow + ks * 32);
+        sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[ks], sacc, 0, 0, 0);
     }
     if (MODE != 0) {
 #pragma unroll
-        for (int j = 0; j < C::KPW; ++j) {
-            const int key0 = (kg * C::KPW + j) * 32;
-            uint32_t bits;
-            if (MODE == 1) {
-                const int left = valid - key0;    // keys of this block that exist
-                bits = left >= 32 ? 0xffffffffu : (left <= 0 ? 0u : ((1u << left) - 1u));
-            } else {
-                const int col = tile_key0 + key0;
-                bits = (uint32_t)(((col >> 6) ? mrow[1] : mrow[0]) >> (col & 63));
-            }
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int key = 8 * (r / 4) + 4 * g + (r % 4);
-                if (!((bits >> key) & 1u)) sacc[j][r] = -INFINITY;
-            }
+        for (int r = 0; r < 16; ++r) {
+            const int key = 8 * (r / 4) + 4 * g + (r % 4);
+            if (!((bits >> key) & 1u)) sacc[r] = -INFINITY;
         }
     }
-    float mx = -INFINITY;
+    float mx = fmaxf(fmaxf(sacc[0], sacc[1]), sacc[2]);
 #pragma unroll
-    for (int j = 0; j < C::KPW; ++j)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sacc[j][r]);
+    for (int r = 3; r < 15; r += 2) mx = fmaxf(fmaxf(mx, sacc[r]), sacc[r + 1]);
+    mx = fmaxf(mx, sacc[15]);
     mx = half_swap_max(mx);
-    const float m_new = fmaxf(m_run, mx);
-    const float mc = (m_new == -INFINITY ? 0.f : m_new) * c;
-    const float alpha = fast_exp2(fmaf(m_run, c, -mc));
-    m_run = m_new;
+    // rescale only when the block maximum outgrows the reference by more than the slack (first block: -inf)
+    const bool grow = (mx - m_ref) * c > RESCALE_SLACK;
+    if (__builtin_amdgcn_ballot_w64(grow) != 0) {
+        const float m_new = grow ? mx : m_ref;
+        const float alpha = m_new == m_ref ? 1.f : fast_exp2((m_ref - m_new) * c);   // -inf reference: exp2(-inf) = 0
+        m_ref = m_new;
+        l_run *= alpha;
+#pragma unroll
+        for (int cb = 0; cb < C::CB; ++cb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) oacc[cb][r] *= alpha;
+    }
+    const float mc = (m_ref == -INFINITY ? 0.f : m_ref) * c;
     float psum = 0.f;
-    bf16x8_t pb[C::KPW][2];
+    bf16x8_t pb[2];
 #pragma unroll
-    for (int j = 0; j < C::KPW; ++j)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const float pv = fast_exp2(fmaf(sacc[j][r], c, -mc));
-            psum += pv;
-            pb[j][r / 8][r % 8] = (__bf16)pv;
-        }
-    l_run = l_run * alpha + psum;
-#pragma unroll
-    for (int cb = 0; cb < C::CB; ++cb)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) oacc[cb][r] *= alpha;
-    // O^T[c][query] += V^T[c][key] * P^T[key][query]
+    for (int r = 0; r < 16; ++r) {
+        const float pv = fast_exp2(fmaf(sacc[r], c, -mc));
+        psum += pv;
+        pb[r / 8][r % 8] = (__bf16)pv;
+    }
+    l_run += psum;
+    // O^T[c][query] += V^T[c][key] * P^T[key][query]; V^T operands via the LDS transpose load
     const int vcol = 16 * (ln >> 4) + 4 * (ln & 3);
     const int vkey = 4 * g + ((ln & 15) >> 2);
 #pragma unroll
-    for (int j = 0; j < C::KPW; ++j) {
+    for (int ks2 = 0; ks2 < 2; ++ks2) {
+        const unsigned char *vbase = ldsV + (kb * 32 + ks2 * 16 + vkey) * C::SV + vcol * 2;
 #pragma unroll
-        for (int ks2 = 0; ks2 < 2; ++ks2) {
-            const unsigned char *vbase = ldsV + ((kg * C::KPW + j) * 32 + ks2 * 16 + vkey) * C::SV + vcol * 2;
-#pragma unroll
-            for (int cb = 0; cb < C::CB; ++cb) {
-                s16x4_t lo = lds_read_tr16(vbase + cb * 64);
-                s16x4_t hi = lds_read_tr16(vbase + cb * 64 + 8 * C::SV);
-                s16x8_t both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-                bf16x8_t a = __builtin_bit_cast(bf16x8_t, both);
-                oacc[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb[j][ks2], oacc[cb], 0, 0, 0);
-            }
+        for (int cb = 0; cb < C::CB; ++cb) {
+            s16x4_t lo = lds_read_tr16(vbase + cb * 64);
+            s16x4_t hi = lds_read_tr16(vbase + cb * 64 + 8 * C::SV);
+            s16x8_t both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+            bf16x8_t a = __builtin_bit_cast(bf16x8_t, both);
+            oacc[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb[ks2], oacc[cb], 0, 0, 0);
         }
     }
 }
 
-template <int D, int QB>
-__global__ __launch_bounds__(256) void tree_attn_bf16_kernel(const AttnParams p)
+// All key blocks of one tile that belong to this wavefront's key group.
+// MODE 0: full prefix tile, 1: prefix tail (keys < valid exist), 2: tree tile (visibility from the mask row).
+template <int D, int QB, int MODE>
+__device__ inline void attn_tile(const unsigned char *ldsK, const unsigned char *ldsV, const bf16x8_t *qreg,
+                                 f32x16_t *oacc, float &m_ref, float &l_run, float c, int kg, int g, int ln,
+                                 int valid, const uint64_t *mrow, int tile_key0)
 {
     using C = Bf16Cfg<D, QB>;
-    __shared__ __attribute__((aligned(16))) unsigned char lds[C::T * C::SK + C::T * C::SV];
-    unsigned char *ldsK = lds;
-    unsigned char *ldsV = lds + C::T * C::SK;
+#pragma unroll
+    for (int j = 0; j < C::KPW; ++j) {
+        const int kb = kg * C::KPW + j;
+        uint32_t bits = 0xffffffffu;
+        if (MODE == 1) {
+            const int left = valid - kb * 32;     // keys of this block that exist
+            bits = left >= 32 ? 0xffffffffu : (left <= 0 ? 0u : ((1u << left) - 1u));
+        } else if (MODE == 2) {
+            const int col = tile_key0 + kb * 32;
+            bits = (uint32_t)(((col >> 6) ? mrow[1] : mrow[0]) >> (col & 63));
+        }
+        attn_block<D, QB, MODE>(ldsK, ldsV, kb, qreg, oacc, m_ref, l_run, c, g, ln, bits);
+    }
+}
+
+template <int D, int QB>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2)))
+void tree_attn_bf16_kernel(const AttnParams p)
+{
+    using C = Bf16Cfg<D, QB>;
+    constexpr int TILE_BYTES = C::T * C::SK + C::T * C::SV;
+    __shared__ __attribute__((aligned(16))) unsigned char lds[2 * TILE_BYTES];     // two tiles: compute one, fill one
 
     const int s = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -214,8 +230,9 @@ __global__ __launch_bounds__(256) void tree_attn_bf16_kernel(const AttnParams p)
     const int t0 = min(s * tps, tiles_b), t1 = min(t0 + tps, tiles_b);
     const int n_tree_tiles = s == 0 ? (p.n + C::T - 1) / C::T : 0;
     const int n_pre = t1 - t0;
-    const int n_iter = n_pre + n_tree_tiles;
-    if (n_iter == 0) return;
+    if (n_pre + n_tree_tiles == 0) return;
+    // leading tiles of this split that are full (only the sequence's last tile can be ragged)
+    const int n_hot = (n_pre > 0 && t1 * C::T > L) ? n_pre - 1 : n_pre;
 
     const int64_t bh = (int64_t)b * p.H + h;
     const __bf16 *q = (const __bf16 *)p.q + bh * p.node_stride * D;
@@ -244,25 +261,56 @@ __global__ __launch_bounds__(256) void tree_attn_bf16_kernel(const AttnParams p)
     f32x16_t oacc[C::CB];
 #pragma unroll
     for (int cb = 0; cb < C::CB; ++cb) oacc[cb] = (f32x16_t){0};
-    float m_run = -INFINITY, l_run = 0.f;
+    float m_ref = -INFINITY, l_run = 0.f;
 
     const int ld_row = tid / C::CPR, ld_chunk = tid % C::CPR;
+    const int ld_off = ld_row * D + ld_chunk * 8;                  // element offset of this thread's first chunk
     uint4 kreg[C::NLD], vreg[C::NLD];
 
-    auto fetch = [&](int it) {
-        const __bf16 *ksrc, *vsrc;
-        int valid;
-        if (it < n_pre) {
-            const int t = t0 + it;
-            ksrc = kp + (int64_t)t * C::T * D;
-            vsrc = vp + (int64_t)t * C::T * D;
-            valid = min(C::T, L - t * C::T);
-        } else {
-            const int tt = it - n_pre;
-            ksrc = kt + (int64_t)tt * C::T * D;
-            vsrc = vt + (int64_t)tt * C::T * D;
-            valid = min(C::T, p.n - tt * C::T);
+    auto stash = [&](int buf) {
+        unsigned char *bk = lds + buf * TILE_BYTES, *bv = bk + C::T * C::SK;
+#pragma unroll
+        for (int i = 0; i < C::NLD; ++i) {
+            const int row = i * C::RPP + ld_row;
+            *(uint4 *)(bk + row * C::SK + ld_chunk * 16) = kreg[i];
+            *(uint4 *)(bv + row * C::SV + ld_chunk * 16) = vreg[i];
         }
+    };
+
+    // ---- full prefix tiles: register prefetch one tile ahead of the LDS fill, LDS double-buffered ----
+    if (n_hot > 0) {
+        const __bf16 *ksrc = kp + (int64_t)t0 * C::T * D + ld_off;
+        const __bf16 *vsrc = vp + (int64_t)t0 * C::T * D + ld_off;
+        auto fetch_full = [&](int it) {
+#pragma unroll
+            for (int i = 0; i < C::NLD; ++i) {
+                kreg[i] = *(const uint4 *)(ksrc + ((int64_t)it * C::T + i * C::RPP) * D);
+                vreg[i] = *(const uint4 *)(vsrc + ((int64_t)it * C::T + i * C::RPP) * D);
+            }
+        };
+        fetch_full(0);
+        stash(0);
+        if (n_hot > 1) fetch_full(1);
+        __syncthreads();
+        for (int it = 0; it < n_hot; ++it) {
+            if (it + 1 < n_hot) stash((it + 1) & 1);          // tile it+1: registers -> the other LDS buffer
+            if (it + 2 < n_hot) fetch_full(it + 2);           // tile it+2: HBM -> registers, lands during the MFMAs
+            if (computes) {
+                const unsigned char *ldsK = lds + (it & 1) * TILE_BYTES;
+                attn_tile<D, QB, 0>(ldsK, ldsK + C::T * C::SK, qreg, oacc, m_ref, l_run, p.c, kg, g, ln, C::T, mrow, 0);
+            }
+            __syncthreads();                                   // tile it fully read, tile it+1 fully written
+        }
+    }
+
+    // ---- ragged last prefix tile and the tree's own tiles: one at a time, rows beyond `valid` zero-filled ----
+    const int n_rest = (n_pre - n_hot) + n_tree_tiles;
+    for (int it = 0; it < n_rest; ++it) {
+        const bool tail = it < n_pre - n_hot;
+        const int tt = tail ? 0 : it - (n_pre - n_hot);
+        const __bf16 *ksrc = tail ? kp + (int64_t)(t1 - 1) * C::T * D : kt + (int64_t)tt * C::T * D;
+        const __bf16 *vsrc = tail ? vp + (int64_t)(t1 - 1) * C::T * D : vt + (int64_t)tt * C::T * D;
+        const int valid = tail ? L - (t1 - 1) * C::T : min(C::T, p.n - tt * C::T);
 #pragma unroll
         for (int i = 0; i < C::NLD; ++i) {
             const int row = i * C::RPP + ld_row;
@@ -273,32 +321,15 @@ __global__ __launch_bounds__(256) void tree_attn_bf16_kernel(const AttnParams p)
                 vreg[i] = *(const uint4 *)(vsrc + (int64_t)row * D + ld_chunk * 8);
             }
         }
-    };
-
-    fetch(0);
-    for (int it = 0; it < n_iter; ++it) {
-        __syncthreads();   // everyone finished reading the previous tile
-#pragma unroll
-        for (int i = 0; i < C::NLD; ++i) {
-            const int row = i * C::RPP + ld_row;
-            *(uint4 *)(ldsK + row * C::SK + ld_chunk * 16) = kreg[i];
-            *(uint4 *)(ldsV + row * C::SV + ld_chunk * 16) = vreg[i];
+        stash(0);
+        __syncthreads();
+        if (computes) {
+            if (tail)
+                attn_tile<D, QB, 1>(lds, lds + C::T * C::SK, qreg, oacc, m_ref, l_run, p.c, kg, g, ln, valid, mrow, 0);
+            else
+                attn_tile<D, QB, 2>(lds, lds + C::T * C::SK, qreg, oacc, m_ref, l_run, p.c, kg, g, ln, 0, mrow, tt * C::T);
         }
         __syncthreads();
-        if (it + 1 < n_iter) fetch(it + 1);
-        if (computes) {
-            if (it < n_pre) {
-                const int t = t0 + it;
-                const int valid = L - t * C::T;
-                if (valid >= C::T)
-                    attn_tile<D, QB, 0>(ldsK, ldsV, qreg, oacc, m_run, l_run, p.c, kg, g, ln, C::T, mrow, 0);
-                else
-                    attn_tile<D, QB, 1>(ldsK, ldsV, qreg, oacc, m_run, l_run, p.c, kg, g, ln, valid, mrow, 0);
-            } else {
-                attn_tile<D, QB, 2>(ldsK, ldsV, qreg, oacc, m_run, l_run, p.c, kg, g, ln, 0, mrow,
-                                    (it - n_pre) * C::T);
-            }
-        }
     }
     if (!computes) return;
 
@@ -330,7 +361,7 @@ __global__ __launch_bounds__(256) void tree_attn_bf16_kernel(const AttnParams p)
                 *(f32x4_t *)(po + cb * 32 + 8 * j + 4 * g) = v;
             }
         if (g == 0) {
-            p.part_m[prow] = m_run;
+            p.part_m[prow] = m_ref;
             p.part_l[prow] = l_tot;
         }
     }
@@ -477,42 +508,41 @@ __global__ __launch_bounds__(256) void tree_attn_f32_kernel(const AttnParams p)
 template <int D, bool OUT_BF16>
 __global__ __launch_bounds__(256) void tree_attn_merge_kernel(const AttnParams p, int T, int KG)
 {
-    const int h = blockIdx.x, b = blockIdx.y;
+    constexpr int TPR = D / 4;            // threads per output row (4 columns each)
+    constexpr int ROWS = 256 / TPR;       // rows per workgroup
+    const int h = blockIdx.y, b = blockIdx.z;
+    const int i = blockIdx.x * ROWS + threadIdx.x / TPR, c4 = (threadIdx.x % TPR) * 4;
+    if (i >= p.n) return;
     const int64_t bh = (int64_t)b * p.H + h;
     int L = p.lens[b];
     L = L < 0 ? 0 : (L > p.max_prefix ? p.max_prefix : L);
     const int tiles_b = (L + T - 1) / T;
     const int tps = (tiles_b + p.S - 1) / p.S;
     // split s ran iff it had prefix tiles, or it is split 0 (which owns the tree tiles)
-    int n_active = 1;
-    for (int s = 1; s < p.S; ++s)
-        if (s * tps < tiles_b) n_active = s + 1;
-    const int sp_active = n_active * KG;
-    for (int idx = threadIdx.x; idx < p.n * (D / 4); idx += 256) {
-        const int i = idx / (D / 4), c4 = (idx % (D / 4)) * 4;
-        float M = -INFINITY;
-        for (int sp = 0; sp < sp_active; ++sp) M = fmaxf(M, p.part_m[(bh * p.SP + sp) * p.n + i]);
-        float den = 0.f;
-        f32x4_t num = {0.f, 0.f, 0.f, 0.f};
-        for (int sp = 0; sp < sp_active; ++sp) {
-            const int64_t prow = (bh * p.SP + sp) * p.n + i;
-            const float w = exp2f((p.part_m[prow] - M) * p.c);
-            if (w > 0.f) {
-                den = fmaf(w, p.part_l[prow], den);
-                const f32x4_t o = *(const f32x4_t *)(p.part_o + prow * D + c4);
-                num += w * o;
-            }
-        }
-        const f32x4_t r = num / den;
-        const int64_t off = (bh * p.node_stride + i) * D + c4;
-        if (OUT_BF16) {
-            bf16x4_t v;
+    const int n_active = tps > 0 ? min(p.S, (tiles_b + tps - 1) / tps) : 1;
+    const int sp_active = max(n_active, 1) * KG;
+    const int64_t row0 = bh * p.SP * p.n + i;          // partial sp of this row is at row0 + sp * n
+    float M = -INFINITY;
+    for (int sp = 0; sp < sp_active; ++sp) M = fmaxf(M, p.part_m[row0 + (int64_t)sp * p.n]);
+    float den = 0.f;
+    f32x4_t num = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll 4
+    for (int sp = 0; sp < sp_active; ++sp) {
+        const int64_t prow = row0 + (int64_t)sp * p.n;
+        const float w = exp2f((p.part_m[prow] - M) * p.c);     // exp2(-inf) = 0 for partials that saw no key
+        const f32x4_t o = *(const f32x4_t *)(p.part_o + prow * D + c4);
+        den = fmaf(w, p.part_l[prow], den);
+        num += w * o;
+    }
+    const f32x4_t r = num / den;
+    const int64_t off = (bh * p.node_stride + i) * D + c4;
+    if (OUT_BF16) {
+        bf16x4_t v;
 #pragma unroll
-            for (int e = 0; e < 4; ++e) v[e] = (__bf16)r[e];
-            *(bf16x4_t *)((__bf16 *)p.out + off) = v;
-        } else {
-            *(f32x4_t *)((float *)p.out + off) = r;
-        }
+        for (int e = 0; e < 4; ++e) v[e] = (__bf16)r[e];
+        *(bf16x4_t *)((__bf16 *)p.out + off) = v;
+    } else {
+        *(f32x4_t *)((float *)p.out + off) = r;
     }
 }
 
@@ -538,7 +568,7 @@ hipError_t launch_bf16(const AttnParams &p, const AttnPlan &pl, hipStream_t st)
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || pl.SP == 1) return e;
-    mcsd_launch(MCSD_KERNEL_ATTN_MERGE, tree_attn_merge_kernel<D, true>, dim3(p.H, p.B), block, st, p, pl.T, pl.KG);
+    mcsd_launch(MCSD_KERNEL_ATTN_MERGE, tree_attn_merge_kernel<D, true>, dim3((p.n + 1024 / D - 1) / (1024 / D), p.H, p.B), block, st, p, pl.T, pl.KG);
     return hipGetLastError();
 }
 
@@ -549,7 +579,7 @@ hipError_t launch_f32(const AttnParams &p, const AttnPlan &pl, hipStream_t st)
     mcsd_launch(MCSD_KERNEL_ATTN_SWEEP, tree_attn_f32_kernel<D>, grid, block, st, p);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || pl.SP == 1) return e;
-    mcsd_launch(MCSD_KERNEL_ATTN_MERGE, tree_attn_merge_kernel<D, false>, dim3(p.H, p.B), block, st, p, pl.T, pl.KG);
+    mcsd_launch(MCSD_KERNEL_ATTN_MERGE, tree_attn_merge_kernel<D, false>, dim3((p.n + 1024 / D - 1) / (1024 / D), p.H, p.B), block, st, p, pl.T, pl.KG);
     return hipGetLastError();
 }
 
