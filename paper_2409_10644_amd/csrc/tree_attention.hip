@@ -1,18 +1,25 @@
 // Tree attention for gfx950 (Sec. 2.2 of arXiv 2409.10644): every node of the candidate tree attends
 // to the prefix KV cache and to its own ancestors under the topology-aware mask.
 //
-// bf16 path.  One workgroup (4 wavefronts) owns one (sequence, head, key split).  The tree's queries are
-// cut into blocks of 32 rows; a wavefront keeps one block of Q in registers for the whole sweep and the
-// workgroup streams K/V tiles through LDS, so every K/V byte leaves HBM once and is used by all queries.
+// bf16 path.  One workgroup of 8 wavefronts per compute unit owns one (sequence, head, key split).  The tree's
+// queries are cut into blocks of 32 rows; a wavefront keeps one block of Q in registers for the whole sweep.  K/V
+// tiles stream from HBM straight into a ring of LDS stages (global_load_lds, 16 bytes per lane, no registers
+// in between), several tiles ahead of the one being computed, so every K/V byte leaves HBM once and is used by
+// all queries.  The LDS image of a tile is XOR-swizzled at 16-byte granularity, which makes both read patterns
+// below bank-conflict free without padding (direct-to-LDS loads can only write 1 KiB contiguous per instruction).
 // Scores are computed transposed, S^T = K * Q^T, with v_mfma_f32_32x32x16_bf16: the accumulator then holds,
 // per lane, 16 keys of ONE query, so the online-softmax reductions are in-lane plus one half-wave swap,
 // and the exponentiated scores are already in the register layout of the B operand of O^T += V^T * P^T.
-// V^T operands are read from the row-major V tile with the LDS transpose load (ds_read_b64_tr_b16).
-// The tree's own keys are one or two extra tiles whose scores are masked with the packed bitmask slice.
+// V^T operands come from the row-major V tile through the LDS transpose load (ds_read_b64_tr_b16).
+// Wavefronts that share a query block split each tile's keys (key groups) and are merged through LDS at the
+// end; key splits across workgroups are merged by the last workgroup to finish (a counter per (sequence, head)).
+// The tree's own keys are extra tiles whose scores are masked with the packed bitmask slice.
 //
-// fp32 path: same split / online-softmax structure on the vector ALU (small reference-precision shapes).
+// fp32 path: split / online-softmax structure on the vector ALU (small reference-precision shapes).
 #include <math.h>
 #include <stdlib.h>
+
+#include <type_traits>
 
 #include "mcsd_internal.h"
 
@@ -36,45 +43,60 @@ struct AttnParams {
     int32_t max_prefix;
     int64_t node_stride, head_stride;
     float c;          // softmax_scale * log2(e)
-    int32_t S;        // key splits in the grid
-    int32_t SP;       // partial results per (b,h): S * key groups per workgroup
+    int32_t S;        // key splits
+    int32_t SP;       // partial results per (b,h) (== S)
+    int32_t *counters; // [B*H] arrivals of the key splits; zero between calls
     float *part_o;    // [B*H][SP][n][D]
-    float *part_m;    // [B*H][SP][n]   running maximum of the raw scores
+    float *part_m;    // [B*H][SP][n]   reference maximum of the raw scores
     float *part_l;    // [B*H][SP][n]   sum of exp2((s - m) * c)
+    int dbg;
 };
 
 struct AttnPlan {
-    int QB, KG, T, S, SP;
+    int QBP;   // query blocks of 32 rows, rounded up to 1, 2 or 4 (bf16 path)
+    int T;     // keys per tile
+    int S;     // key splits
+    int NS;    // LDS stages of the bf16 sweep: 4 when one workgroup per compute unit suffices, else 2
 };
 
-__host__ __device__ inline int key_groups(int QB) { return QB <= 2 ? 2 : 1; }
-__host__ __device__ inline int tile_keys_bf16(int) { return 64; }
+__host__ __device__ inline int tile_keys_bf16(int QBP) { return QBP == 1 ? 128 : 64; }   // == SweepCfg::T
 
 AttnPlan make_plan(int dtype, int B, int H, int n, int max_prefix)
 {
     AttnPlan pl;
     if (dtype == MCSD_BF16) {
-        pl.QB = (n + 31) / 32;
-        pl.KG = key_groups(pl.QB);
-        pl.T = tile_keys_bf16(pl.QB);
+        const int qb = (n + 31) / 32;
+        pl.QBP = qb <= 1 ? 1 : (qb == 2 ? 2 : 4);
+        pl.T = tile_keys_bf16(pl.QBP);
     } else {
-        pl.QB = 1;
-        pl.KG = 1;
+        pl.QBP = 1;
         pl.T = 32;
     }
     const long bh = (long)B * H;
-    const int tiles_max = (max_prefix + pl.T - 1) / pl.T;
-    long want = (512 + bh - 1) / bh;           // aim for >= 2 workgroups per compute unit
-    long cap = tiles_max / 2;                   // at least two tiles per split
-    long S = want < cap ? want : cap;
+    const long tiles_max = (max_prefix + pl.T - 1) / pl.T;
+    long S;
+    if (dtype == MCSD_BF16) {
+        // Splitting the keys of one (sequence, head) over several workgroups costs a round trip through memory
+        // (about 10 us): only worth it when a workgroup would otherwise sweep more than 64 tiles.
+        S = (512 + bh - 1) / bh;                            // two workgroups per compute unit
+        if (S > tiles_max / 64) S = tiles_max / 64;
+    } else {
+        S = (512 + bh - 1) / bh;
+        if (S > tiles_max) S = tiles_max;
+    }
     if (S < 1) S = 1;
     if (S > 64) S = 64;
-    if (const char *ov = getenv("MCSD_ATTN_SPLITS")) {     // tuning override: number of key splits
+    if (const char *ov = getenv("MCSD_ATTN_SPLITS")) {      // tuning override: number of key splits
         const long v = atol(ov);
         if (v >= 1 && v <= 64) S = v;
     }
+    // few workgroups: one per compute unit with a deep ring; many: two per compute unit with a double buffer
+    pl.NS = (dtype == MCSD_BF16 && pl.QBP > 1 && bh * S <= 256) ? 4 : 2;
+    if (const char *ov = getenv("MCSD_ATTN_STAGES")) {      // tuning override: 2 or 4 stages
+        const long v = atol(ov);
+        if ((v == 2 || v == 4) && pl.QBP > 1) pl.NS = (int)v;
+    }
     pl.S = (int)S;
-    pl.SP = pl.S * pl.KG;
     return pl;
 }
 
@@ -98,130 +120,203 @@ __device__ inline s16x4_t lds_read_tr16(const unsigned char *p)
     return __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4_t __attribute__((address_space(3))) *)(p));
 }
 
+// 16 bytes per lane from global memory straight into LDS: lane l lands at lds_base + 16*l (lds_base uniform).
+__device__ inline void load_to_lds16(const void *gsrc, void *lds_base)
+{
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)gsrc,
+                                     (__attribute__((address_space(3))) void *)lds_base, 16, 0, 0);
+}
+
+// s_waitcnt vmcnt(N) only (expcnt / lgkmcnt left at their maxima)
+#define MCSD_WAIT_VMCNT(N) __builtin_amdgcn_s_waitcnt(((N) & 15) | (7 << 4) | (15 << 8) | (((N) >> 4) << 14))
+
 // ---------------------------------------------------------------------------------------------------
 // bf16 / MFMA kernel
 // ---------------------------------------------------------------------------------------------------
-template <int D, int QB>
-struct Bf16Cfg {
-    static constexpr int KG = QB <= 2 ? 2 : 1;  // key groups: wavefronts that share a query block split the tile's keys
-    static constexpr int T = 64;                // keys per tile
-    static constexpr int KPW = T / 32 / KG;     // 32-key blocks per wavefront per tile
-    static constexpr int SK = D * 2 + 16;       // LDS row stride of the K tile (bytes): 4 banks per row
-    static constexpr int SV = D * 2 + 64;       // LDS row stride of the V tile (bytes): 16 banks per row
-    static constexpr int CPR = D / 8;           // 16-byte chunks per K/V row
-    static constexpr int RPP = 256 / CPR;       // rows per load pass of the workgroup
-    static constexpr int NLD = T / RPP;         // load passes per tile
-    static constexpr int KS = D / 16;           // k-steps of S^T = K Q^T
-    static constexpr int CB = D / 32;           // 32-row blocks of O^T
+template <int D, int QBP, int NS_>
+struct SweepCfg {
+    static constexpr int WAVES = 4;
+    static constexpr int KG = 4 / QBP;                 // key groups: wavefronts that share a query block and split the keys
+    static constexpr int KPW = QBP == 4 ? 2 : 1;       // 32-key blocks per wavefront per tile
+    static constexpr int THREADS = WAVES * 64;
+    static constexpr int T = 32 * KG * KPW;            // keys per tile (64, 64, 128 for QBP = 4, 2, 1)
+    static constexpr int RB = D * 2;                   // bytes per K/V row
+    static constexpr int CPR = RB / 16;                // 16-byte chunks per row
+    static constexpr int RPI = 64 / CPR;               // rows covered by one direct-to-LDS instruction (1 KiB)
+    static constexpr int TILE_K = T * RB;              // bytes of the K half of a stage; V follows
+    static constexpr int TILE = 2 * TILE_K;
+    static constexpr int NI = T / RPI / WAVES;         // direct-to-LDS instructions per wavefront for K (same for V)
+    static constexpr int DPT = 2 * NI;                 // ... per tile
+    static constexpr int NS = NS_;                     // LDS stages: one being computed, NS - 1 being filled
+    static constexpr int KS = D / 16;                  // k-steps of S^T = K Q^T
+    static constexpr int CB = D / 32;                  // 32-row blocks of O^T
+    static constexpr int CPT = T * CPR / THREADS;      // 16-byte chunks per thread for K (same for V), register path
+    static constexpr int MSLOT = 32 * D * 4 + 256;     // LDS bytes to hand one query block's (O, m, l) to another wavefront
+    static constexpr int LDS_BYTES = NS * TILE > (KG - 1) * QBP * MSLOT ? NS * TILE : (KG - 1) * QBP * MSLOT;
+    static_assert(NI >= 1 && CPT >= 1 && (NS - 2) * DPT < 64 && LDS_BYTES <= 160 * 1024 - 64, "tile does not map onto the workgroup");
 };
+
+// XOR swizzle of the 16-byte chunk index inside row r.  With it, 16 consecutive rows read at the same logical
+// chunk (K operand loads) and 4 consecutive rows read at 4 consecutive chunks (V transpose loads) both hit 16
+// different 16-byte bank groups.
+template <int D>
+__device__ inline int swz(int r)
+{
+    return D == 128 ? (((r & 3) << 2) | ((r >> 2) & 3)) : ((((r >> 1) & 1) << 2) | ((r >> 2) & 3));
+}
 
 // Log2-domain slack of the running reference maximum: the accumulators are rescaled only when a block's maximum
 // exceeds the reference by more than this, so exponentiated scores stay below 2^RESCALE_SLACK.  The result is
 // exact: numerator and denominator always share the same reference.
 constexpr float RESCALE_SLACK = 6.f;
 
-// One block of 32 keys against the wavefront's 32 queries.
-// MODE 0: all keys visible; otherwise bit k of `bits` says whether key k of the block is visible to this lane's query.
-template <int D, int QB, int MODE>
-__device__ inline void attn_block(const unsigned char *ldsK, const unsigned char *ldsV, int kb, const bf16x8_t *qreg,
-                                  f32x16_t *oacc, float &m_ref, float &l_run, float c, int g, int ln, uint32_t bits)
+// Per-lane LDS offsets of the two operand read patterns inside a stage (computed once).
+struct LaneAddr {
+    int k;   // K operand: row (kg*32 + ln), chunk g ^ swz; XOR ks*32 selects the k-step
+    int v;   // V^T operand: row (kg*32 + 4g + j/4), chunk/sub of this lane; XOR ct*16 and an immediate select the rest
+};
+
+// State of one 32-query block held by a wavefront.
+template <int D>
+struct QBlock {
+    bf16x8_t q[D / 16];        // Q as B operands: lane holds Q[row][ks*16 + 8g .. +8]
+    f32x16_t o[D / 32];        // O^T accumulators
+    float m_ref, l_run;        // reference maximum (raw score units), per-lane part of the denominator
+};
+
+// Exponentials of one pair of scores: p = exp2(s*c - mc), added to the denominator and packed as bf16 into P^T
+// (kept as dwords: pb[r/8] is one B operand).  The empty asm keeps the pair where it is written, between two MFMAs.
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+typedef __attribute__((ext_vector_type(4))) unsigned u32x4_t;
+__device__ inline void softmax_exp2(const f32x16_t &sacc, int r, float c, float mc, float &psum, u32x4_t *pb)
 {
-    using C = Bf16Cfg<D, QB>;
-    // S^T[key][query] = K * Q^T : lane (query = ln, half g) gets keys 8*(r/4) + 4*g + r%4, r = 0..15
-    f32x16_t sacc = {0};
-    const unsigned char *krow = ldsK + (kb * 32 + ln) * C::SK + g * 16;
+    const float p0 = fast_exp2(fmaf(sacc[r], c, -mc)), p1 = fast_exp2(fmaf(sacc[r + 1], c, -mc));
+    psum += p0 + p1;
+    bf16x2_t pk;
+    pk[0] = (__bf16)p0;
+    pk[1] = (__bf16)p1;
+    unsigned u = __builtin_bit_cast(unsigned, pk);
+    asm volatile("" : "+v"(u));
+    pb[r / 8][(r % 8) / 2] = u;
+}
+
+// One tile: the wavefront's KPW blocks of 32 keys against its 32 queries.  With two blocks the instruction stream
+// is laid out so that the matrix pipe and the vector ALU overlap inside the wavefront:
+//     QK_0, QK_1 | block maxima, rare rescale | exp(0) | PV_0 with exp(1) in its shadow | PV_1
+// Operand reads are issued ahead of their use.  MODE 0: all keys visible; otherwise bit k of bits[u] says whether
+// key k of block u is visible to this lane's query.
+template <int D, int QBP, int NS, int MODE>
+__device__ inline void attn_tile(const unsigned char *stage, const LaneAddr la, QBlock<D> &qs, float c, int g,
+                                 const uint32_t *bits)
+{
+    using C = SweepCfg<D, QBP, NS>;
+    constexpr int U = C::KPW;
+    // K rows of the blocks (A operands of S^T = K Q^T); block u sits 32*u rows below the lane's base row
+    bf16x8_t kf[U][C::KS];
 #pragma unroll
-    for (int ks = 0; ks < C::KS; ++ks) {
-        bf16x8_t a = *(const bf16x8_t *)(krow + ks * 32);
-        sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[ks], sacc, 0, 0, 0);
+    for (int u = 0; u < U; ++u)
+#pragma unroll
+        for (int ks = 0; ks < C::KS; ++ks) kf[u][ks] = *(const bf16x8_t *)(stage + (la.k ^ (ks * 32)) + u * 32 * C::RB);
+    __builtin_amdgcn_sched_barrier(0);
+    // S^T[key][query] : lane (query = ln, half g) gets keys 8*(r/4) + 4*g + r%4, r = 0..15
+    f32x16_t sacc[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        sacc[u] = (f32x16_t){0};
+#pragma unroll
+        for (int ks = 0; ks < C::KS; ++ks) sacc[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[u][ks], qs.q[ks], sacc[u], 0, 0, 0);
     }
-    if (MODE != 0) {
+    // V^T fragments via the LDS transpose load, issued ahead of their use: block 0's during the softmax, block 1's
+    // before the first PV MFMA.  The reads of one k-step pair (ks2, e4) sit 16*ks2 + 8*e4 rows below the lane's
+    // base row; the chunk select is cb*4 ^ e4*2.
+    const unsigned char *vst = stage + C::TILE_K;
+    bf16x8_t vf[U][2][C::CB];
+    auto read_v = [&](int u) {
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int key = 8 * (r / 4) + 4 * g + (r % 4);
-            if (!((bits >> key) & 1u)) sacc[r] = -INFINITY;
+        for (int ks2 = 0; ks2 < 2; ++ks2)
+#pragma unroll
+            for (int cb = 0; cb < C::CB; ++cb) {
+                const s16x4_t lo = lds_read_tr16(vst + (la.v ^ (((cb * 4) ^ 0) * 16)) + (u * 32 + ks2 * 16) * C::RB);
+                const s16x4_t hi = lds_read_tr16(vst + (la.v ^ (((cb * 4) ^ 2) * 16)) + (u * 32 + ks2 * 16 + 8) * C::RB);
+                vf[u][ks2][cb] = __builtin_bit_cast(bf16x8_t, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+            }
+    };
+    read_v(0);
+    // masking, maximum over the tile's blocks, rare rescale of the accumulators
+    float mx = -INFINITY;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        if (MODE != 0) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int key = 8 * (r / 4) + 4 * g + (r % 4);
+                if (!((bits[u] >> key) & 1u)) sacc[u][r] = -INFINITY;
+            }
         }
-    }
-    float mx = fmaxf(fmaxf(sacc[0], sacc[1]), sacc[2]);
+        mx = fmaxf(fmaxf(mx, sacc[u][0]), sacc[u][1]);
 #pragma unroll
-    for (int r = 3; r < 15; r += 2) mx = fmaxf(fmaxf(mx, sacc[r]), sacc[r + 1]);
-    mx = fmaxf(mx, sacc[15]);
+        for (int r = 2; r < 16; r += 2) mx = fmaxf(fmaxf(mx, sacc[u][r]), sacc[u][r + 1]);
+    }
     mx = half_swap_max(mx);
-    // rescale only when the block maximum outgrows the reference by more than the slack (first block: -inf)
-    const bool grow = (mx - m_ref) * c > RESCALE_SLACK;
+    // rescale only when the maximum outgrows the reference by more than the slack (first tile: -inf)
+    const bool grow = (mx - qs.m_ref) * c > RESCALE_SLACK;
     if (__builtin_amdgcn_ballot_w64(grow) != 0) {
-        const float m_new = grow ? mx : m_ref;
-        const float alpha = m_new == m_ref ? 1.f : fast_exp2((m_ref - m_new) * c);   // -inf reference: exp2(-inf) = 0
-        m_ref = m_new;
-        l_run *= alpha;
+        const float m_new = grow ? mx : qs.m_ref;
+        const float alpha = m_new == qs.m_ref ? 1.f : fast_exp2((qs.m_ref - m_new) * c);   // -inf reference: exp2(-inf) = 0
+        qs.m_ref = m_new;
+        qs.l_run *= alpha;
 #pragma unroll
         for (int cb = 0; cb < C::CB; ++cb)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) oacc[cb][r] *= alpha;
+            for (int r = 0; r < 16; ++r) qs.o[cb][r] *= alpha;
     }
-    const float mc = (m_ref == -INFINITY ? 0.f : m_ref) * c;
+    const float mc = (qs.m_ref == -INFINITY ? 0.f : qs.m_ref) * c;
+    u32x4_t pb[U][2];
     float psum = 0.f;
-    bf16x8_t pb[2];
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-        const float pv = fast_exp2(fmaf(sacc[r], c, -mc));
-        psum += pv;
-        pb[r / 8][r % 8] = (__bf16)pv;
-    }
-    l_run += psum;
-    // O^T[c][query] += V^T[c][key] * P^T[key][query]; V^T operands via the LDS transpose load
-    const int vcol = 16 * (ln >> 4) + 4 * (ln & 3);
-    const int vkey = 4 * g + ((ln & 15) >> 2);
+    for (int r = 0; r < 16; r += 2) softmax_exp2(sacc[0], r, c, mc, psum, pb[0]);
+    __builtin_amdgcn_sched_barrier(0);
+    // O^T[c][query] += V^T[c][key] * P^T[key][query]
+    if (U == 2) {
+        read_v(1);
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int ks2 = 0; ks2 < 2; ++ks2) {
-        const unsigned char *vbase = ldsV + (kb * 32 + ks2 * 16 + vkey) * C::SV + vcol * 2;
-#pragma unroll
-        for (int cb = 0; cb < C::CB; ++cb) {
-            s16x4_t lo = lds_read_tr16(vbase + cb * 64);
-            s16x4_t hi = lds_read_tr16(vbase + cb * 64 + 8 * C::SV);
-            s16x8_t both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-            bf16x8_t a = __builtin_bit_cast(bf16x8_t, both);
-            oacc[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb[ks2], oacc[cb], 0, 0, 0);
+        for (int i = 0; i < 2 * C::CB; ++i) {
+            const int ks2 = i / C::CB, cb = i % C::CB;
+            qs.o[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[0][ks2][cb], __builtin_bit_cast(bf16x8_t, pb[0][ks2]), qs.o[cb], 0, 0, 0);
+            if (C::CB == 4) softmax_exp2(sacc[U - 1], 2 * i, c, mc, psum, pb[U - 1]);
+            else { softmax_exp2(sacc[U - 1], 4 * i, c, mc, psum, pb[U - 1]); softmax_exp2(sacc[U - 1], 4 * i + 2, c, mc, psum, pb[U - 1]); }
+            __builtin_amdgcn_sched_barrier(0);
         }
     }
-}
-
-// All key blocks of one tile that belong to this wavefront's key group.
-// MODE 0: full prefix tile, 1: prefix tail (keys < valid exist), 2: tree tile (visibility from the mask row).
-template <int D, int QB, int MODE>
-__device__ inline void attn_tile(const unsigned char *ldsK, const unsigned char *ldsV, const bf16x8_t *qreg,
-                                 f32x16_t *oacc, float &m_ref, float &l_run, float c, int kg, int g, int ln,
-                                 int valid, const uint64_t *mrow, int tile_key0)
-{
-    using C = Bf16Cfg<D, QB>;
 #pragma unroll
-    for (int j = 0; j < C::KPW; ++j) {
-        const int kb = kg * C::KPW + j;
-        uint32_t bits = 0xffffffffu;
-        if (MODE == 1) {
-            const int left = valid - kb * 32;     // keys of this block that exist
-            bits = left >= 32 ? 0xffffffffu : (left <= 0 ? 0u : ((1u << left) - 1u));
-        } else if (MODE == 2) {
-            const int col = tile_key0 + kb * 32;
-            bits = (uint32_t)(((col >> 6) ? mrow[1] : mrow[0]) >> (col & 63));
-        }
-        attn_block<D, QB, MODE>(ldsK, ldsV, kb, qreg, oacc, m_ref, l_run, c, g, ln, bits);
-    }
+    for (int ks2 = 0; ks2 < 2; ++ks2)
+#pragma unroll
+        for (int cb = 0; cb < C::CB; ++cb)
+            qs.o[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[U - 1][ks2][cb], __builtin_bit_cast(bf16x8_t, pb[U - 1][ks2]), qs.o[cb], 0, 0, 0);
+    qs.l_run += psum;
 }
 
-template <int D, int QB>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2)))
+template <int D, int QBP, int NS>
+__global__ __launch_bounds__((SweepCfg<D, QBP, NS>::THREADS)) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void tree_attn_bf16_kernel(const AttnParams p)
 {
-    using C = Bf16Cfg<D, QB>;
-    constexpr int TILE_BYTES = C::T * C::SK + C::T * C::SV;
-    __shared__ __attribute__((aligned(16))) unsigned char lds[2 * TILE_BYTES];     // two tiles: compute one, fill one
+    using C = SweepCfg<D, QBP, NS>;
+    __shared__ __attribute__((aligned(1024))) unsigned char ring[C::LDS_BYTES];
+    __shared__ int s_last;
 
-    const int s = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+    // Workgroup ids are dealt round-robin to the 8 XCDs: renumber so that the key splits of one (sequence, head),
+    // which meet again in the final merge, run on one XCD and share its L2.
+    const int total = gridDim.x;
+    int wg = blockIdx.x;
+    if ((total & 7) == 0) wg = (wg & 7) * (total >> 3) + (wg >> 3);
+    const int s = wg % p.S;
+    const int bhi = wg / p.S;
+    const int h = bhi % p.H, b = bhi / p.H;
+
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int g = lane >> 5, ln = lane & 31;
-    const int qb = wave % QB, kg = wave / QB;
-    const bool computes = kg < C::KG;
+    const int qb = wave % QBP, kg = wave / QBP;
 
     int L = p.lens[b];
     L = L < 0 ? 0 : (L > p.max_prefix ? p.max_prefix : L);
@@ -230,7 +325,8 @@ void tree_attn_bf16_kernel(const AttnParams p)
     const int t0 = min(s * tps, tiles_b), t1 = min(t0 + tps, tiles_b);
     const int n_tree_tiles = s == 0 ? (p.n + C::T - 1) / C::T : 0;
     const int n_pre = t1 - t0;
-    if (n_pre + n_tree_tiles == 0) return;
+    if (n_pre + n_tree_tiles == 0) return;                  // this split has no keys; it is not counted either
+    const int n_active = tps > 0 ? min(p.S, (tiles_b + tps - 1) / tps) : 1;   // splits that run for this sequence
     // leading tiles of this split that are full (only the sequence's last tile can be ragged)
     const int n_hot = (n_pre > 0 && t1 * C::T > L) ? n_pre - 1 : n_pre;
 
@@ -239,103 +335,193 @@ void tree_attn_bf16_kernel(const AttnParams p)
     const __bf16 *kt = (const __bf16 *)p.kt + bh * p.node_stride * D;
     const __bf16 *vt = (const __bf16 *)p.vt + bh * p.node_stride * D;
     const int64_t pre0 = p.seq_base[b] + (int64_t)h * p.head_stride;
-    const __bf16 *kp = (const __bf16 *)p.kp + pre0;
-    const __bf16 *vp = (const __bf16 *)p.vp + pre0;
+    const unsigned char *kp = (const unsigned char *)((const __bf16 *)p.kp + pre0);
+    const unsigned char *vp = (const unsigned char *)((const __bf16 *)p.vp + pre0);
 
-    // Q block of this wavefront as B operands: lane holds Q[row][ks*16 + 8g .. +8]
+    // query block of this wavefront; mask row of this lane's query (zero for padded rows)
+    QBlock<D> qs;
     const int qrow = qb * 32 + ln;
-    bf16x8_t qreg[C::KS];
 #pragma unroll
     for (int ks = 0; ks < C::KS; ++ks) {
         uint4 v = make_uint4(0, 0, 0, 0);
         if (qrow < p.n) v = *(const uint4 *)(q + (int64_t)qrow * D + ks * 16 + g * 8);
-        qreg[ks] = __builtin_bit_cast(bf16x8_t, v);
+        qs.q[ks] = __builtin_bit_cast(bf16x8_t, v);
     }
-    // mask row of this lane's query (zero for padded rows)
     uint64_t mrow[2] = {0, 0};
     if (qrow < p.n) {
         mrow[0] = p.mask_bits[(int64_t)qrow * p.mask_words];
         if (p.mask_words > 1) mrow[1] = p.mask_bits[(int64_t)qrow * p.mask_words + 1];
     }
-
-    f32x16_t oacc[C::CB];
 #pragma unroll
-    for (int cb = 0; cb < C::CB; ++cb) oacc[cb] = (f32x16_t){0};
-    float m_ref = -INFINITY, l_run = 0.f;
+    for (int cb = 0; cb < C::CB; ++cb) qs.o[cb] = (f32x16_t){0};
+    qs.m_ref = -INFINITY;
+    qs.l_run = 0.f;
 
-    const int ld_row = tid / C::CPR, ld_chunk = tid % C::CPR;
-    const int ld_off = ld_row * D + ld_chunk * 8;                  // element offset of this thread's first chunk
-    uint4 kreg[C::NLD], vreg[C::NLD];
-
-    auto stash = [&](int buf) {
-        unsigned char *bk = lds + buf * TILE_BYTES, *bv = bk + C::T * C::SK;
+    // operand read offsets of this lane inside a stage; its first key block starts at row kg * KPW * 32
+    LaneAddr la;
+    {
+        const int krow = kg * C::KPW * 32 + ln;
+        la.k = krow * C::RB + ((g ^ swz<D>(krow)) * 16);
+        const int j = ln & 15, grp = ln >> 4, jr = j >> 2;
+        const int vrow = kg * C::KPW * 32 + 4 * g + jr;               // + 32*u + 16*ks2 + 8*e4 by immediate
+        const int lchunk = grp * 2 + ((j & 3) >> 1);                   // + 4*cb
+        // swz(vrow + 32*u + 16*ks2 + 8*e4) = swz(vrow) ^ (e4 << 1): the e4 part is folded into the compile-time XOR
+        la.v = vrow * C::RB + ((lchunk ^ swz<D>(vrow)) * 16) + (j & 1) * 8;
+    }
+    uint32_t all_keys[C::KPW];
 #pragma unroll
-        for (int i = 0; i < C::NLD; ++i) {
-            const int row = i * C::RPP + ld_row;
-            *(uint4 *)(bk + row * C::SK + ld_chunk * 16) = kreg[i];
-            *(uint4 *)(bv + row * C::SV + ld_chunk * 16) = vreg[i];
-        }
-    };
+    for (int u = 0; u < C::KPW; ++u) all_keys[u] = 0xffffffffu;
 
-    // ---- full prefix tiles: register prefetch one tile ahead of the LDS fill, LDS double-buffered ----
+    // ---- full prefix tiles: HBM -> LDS directly, one tile ahead of the compute ----
     if (n_hot > 0) {
-        const __bf16 *ksrc = kp + (int64_t)t0 * C::T * D + ld_off;
-        const __bf16 *vsrc = vp + (int64_t)t0 * C::T * D + ld_off;
-        auto fetch_full = [&](int it) {
+        // lane's source offset inside a tile for instruction i: row G*RPI + lane/CPR, logical chunk (lane%CPR)^swz(row)
+        int goff[C::NI];
 #pragma unroll
-            for (int i = 0; i < C::NLD; ++i) {
-                kreg[i] = *(const uint4 *)(ksrc + ((int64_t)it * C::T + i * C::RPP) * D);
-                vreg[i] = *(const uint4 *)(vsrc + ((int64_t)it * C::T + i * C::RPP) * D);
+        for (int i = 0; i < C::NI; ++i) {
+            const int G = i * C::WAVES + wave;
+            const int r = G * C::RPI + lane / C::CPR;
+            goff[i] = r * C::RB + (((lane % C::CPR) ^ swz<D>(r)) * 16);
+        }
+        const unsigned char *ksrc = kp + (int64_t)t0 * C::TILE_K;
+        const unsigned char *vsrc = vp + (int64_t)t0 * C::TILE_K;
+        // Stage numbers are compile-time constants so that the compiler can tell the stage being filled from
+        // the stage being read (otherwise it makes every LDS read wait for the loads just issued).
+        auto issue_tile = [&](int it, auto stage) {
+            unsigned char *dst = ring + decltype(stage)::value * C::TILE + wave * 1024;
+            static_assert(decltype(stage)::value < NS, "stage out of range");
+#pragma unroll
+            for (int i = 0; i < C::NI; ++i) {
+                load_to_lds16(ksrc + (int64_t)it * C::TILE_K + goff[i], dst + i * C::WAVES * 1024);
+                load_to_lds16(vsrc + (int64_t)it * C::TILE_K + goff[i], dst + C::TILE_K + i * C::WAVES * 1024);
             }
         };
-        fetch_full(0);
-        stash(0);
-        if (n_hot > 1) fetch_full(1);
-        __syncthreads();
-        for (int it = 0; it < n_hot; ++it) {
-            if (it + 1 < n_hot) stash((it + 1) & 1);          // tile it+1: registers -> the other LDS buffer
-            if (it + 2 < n_hot) fetch_full(it + 2);           // tile it+2: HBM -> registers, lands during the MFMAs
-            if (computes) {
-                const unsigned char *ldsK = lds + (it & 1) * TILE_BYTES;
-                attn_tile<D, QB, 0>(ldsK, ldsK + C::T * C::SK, qreg, oacc, m_ref, l_run, p.c, kg, g, ln, C::T, mrow, 0);
-            }
-            __syncthreads();                                   // tile it fully read, tile it+1 fully written
+        auto step = [&](int it, auto stage) {
+            constexpr int ST = decltype(stage)::value;
+            // this wavefront's part of tile `it` has landed once at most NS-2 later tiles are outstanding
+            if (NS > 2 && it + NS - 2 < n_hot) MCSD_WAIT_VMCNT((NS - 2) * C::DPT);
+            else MCSD_WAIT_VMCNT(0);
+            __builtin_amdgcn_s_barrier();                     // ... and everyone's; the stage of tile it-1 is free again
+            if (it + NS - 1 < n_hot) issue_tile(it + NS - 1, std::integral_constant<int, (ST + NS - 1) % NS>());
+            attn_tile<D, QBP, NS, 0>(ring + ST * C::TILE, la, qs, p.c, g, all_keys);
+        };
+        issue_tile(0, std::integral_constant<int, 0>());
+        if (NS > 2) {
+            if (1 < n_hot) issue_tile(1, std::integral_constant<int, 1 % NS>());
+            if (2 < n_hot) issue_tile(2, std::integral_constant<int, 2 % NS>());
         }
+        int it = 0;
+        for (; it + NS <= n_hot; it += NS) {
+            step(it, std::integral_constant<int, 0>());
+            step(it + 1, std::integral_constant<int, 1>());
+            if (NS > 2) {
+                step(it + 2, std::integral_constant<int, 2 % NS>());
+                step(it + 3, std::integral_constant<int, 3 % NS>());
+            }
+        }
+        if (it < n_hot) step(it, std::integral_constant<int, 0>());
+        if (NS > 2) {
+            if (it + 1 < n_hot) step(it + 1, std::integral_constant<int, 1>());
+            if (it + 2 < n_hot) step(it + 2, std::integral_constant<int, 2 % NS>());
+        }
+        MCSD_WAIT_VMCNT(0);
     }
+    __syncthreads();
 
-    // ---- ragged last prefix tile and the tree's own tiles: one at a time, rows beyond `valid` zero-filled ----
+    // ---- ragged last prefix tile and the tree's own tiles: through registers, rows beyond `valid` zero-filled ----
     const int n_rest = (n_pre - n_hot) + n_tree_tiles;
     for (int it = 0; it < n_rest; ++it) {
         const bool tail = it < n_pre - n_hot;
         const int tt = tail ? 0 : it - (n_pre - n_hot);
-        const __bf16 *ksrc = tail ? kp + (int64_t)(t1 - 1) * C::T * D : kt + (int64_t)tt * C::T * D;
-        const __bf16 *vsrc = tail ? vp + (int64_t)(t1 - 1) * C::T * D : vt + (int64_t)tt * C::T * D;
+        const unsigned char *ksrc = tail ? kp + (int64_t)(t1 - 1) * C::TILE_K : (const unsigned char *)kt + (int64_t)tt * C::TILE_K;
+        const unsigned char *vsrc = tail ? vp + (int64_t)(t1 - 1) * C::TILE_K : (const unsigned char *)vt + (int64_t)tt * C::TILE_K;
         const int valid = tail ? L - (t1 - 1) * C::T : min(C::T, p.n - tt * C::T);
 #pragma unroll
-        for (int i = 0; i < C::NLD; ++i) {
-            const int row = i * C::RPP + ld_row;
-            kreg[i] = make_uint4(0, 0, 0, 0);
-            vreg[i] = make_uint4(0, 0, 0, 0);
-            if (row < valid) {
-                kreg[i] = *(const uint4 *)(ksrc + (int64_t)row * D + ld_chunk * 8);
-                vreg[i] = *(const uint4 *)(vsrc + (int64_t)row * D + ld_chunk * 8);
+        for (int i0 = 0; i0 < C::CPT; i0 += 4) {           // four chunks of K and V at a time keeps the staging small
+            uint4 kreg[4], vreg[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int x = (i0 + i) * C::THREADS + tid, row = x / C::CPR, ch = x % C::CPR;
+                kreg[i] = make_uint4(0, 0, 0, 0);
+                vreg[i] = make_uint4(0, 0, 0, 0);
+                if (i0 + i < C::CPT && row < valid) {
+                    kreg[i] = *(const uint4 *)(ksrc + row * C::RB + ch * 16);
+                    vreg[i] = *(const uint4 *)(vsrc + row * C::RB + ch * 16);
+                }
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int x = (i0 + i) * C::THREADS + tid, row = x / C::CPR, ch = x % C::CPR;
+                const int off = row * C::RB + ((ch ^ swz<D>(row)) * 16);
+                if (i0 + i < C::CPT) {
+                    *(uint4 *)(ring + off) = kreg[i];
+                    *(uint4 *)(ring + C::TILE_K + off) = vreg[i];
+                }
             }
         }
-        stash(0);
         __syncthreads();
-        if (computes) {
-            if (tail)
-                attn_tile<D, QB, 1>(lds, lds + C::T * C::SK, qreg, oacc, m_ref, l_run, p.c, kg, g, ln, valid, mrow, 0);
-            else
-                attn_tile<D, QB, 2>(lds, lds + C::T * C::SK, qreg, oacc, m_ref, l_run, p.c, kg, g, ln, 0, mrow, tt * C::T);
+        uint32_t bits[C::KPW];
+#pragma unroll
+        for (int u = 0; u < C::KPW; ++u) {
+            const int key0 = (kg * C::KPW + u) * 32;          // first key of this block inside the tile
+            if (tail) {
+                const int left = valid - key0;                 // keys of the block that exist
+                bits[u] = left >= 32 ? 0xffffffffu : (left <= 0 ? 0u : ((1u << left) - 1u));
+            } else {
+                const int col = tt * C::T + key0;
+                bits[u] = (uint32_t)(((col >> 6) ? mrow[1] : mrow[0]) >> (col & 63));
+            }
+        }
+        attn_tile<D, QBP, NS, 1>(ring, la, qs, p.c, g, bits);
+        __syncthreads();
+    }
+
+    // ---- merge the key groups of each query block through LDS (layout [c/4][query] keeps lanes contiguous) ----
+    float l_tot = half_swap_sum(qs.l_run);
+    if (C::KG > 1) {
+        if (kg > 0) {
+            unsigned char *slot = ring + ((kg - 1) * QBP + qb) * C::MSLOT;
+#pragma unroll
+            for (int cb = 0; cb < C::CB; ++cb)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    f32x4_t v;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) v[e] = qs.o[cb][4 * j + e];
+                    *(f32x4_t *)(slot + (((cb * 4 + j) * 2 + g) * 32 + ln) * 16) = v;
+                }
+            if (g == 0) {
+                ((float *)(slot + 32 * D * 4))[ln] = qs.m_ref;
+                ((float *)(slot + 32 * D * 4))[32 + ln] = l_tot;
+            }
         }
         __syncthreads();
     }
-    if (!computes) return;
-
-    const float l_tot = half_swap_sum(l_run);
-    if (qrow >= p.n) return;
-    if (p.SP == 1) {
+    // wavefronts of key group 0 now own one query block each; the others are done
+    auto merge_from = [&](const float *src_o, float m_k, float l_k) {
+        // (O, m, l) of the same query block from elsewhere, fragments in this lane's register layout
+        const float m_new = fmaxf(qs.m_ref, m_k);
+        const bool any = m_new != -INFINITY;                  // false: neither side has seen a key
+        const float a = any ? fast_exp2((qs.m_ref - m_new) * p.c) : 1.f, bsc = any ? fast_exp2((m_k - m_new) * p.c) : 0.f;
+        qs.m_ref = m_new;
+        l_tot = l_tot * a + l_k * bsc;
+#pragma unroll
+        for (int cb = 0; cb < C::CB; ++cb)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const f32x4_t v = *(const f32x4_t *)(src_o + (((cb * 4 + j) * 2 + g) * 32 + ln) * 4);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) qs.o[cb][4 * j + e] = qs.o[cb][4 * j + e] * a + v[e] * bsc;
+            }
+    };
+    if (kg == 0) {
+#pragma unroll 1
+        for (int k = 1; k < C::KG; ++k) {
+            const unsigned char *slot = ring + ((k - 1) * QBP + qb) * C::MSLOT;
+            merge_from((const float *)slot, ((const float *)(slot + 32 * D * 4))[ln], ((const float *)(slot + 32 * D * 4))[32 + ln]);
+        }
+    }
+    auto store_out = [&]() {
+        if (qrow >= p.n) return;
         const float inv = 1.f / l_tot;
         __bf16 *o = (__bf16 *)p.out + (bh * p.node_stride + qrow) * D;
 #pragma unroll
@@ -344,27 +530,77 @@ void tree_attn_bf16_kernel(const AttnParams p)
             for (int j = 0; j < 4; ++j) {
                 bf16x4_t v;
 #pragma unroll
-                for (int e = 0; e < 4; ++e) v[e] = (__bf16)(oacc[cb][4 * j + e] * inv);
+                for (int e = 0; e < 4; ++e) v[e] = (__bf16)(qs.o[cb][4 * j + e] * inv);
                 *(bf16x4_t *)(o + cb * 32 + 8 * j + 4 * g) = v;
             }
-    } else {
-        const int sp = s * C::KG + kg;
-        const int64_t prow = (bh * p.SP + sp) * p.n + qrow;
-        float *po = p.part_o + prow * D;
+    };
+    if (p.S == 1) {
+        if (kg == 0) store_out();
+        return;
+    }
+
+    // ---- key splits: every split publishes (O, m, l) in register-fragment order (fully coalesced); the last
+    // workgroup to arrive for this (sequence, head) folds all of them and writes the output.  The exchange uses
+    // device-coherent (sc1) stores and loads and a relaxed device-scope counter, ordered by waiting for the stores
+    // to complete: no L2 write-back / invalidate as a release-acquire fence pair would cost on every workgroup. ----
+    constexpr int PSTRIDE = QBP * 32 * D;                     // floats of O per (b, h, split)
+    constexpr int COHERENT = 16;                              // cache policy bits of the buffer ops: sc1
+    if (kg == 0) {
+        float *po = p.part_o + ((bh * p.SP + s) * (int64_t)PSTRIDE) + qb * 32 * D;
+        const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(po, 0, 32 * D * 4, 0x00020000);
 #pragma unroll
         for (int cb = 0; cb < C::CB; ++cb)
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                f32x4_t v;
+                u32x4_t v;
 #pragma unroll
-                for (int e = 0; e < 4; ++e) v[e] = oacc[cb][4 * j + e];
-                *(f32x4_t *)(po + cb * 32 + 8 * j + 4 * g) = v;
+                for (int e = 0; e < 4; ++e) v[e] = __float_as_uint(qs.o[cb][4 * j + e]);
+                __builtin_amdgcn_raw_buffer_store_b128(v, rs, (((cb * 4 + j) * 2 + g) * 32 + ln) * 16, 0, COHERENT);
             }
         if (g == 0) {
-            p.part_m[prow] = m_ref;
-            p.part_l[prow] = l_tot;
+            const int64_t prow = (bh * p.SP + s) * (QBP * 32) + qb * 32 + ln;
+            __hip_atomic_store(p.part_m + prow, qs.m_ref, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(p.part_l + prow, l_tot, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
     }
+    MCSD_WAIT_VMCNT(0);                                    // this wavefront's partials have reached memory
+    __syncthreads();
+    if (tid == 0) {
+        const int old = __hip_atomic_fetch_add(&p.counters[bh], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const int last = old == n_active - 1;
+        if (last) __hip_atomic_store(&p.counters[bh], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // zero for the next call
+        s_last = last;
+    }
+    __syncthreads();
+    if (!s_last || kg != 0) return;
+    // fold all partials in split order, this workgroup's own included: the result does not depend on which
+    // workgroup happened to arrive last
+    qs.m_ref = -INFINITY;
+    l_tot = 0.f;
+#pragma unroll
+    for (int cb = 0; cb < C::CB; ++cb) qs.o[cb] = (f32x16_t){0};
+#pragma unroll 1
+    for (int sp = 0; sp < n_active; ++sp) {
+        const int64_t prow = (bh * p.SP + sp) * (QBP * 32) + qb * 32 + ln;
+        const float m_k = __hip_atomic_load(p.part_m + prow, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const float l_k = __hip_atomic_load(p.part_l + prow, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const float *po = p.part_o + ((bh * p.SP + sp) * (int64_t)PSTRIDE) + qb * 32 * D;
+        const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(po), 0, 32 * D * 4, 0x00020000);
+        const float m_new = fmaxf(qs.m_ref, m_k);
+        const bool any = m_new != -INFINITY;                  // false: neither side has seen a key
+        const float a = any ? fast_exp2((qs.m_ref - m_new) * p.c) : 1.f, bsc = any ? fast_exp2((m_k - m_new) * p.c) : 0.f;
+        qs.m_ref = m_new;
+        l_tot = l_tot * a + l_k * bsc;
+#pragma unroll
+        for (int cb = 0; cb < C::CB; ++cb)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const u32x4_t v = __builtin_amdgcn_raw_buffer_load_b128(rs, (((cb * 4 + j) * 2 + g) * 32 + ln) * 16, 0, COHERENT);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) qs.o[cb][4 * j + e] = qs.o[cb][4 * j + e] * a + __uint_as_float(v[e]) * bsc;
+            }
+    }
+    store_out();
 }
 
 // ---------------------------------------------------------------------------------------------------
@@ -546,29 +782,44 @@ __global__ __launch_bounds__(256) void tree_attn_merge_kernel(const AttnParams p
     }
 }
 
-size_t workspace_bytes_for(const AttnPlan &pl, int B, int H, int d, int n)
+
+__global__ void fill_zero_kernel(uint32_t *p, size_t n)
 {
-    if (pl.SP == 1) return 0;
-    const size_t rows = (size_t)B * H * pl.SP * n;
-    size_t bytes = rows * d * sizeof(float);
-    bytes = (bytes + 255) & ~(size_t)255;
-    bytes += 2 * ((rows * sizeof(float) + 255) & ~(size_t)255);
-    return bytes;
+    size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (; i < n; i += stride) p[i] = 0u;
+}
+
+size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+// workspace: [counters int32 B*H] [part_m] [part_l] [part_o]; counters are always present
+size_t partial_rows(const AttnPlan &pl, int dtype, int B, int H, int n)
+{
+    // bf16 path: whole 32-row query blocks in register-fragment order; fp32 path: n rows
+    return (size_t)B * H * pl.S * (dtype == MCSD_BF16 ? (size_t)pl.QBP * 32 : (size_t)n);
+}
+
+size_t workspace_bytes_for(const AttnPlan &pl, int dtype, int B, int H, int d, int n)
+{
+    size_t bytes = align256(sizeof(int32_t) * (size_t)B * H);
+    if (pl.S == 1) return bytes;
+    const size_t rows = partial_rows(pl, dtype, B, H, n);
+    return bytes + 2 * align256(rows * sizeof(float)) + align256(rows * d * sizeof(float));
+}
+
+template <int D, int QBP, int NS>
+void launch_sweep(const AttnParams &p, const AttnPlan &pl, hipStream_t st)
+{
+    const dim3 grid((unsigned)((size_t)pl.S * p.H * p.B));
+    mcsd_launch(MCSD_KERNEL_ATTN_SWEEP, tree_attn_bf16_kernel<D, QBP, NS>, grid, dim3(SweepCfg<D, QBP, NS>::THREADS), st, p);
 }
 
 template <int D>
 hipError_t launch_bf16(const AttnParams &p, const AttnPlan &pl, hipStream_t st)
 {
-    dim3 grid(pl.S, p.H, p.B), block(256);
-    switch (pl.QB) {
-    case 1: mcsd_launch(MCSD_KERNEL_ATTN_SWEEP, tree_attn_bf16_kernel<D, 1>, grid, block, st, p); break;
-    case 2: mcsd_launch(MCSD_KERNEL_ATTN_SWEEP, tree_attn_bf16_kernel<D, 2>, grid, block, st, p); break;
-    case 3: mcsd_launch(MCSD_KERNEL_ATTN_SWEEP, tree_attn_bf16_kernel<D, 3>, grid, block, st, p); break;
-    default: mcsd_launch(MCSD_KERNEL_ATTN_SWEEP, tree_attn_bf16_kernel<D, 4>, grid, block, st, p); break;
-    }
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess || pl.SP == 1) return e;
-    mcsd_launch(MCSD_KERNEL_ATTN_MERGE, tree_attn_merge_kernel<D, true>, dim3((p.n + 1024 / D - 1) / (1024 / D), p.H, p.B), block, st, p, pl.T, pl.KG);
+    if (pl.QBP == 1) launch_sweep<D, 1, 2>(p, pl, st);
+    else if (pl.QBP == 2) { if (pl.NS == 4) launch_sweep<D, 2, 4>(p, pl, st); else launch_sweep<D, 2, 2>(p, pl, st); }
+    else { if (pl.NS == 4) launch_sweep<D, 4, 4>(p, pl, st); else launch_sweep<D, 4, 2>(p, pl, st); }
     return hipGetLastError();
 }
 
@@ -578,8 +829,8 @@ hipError_t launch_f32(const AttnParams &p, const AttnPlan &pl, hipStream_t st)
     dim3 grid(pl.S, p.H, p.B), block(256);
     mcsd_launch(MCSD_KERNEL_ATTN_SWEEP, tree_attn_f32_kernel<D>, grid, block, st, p);
     hipError_t e = hipGetLastError();
-    if (e != hipSuccess || pl.SP == 1) return e;
-    mcsd_launch(MCSD_KERNEL_ATTN_MERGE, tree_attn_merge_kernel<D, false>, dim3((p.n + 1024 / D - 1) / (1024 / D), p.H, p.B), block, st, p, pl.T, pl.KG);
+    if (e != hipSuccess || pl.S == 1) return e;
+    mcsd_launch(MCSD_KERNEL_ATTN_MERGE, tree_attn_merge_kernel<D, false>, dim3((p.n + 1024 / D - 1) / (1024 / D), p.H, p.B), block, st, p, pl.T, 1);
     return hipGetLastError();
 }
 
@@ -592,8 +843,18 @@ extern "C" size_t mcsd_tree_attention_workspace(int32_t B, int32_t H, int32_t d,
     // the larger of the two dtypes' needs, so one buffer serves both
     const AttnPlan a = make_plan(MCSD_BF16, B, H, n_nodes, max_prefix);
     const AttnPlan f = make_plan(MCSD_F32, B, H, n_nodes, max_prefix);
-    const size_t wa = workspace_bytes_for(a, B, H, d, n_nodes), wf = workspace_bytes_for(f, B, H, d, n_nodes);
+    const size_t wa = workspace_bytes_for(a, MCSD_BF16, B, H, d, n_nodes), wf = workspace_bytes_for(f, MCSD_F32, B, H, d, n_nodes);
     return wa > wf ? wa : wf;
+}
+
+extern "C" int mcsd_workspace_init(void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    if (!workspace || ((uintptr_t)workspace & 255) || (workspace_bytes & 3)) return MCSD_EINVAL;
+    if (workspace_bytes == 0) return MCSD_OK;
+    const size_t n = workspace_bytes / 4;
+    const unsigned blocks = (unsigned)((n + 255) / 256 < 4096 ? (n + 255) / 256 : 4096);
+    hipLaunchKernelGGL(fill_zero_kernel, dim3(blocks), dim3(256), 0, (hipStream_t)hip_stream, (uint32_t *)workspace, n);
+    return mcsd_hip_status(hipGetLastError());
 }
 
 extern "C" int mcsd_tree_attention(const mcsd_mask_view_t *mask, mcsd_dtype_t dtype, int32_t B, int32_t H, int32_t d,
@@ -613,15 +874,14 @@ extern "C" int mcsd_tree_attention(const mcsd_mask_view_t *mask, mcsd_dtype_t dt
     if (!(softmax_scale > 0.f) || !isfinite(softmax_scale)) return MCSD_EINVAL;
     if (d != 64 && d != 128) return MCSD_EUNSUPPORTED;
     if (n > MCSD_ATTN_MAX_NODES) return MCSD_EUNSUPPORTED;
-    if (mask->words_per_row > 2 && n > 128) return MCSD_EUNSUPPORTED;
     const uintptr_t align = (uintptr_t)q | (uintptr_t)k_tree | (uintptr_t)v_tree | (uintptr_t)out |
                             (uintptr_t)k_prefix | (uintptr_t)v_prefix;
     if (align & 15) return MCSD_EINVAL;
     if (((node_stride * d) & 7) || (head_stride & 7)) return MCSD_EINVAL;
 
     const AttnPlan pl = make_plan(dtype, B, H, n, max_prefix);
-    const size_t need = workspace_bytes_for(pl, B, H, d, n);
-    if (need > 0 && (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 255))) return MCSD_EWORKSPACE;
+    const size_t need = workspace_bytes_for(pl, dtype, B, H, d, n);
+    if (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 255)) return MCSD_EWORKSPACE;
 
     AttnParams p;
     p.q = q; p.kt = k_tree; p.vt = v_tree; p.kp = k_prefix; p.vp = v_prefix; p.out = out;
@@ -630,15 +890,19 @@ extern "C" int mcsd_tree_attention(const mcsd_mask_view_t *mask, mcsd_dtype_t dt
     p.B = B; p.H = H; p.n = n; p.max_prefix = max_prefix;
     p.node_stride = node_stride; p.head_stride = head_stride;
     p.c = softmax_scale * 1.4426950408889634f;
-    p.S = pl.S; p.SP = pl.SP;
+    p.S = pl.S; p.SP = pl.S;
+    p.dbg = getenv("MCSD_DBG") ? atoi(getenv("MCSD_DBG")) : 0;
+    char *w = (char *)workspace;
+    p.counters = (int32_t *)w;
+    w += align256(sizeof(int32_t) * (size_t)B * H);
     p.part_o = p.part_m = p.part_l = nullptr;
-    if (need > 0) {
-        const size_t rows = (size_t)B * H * pl.SP * n;
-        const size_t o_bytes = (rows * d * sizeof(float) + 255) & ~(size_t)255;
-        const size_t r_bytes = (rows * sizeof(float) + 255) & ~(size_t)255;
-        p.part_o = (float *)workspace;
-        p.part_m = (float *)((char *)workspace + o_bytes);
-        p.part_l = (float *)((char *)workspace + o_bytes + r_bytes);
+    if (pl.S > 1) {
+        const size_t rows = partial_rows(pl, dtype, B, H, n);
+        p.part_m = (float *)w;
+        w += align256(rows * sizeof(float));
+        p.part_l = (float *)w;
+        w += align256(rows * sizeof(float));
+        p.part_o = (float *)w;
     }
     hipStream_t st = (hipStream_t)hip_stream;
     hipError_t e;
