@@ -71,7 +71,6 @@ class Step:
         self.n = self.view.n_nodes
         ws_bytes = binding.tree_attention_workspace(w.B, w.H, w.d, self.n, self.cap)
         self.ws = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device="cuda")
-        binding.workspace_init(self.ws)
         vi = self.vi
         self.p, self.q = H.dev(vi["p_target"]), H.dev(vi["q_draft"])
         self.tokens, self.ua, self.us = H.dev(vi["tokens"]), H.dev(vi["u_accept"]), H.dev(vi["u_sample"])
@@ -238,6 +237,8 @@ def main():
     value = w.B * st.n / (ms_per_step * 1e-3)
 
     roof = roofline_of(st, hip, args.kernel_reps)
+    m_avg = time_kernel(st, hip, binding.KERNEL_ATTN_MERGE, lambda i: st.attention(i), args.kernel_reps)[0] \
+        if st.ws.numel() > 256 else 0.0
     v_avg = time_kernel(st, hip, binding.KERNEL_VERIFY_WALK, lambda i: st.verify(), args.kernel_reps)[0]
     out = {
         "metric": "verified tree-tokens/s, whole verification step (32 tree-attention layers + acceptance)",
@@ -250,7 +251,8 @@ def main():
                    "layers_per_step": N_LAYERS, "kv_sets": n_sets, "verified_vs_oracle": True,
                    "mean_accept_len": round(alpha, 3)},
         "roofline": roof,
-        "kernels_us": {"attn_sweep": roof["avg_launch_us"], "verify_walk": round(v_avg * 1e3, 2)},
+        "kernels_us": {"attn_sweep": roof["avg_launch_us"], "attn_merge": round(m_avg * 1e3, 2),
+                       "verify_walk": round(v_avg * 1e3, 2)},
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(st)

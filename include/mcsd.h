@@ -104,17 +104,12 @@ void mcsd_free_mask(mcsd_mask_t *mask);
  *                          MCSD_F32: fp32 end to end on the vector ALU.
  * Limits: d in {64, 128}; 1 <= n_nodes <= MCSD_ATTN_MAX_NODES; softmax_scale finite and > 0; all tensor
  * base addresses 16-byte aligned; node_stride*d and head_stride and seq_base multiples of 8 elements.
- * workspace: DEVICE, at least mcsd_tree_attention_workspace(...) bytes (never 0), 256-byte aligned.  It holds one
- * arrival counter per (sequence, head) and the partial results of the key splits.  The counters must be zero
- * when a call starts and every call leaves them zero again: clear the buffer ONCE after allocating it, with
- * mcsd_workspace_init() or any zero fill, and again only if a call was abandoned mid-flight.  The partial results
- * need no initialisation.  Calls that share a workspace must be ordered on one stream.  Inputs are never modified.
+ * workspace: DEVICE, at least mcsd_tree_attention_workspace(...) bytes (0 when the keys are not split: then it may
+ * be NULL), 256-byte aligned; holds the partial results of the key splits; contents need not be initialised and
+ * are not meaningful afterwards.  Calls that share a workspace must be ordered on one stream.  Inputs are never
+ * modified.
  * ------------------------------------------------------------------------------------------------- */
 size_t mcsd_tree_attention_workspace(int32_t B, int32_t H, int32_t d, int32_t n_nodes, int32_t max_prefix);
-
-/* Zero-fills a workspace with a small kernel on hip_stream (safe under stream capture).  workspace: DEVICE,
- * 256-byte aligned; workspace_bytes a multiple of 4. */
-int mcsd_workspace_init(void *workspace, size_t workspace_bytes, void *hip_stream);
 
 int mcsd_tree_attention(const mcsd_mask_view_t *mask, mcsd_dtype_t dtype, int32_t B, int32_t H, int32_t d,
                         const void *q, const void *k_tree, const void *v_tree, int64_t node_stride,

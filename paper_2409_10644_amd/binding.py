@@ -15,7 +15,7 @@ MCSD_F32, MCSD_BF16 = 0, 1
 MCSD_DRAFT_INIT, MCSD_TARGET_INIT = 0, 1
 
 EXPORTS = ["mcsd_strerror", "mcsd_build_mask", "mcsd_slice_mask", "mcsd_free_mask",
-           "mcsd_tree_attention_workspace", "mcsd_workspace_init", "mcsd_tree_attention",
+           "mcsd_tree_attention_workspace", "mcsd_tree_attention",
            "mcsd_verify_tree_workspace", "mcsd_verify_tree", "mcsd_profile_next"]
 
 
@@ -56,8 +56,6 @@ def _load() -> C.CDLL:
     lib.mcsd_free_mask.argtypes = [vp]
     lib.mcsd_tree_attention_workspace.restype = sz
     lib.mcsd_tree_attention_workspace.argtypes = [i32, i32, i32, i32, i32]
-    lib.mcsd_workspace_init.restype = C.c_int
-    lib.mcsd_workspace_init.argtypes = [vp, sz, vp]
     lib.mcsd_tree_attention.restype = C.c_int
     lib.mcsd_tree_attention.argtypes = [C.POINTER(MaskView), C.c_int, i32, i32, i32, vp, vp, vp, i64, vp, vp, vp,
                                         vp, i64, i32, C.c_float, vp, vp, sz, vp]
@@ -135,11 +133,6 @@ def free_mask(mask: Mask) -> None:
 
 def tree_attention_workspace(B: int, H: int, d: int, n_nodes: int, max_prefix: int) -> int:
     return int(lib.mcsd_tree_attention_workspace(B, H, d, n_nodes, max_prefix))
-
-
-def workspace_init(workspace: torch.Tensor, stream=None) -> None:
-    _check(lib.mcsd_workspace_init(_ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream)),
-           "mcsd_workspace_init")
 
 
 def tree_attention(view: MaskView, dtype: int, B: int, H: int, d: int, q: torch.Tensor, k_tree: torch.Tensor,

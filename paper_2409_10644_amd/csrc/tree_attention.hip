@@ -12,7 +12,7 @@
 // and the exponentiated scores are already in the register layout of the B operand of O^T += V^T * P^T.
 // V^T operands come from the row-major V tile through the LDS transpose load (ds_read_b64_tr_b16).
 // Wavefronts that share a query block split each tile's keys (key groups) and are merged through LDS at the
-// end; key splits across workgroups are merged by the last workgroup to finish (a counter per (sequence, head)).
+// end; key splits across workgroups write partial results that a small second kernel folds.
 // The tree's own keys are extra tiles whose scores are masked with the packed bitmask slice.
 //
 // fp32 path: split / online-softmax structure on the vector ALU (small reference-precision shapes).
@@ -44,8 +44,8 @@ struct AttnParams {
     int64_t node_stride, head_stride;
     float c;          // softmax_scale * log2(e)
     int32_t S;        // key splits
+    int32_t tps;      // tiles per split (bf16 sweep): split s owns tiles [s*tps, (s+1)*tps) of every sequence
     int32_t SP;       // partial results per (b,h) (== S)
-    int32_t *counters; // [B*H] arrivals of the key splits; zero between calls
     float *part_o;    // [B*H][SP][n][D]
     float *part_m;    // [B*H][SP][n]   reference maximum of the raw scores
     float *part_l;    // [B*H][SP][n]   sum of exp2((s - m) * c)
@@ -74,16 +74,11 @@ AttnPlan make_plan(int dtype, int B, int H, int n, int max_prefix)
     }
     const long bh = (long)B * H;
     const long tiles_max = (max_prefix + pl.T - 1) / pl.T;
-    long S;
-    if (dtype == MCSD_BF16) {
-        // Splitting the keys of one (sequence, head) over several workgroups costs a round trip through memory
-        // (about 10 us): only worth it when a workgroup would otherwise sweep more than 64 tiles.
-        S = (512 + bh - 1) / bh;                            // two workgroups per compute unit
-        if (S > tiles_max / 64) S = tiles_max / 64;
-    } else {
-        S = (512 + bh - 1) / bh;
-        if (S > tiles_max) S = tiles_max;
-    }
+    // Key splits: enough workgroups for two per compute unit, at least two tiles per split, at most 8 splits
+    // (every split costs a partial result of QBP*32 rows and the second kernel has to fold them).
+    long S = (512 + bh - 1) / bh;
+    if (S > tiles_max / 2) S = tiles_max / 2;
+    if (dtype == MCSD_BF16 && S > 8) S = 8;
     if (S < 1) S = 1;
     if (S > 64) S = 64;
     if (const char *ov = getenv("MCSD_ATTN_SPLITS")) {      // tuning override: number of key splits
@@ -303,10 +298,9 @@ void tree_attn_bf16_kernel(const AttnParams p)
 {
     using C = SweepCfg<D, QBP, NS>;
     __shared__ __attribute__((aligned(1024))) unsigned char ring[C::LDS_BYTES];
-    __shared__ int s_last;
 
     // Workgroup ids are dealt round-robin to the 8 XCDs: renumber so that the key splits of one (sequence, head),
-    // which meet again in the final merge, run on one XCD and share its L2.
+    // which read the same Q, tree K/V and mask rows and write neighbouring partial results, share one XCD's L2.
     const int total = gridDim.x;
     int wg = blockIdx.x;
     if ((total & 7) == 0) wg = (wg & 7) * (total >> 3) + (wg >> 3);
@@ -321,12 +315,12 @@ void tree_attn_bf16_kernel(const AttnParams p)
     int L = p.lens[b];
     L = L < 0 ? 0 : (L > p.max_prefix ? p.max_prefix : L);
     const int tiles_b = (L + C::T - 1) / C::T;
-    const int tps = (tiles_b + p.S - 1) / p.S;
+    const int tps = p.tps;                                  // fixed per call: short sequences use fewer splits
     const int t0 = min(s * tps, tiles_b), t1 = min(t0 + tps, tiles_b);
     const int n_tree_tiles = s == 0 ? (p.n + C::T - 1) / C::T : 0;
     const int n_pre = t1 - t0;
-    if (n_pre + n_tree_tiles == 0) return;                  // this split has no keys; it is not counted either
-    const int n_active = tps > 0 ? min(p.S, (tiles_b + tps - 1) / tps) : 1;   // splits that run for this sequence
+    if (n_pre + n_tree_tiles == 0) return;                  // this split has no keys
+    const int n_active = max(1, (tiles_b + tps - 1) / tps);  // splits that run for this sequence (<= S)
     // leading tiles of this split that are full (only the sequence's last tile can be ragged)
     const int n_hot = (n_pre > 0 && t1 * C::T > L) ? n_pre - 1 : n_pre;
 
@@ -534,73 +528,69 @@ void tree_attn_bf16_kernel(const AttnParams p)
                 *(bf16x4_t *)(o + cb * 32 + 8 * j + 4 * g) = v;
             }
     };
-    if (p.S == 1) {
+    if (n_active == 1) {                                   // the only split of this sequence: no exchange needed
         if (kg == 0) store_out();
         return;
     }
 
-    // ---- key splits: every split publishes (O, m, l) in register-fragment order (fully coalesced); the last
-    // workgroup to arrive for this (sequence, head) folds all of them and writes the output.  The exchange uses
-    // device-coherent (sc1) stores and loads and a relaxed device-scope counter, ordered by waiting for the stores
-    // to complete: no L2 write-back / invalidate as a release-acquire fence pair would cost on every workgroup. ----
-    constexpr int PSTRIDE = QBP * 32 * D;                     // floats of O per (b, h, split)
-    constexpr int COHERENT = 16;                              // cache policy bits of the buffer ops: sc1
+    // ---- key splits: every split writes (O, m, l) in register-fragment order (fully coalesced); a small second
+    // kernel folds them (a kernel boundary is the cheapest device-wide hand-over for this little data) ----
     if (kg == 0) {
-        float *po = p.part_o + ((bh * p.SP + s) * (int64_t)PSTRIDE) + qb * 32 * D;
-        const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(po, 0, 32 * D * 4, 0x00020000);
+        float *po = p.part_o + ((bh * p.SP + s) * (int64_t)(QBP * 32 * D)) + qb * 32 * D;
 #pragma unroll
         for (int cb = 0; cb < C::CB; ++cb)
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                u32x4_t v;
+                f32x4_t v;
 #pragma unroll
-                for (int e = 0; e < 4; ++e) v[e] = __float_as_uint(qs.o[cb][4 * j + e]);
-                __builtin_amdgcn_raw_buffer_store_b128(v, rs, (((cb * 4 + j) * 2 + g) * 32 + ln) * 16, 0, COHERENT);
+                for (int e = 0; e < 4; ++e) v[e] = qs.o[cb][4 * j + e];
+                *(f32x4_t *)(po + (((cb * 4 + j) * 2 + g) * 32 + ln) * 4) = v;
             }
         if (g == 0) {
             const int64_t prow = (bh * p.SP + s) * (QBP * 32) + qb * 32 + ln;
-            __hip_atomic_store(p.part_m + prow, qs.m_ref, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            __hip_atomic_store(p.part_l + prow, l_tot, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            p.part_m[prow] = qs.m_ref;
+            p.part_l[prow] = l_tot;
         }
     }
-    MCSD_WAIT_VMCNT(0);                                    // this wavefront's partials have reached memory
-    __syncthreads();
-    if (tid == 0) {
-        const int old = __hip_atomic_fetch_add(&p.counters[bh], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        const int last = old == n_active - 1;
-        if (last) __hip_atomic_store(&p.counters[bh], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // zero for the next call
-        s_last = last;
-    }
-    __syncthreads();
-    if (!s_last || kg != 0) return;
-    // fold all partials in split order, this workgroup's own included: the result does not depend on which
-    // workgroup happened to arrive last
-    qs.m_ref = -INFINITY;
-    l_tot = 0.f;
-#pragma unroll
-    for (int cb = 0; cb < C::CB; ++cb) qs.o[cb] = (f32x16_t){0};
-#pragma unroll 1
+}
+
+// Folds the partial results of the key splits of the bf16 sweep.  One thread per 4 output columns of one query;
+// fragment order makes the loads of a wavefront contiguous.  Partials are folded in split order.
+template <int D, int QBP>
+__global__ __launch_bounds__(256) void tree_attn_merge_bf16_kernel(const AttnParams p, int T)
+{
+    constexpr int POS = D * 8;                                // float4 positions per (b, h, query block)
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int pos = (int)(idx % POS);
+    const int qb = (int)((idx / POS) % QBP);
+    const int64_t bh = idx / ((int64_t)POS * QBP);
+    if (bh >= (int64_t)p.B * p.H) return;
+    const int ln = pos & 31, g = (pos >> 5) & 1, f = pos >> 6;
+    const int row = qb * 32 + ln;
+    if (row >= p.n) return;
+    int L = p.lens[bh / p.H];
+    L = L < 0 ? 0 : (L > p.max_prefix ? p.max_prefix : L);
+    const int tiles_b = (L + T - 1) / T;
+    const int n_active = max(1, (tiles_b + p.tps - 1) / p.tps);
+    if (n_active == 1) return;                                // the sweep wrote this sequence's output itself
+    float M = -INFINITY;
+    for (int sp = 0; sp < n_active; ++sp) M = fmaxf(M, p.part_m[(bh * p.SP + sp) * (QBP * 32) + row]);
+    float den = 0.f;
+    f32x4_t num = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll 4
     for (int sp = 0; sp < n_active; ++sp) {
-        const int64_t prow = (bh * p.SP + sp) * (QBP * 32) + qb * 32 + ln;
-        const float m_k = __hip_atomic_load(p.part_m + prow, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        const float l_k = __hip_atomic_load(p.part_l + prow, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        const float *po = p.part_o + ((bh * p.SP + sp) * (int64_t)PSTRIDE) + qb * 32 * D;
-        const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(po), 0, 32 * D * 4, 0x00020000);
-        const float m_new = fmaxf(qs.m_ref, m_k);
-        const bool any = m_new != -INFINITY;                  // false: neither side has seen a key
-        const float a = any ? fast_exp2((qs.m_ref - m_new) * p.c) : 1.f, bsc = any ? fast_exp2((m_k - m_new) * p.c) : 0.f;
-        qs.m_ref = m_new;
-        l_tot = l_tot * a + l_k * bsc;
-#pragma unroll
-        for (int cb = 0; cb < C::CB; ++cb)
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const u32x4_t v = __builtin_amdgcn_raw_buffer_load_b128(rs, (((cb * 4 + j) * 2 + g) * 32 + ln) * 16, 0, COHERENT);
-#pragma unroll
-                for (int e = 0; e < 4; ++e) qs.o[cb][4 * j + e] = qs.o[cb][4 * j + e] * a + __uint_as_float(v[e]) * bsc;
-            }
+        const int64_t prow = (bh * p.SP + sp) * (QBP * 32) + row;
+        const float w = fast_exp2((p.part_m[prow] - M) * p.c);   // exp2(-inf) = 0 for a split that saw no visible key
+        const f32x4_t o = *(const f32x4_t *)(p.part_o + ((bh * p.SP + sp) * (int64_t)(QBP * 32 * D)) + qb * 32 * D + pos * 4);
+        den = fmaf(w, p.part_l[prow], den);
+        num += w * o;
     }
-    store_out();
+    const f32x4_t r = num / den;
+    bf16x4_t v;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) v[e] = (__bf16)r[e];
+    const int c = (f / 4) * 32 + 8 * (f % 4) + 4 * g;
+    *(bf16x4_t *)((__bf16 *)p.out + (bh * p.node_stride + row) * D + c) = v;
 }
 
 // ---------------------------------------------------------------------------------------------------
@@ -783,16 +773,9 @@ __global__ __launch_bounds__(256) void tree_attn_merge_kernel(const AttnParams p
 }
 
 
-__global__ void fill_zero_kernel(uint32_t *p, size_t n)
-{
-    size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x;
-    const size_t stride = (size_t)gridDim.x * blockDim.x;
-    for (; i < n; i += stride) p[i] = 0u;
-}
-
 size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
-// workspace: [counters int32 B*H] [part_m] [part_l] [part_o]; counters are always present
+// workspace: [part_m] [part_l] [part_o]; nothing when the keys are not split
 size_t partial_rows(const AttnPlan &pl, int dtype, int B, int H, int n)
 {
     // bf16 path: whole 32-row query blocks in register-fragment order; fp32 path: n rows
@@ -801,10 +784,9 @@ size_t partial_rows(const AttnPlan &pl, int dtype, int B, int H, int n)
 
 size_t workspace_bytes_for(const AttnPlan &pl, int dtype, int B, int H, int d, int n)
 {
-    size_t bytes = align256(sizeof(int32_t) * (size_t)B * H);
-    if (pl.S == 1) return bytes;
+    if (pl.S == 1) return 0;
     const size_t rows = partial_rows(pl, dtype, B, H, n);
-    return bytes + 2 * align256(rows * sizeof(float)) + align256(rows * d * sizeof(float));
+    return 2 * align256(rows * sizeof(float)) + align256(rows * d * sizeof(float));
 }
 
 template <int D, int QBP, int NS>
@@ -814,12 +796,24 @@ void launch_sweep(const AttnParams &p, const AttnPlan &pl, hipStream_t st)
     mcsd_launch(MCSD_KERNEL_ATTN_SWEEP, tree_attn_bf16_kernel<D, QBP, NS>, grid, dim3(SweepCfg<D, QBP, NS>::THREADS), st, p);
 }
 
+template <int D, int QBP>
+void launch_merge(const AttnParams &p, const AttnPlan &pl, hipStream_t st)
+{
+    const size_t threads = (size_t)p.B * p.H * QBP * D * 8;
+    mcsd_launch(MCSD_KERNEL_ATTN_MERGE, tree_attn_merge_bf16_kernel<D, QBP>, dim3((unsigned)((threads + 255) / 256)), dim3(256), st, p, pl.T);
+}
+
 template <int D>
 hipError_t launch_bf16(const AttnParams &p, const AttnPlan &pl, hipStream_t st)
 {
     if (pl.QBP == 1) launch_sweep<D, 1, 2>(p, pl, st);
     else if (pl.QBP == 2) { if (pl.NS == 4) launch_sweep<D, 2, 4>(p, pl, st); else launch_sweep<D, 2, 2>(p, pl, st); }
     else { if (pl.NS == 4) launch_sweep<D, 4, 4>(p, pl, st); else launch_sweep<D, 4, 2>(p, pl, st); }
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || pl.S == 1) return e;
+    if (pl.QBP == 1) launch_merge<D, 1>(p, pl, st);
+    else if (pl.QBP == 2) launch_merge<D, 2>(p, pl, st);
+    else launch_merge<D, 4>(p, pl, st);
     return hipGetLastError();
 }
 
@@ -847,16 +841,6 @@ extern "C" size_t mcsd_tree_attention_workspace(int32_t B, int32_t H, int32_t d,
     return wa > wf ? wa : wf;
 }
 
-extern "C" int mcsd_workspace_init(void *workspace, size_t workspace_bytes, void *hip_stream)
-{
-    if (!workspace || ((uintptr_t)workspace & 255) || (workspace_bytes & 3)) return MCSD_EINVAL;
-    if (workspace_bytes == 0) return MCSD_OK;
-    const size_t n = workspace_bytes / 4;
-    const unsigned blocks = (unsigned)((n + 255) / 256 < 4096 ? (n + 255) / 256 : 4096);
-    hipLaunchKernelGGL(fill_zero_kernel, dim3(blocks), dim3(256), 0, (hipStream_t)hip_stream, (uint32_t *)workspace, n);
-    return mcsd_hip_status(hipGetLastError());
-}
-
 extern "C" int mcsd_tree_attention(const mcsd_mask_view_t *mask, mcsd_dtype_t dtype, int32_t B, int32_t H, int32_t d,
                                    const void *q, const void *k_tree, const void *v_tree, int64_t node_stride,
                                    const void *k_prefix, const void *v_prefix, const int64_t *seq_base_dev,
@@ -881,7 +865,7 @@ extern "C" int mcsd_tree_attention(const mcsd_mask_view_t *mask, mcsd_dtype_t dt
 
     const AttnPlan pl = make_plan(dtype, B, H, n, max_prefix);
     const size_t need = workspace_bytes_for(pl, dtype, B, H, d, n);
-    if (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 255)) return MCSD_EWORKSPACE;
+    if (need > 0 && (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 255))) return MCSD_EWORKSPACE;
 
     AttnParams p;
     p.q = q; p.kt = k_tree; p.vt = v_tree; p.kp = k_prefix; p.vp = v_prefix; p.out = out;
@@ -891,10 +875,10 @@ extern "C" int mcsd_tree_attention(const mcsd_mask_view_t *mask, mcsd_dtype_t dt
     p.node_stride = node_stride; p.head_stride = head_stride;
     p.c = softmax_scale * 1.4426950408889634f;
     p.S = pl.S; p.SP = pl.S;
+    p.tps = (int32_t)((((int64_t)max_prefix + pl.T - 1) / pl.T + pl.S - 1) / pl.S);
+    if (p.tps < 1) p.tps = 1;
     p.dbg = getenv("MCSD_DBG") ? atoi(getenv("MCSD_DBG")) : 0;
     char *w = (char *)workspace;
-    p.counters = (int32_t *)w;
-    w += align256(sizeof(int32_t) * (size_t)B * H);
     p.part_o = p.part_m = p.part_l = nullptr;
     if (pl.S > 1) {
         const size_t rows = partial_rows(pl, dtype, B, H, n);

@@ -55,38 +55,67 @@ __device__ inline double residual_at(const float *prow, const float *qrow, const
 }
 
 // Builds heapB for the distribution (prow, qrow, rounds) and returns its total.  All threads call it.
+// A wavefront handles GROUP blocks of 256 elements at a time: all their loads are issued before any is used, and
+// the GROUP butterflies are independent instruction streams, so a round costs about one memory latency.
 __device__ double block_tree_sum(Shared &sh, const VerifyParams &P, const float *prow, const float *qrow,
                                  int rounds)
 {
+    constexpr int GROUP = 8;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const bool vec = (((uintptr_t)prow | (uintptr_t)qrow) & 15) == 0;
-    for (int blk = wave; blk < P.NB; blk += VT / 64) {
-        const int t0 = blk * BLK + lane * 4;
-        double v[4] = {0.0, 0.0, 0.0, 0.0};
-        if (vec && t0 + 3 < P.V) {
-            const float4 pv = *(const float4 *)(prow + t0);
-            float4 qv = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (rounds > 0) qv = *(const float4 *)(qrow + t0);
-            const float pe[4] = {pv.x, pv.y, pv.z, pv.w}, qe[4] = {qv.x, qv.y, qv.z, qv.w};
+    for (int blk0 = wave; blk0 < P.NB; blk0 += GROUP * (VT / 64)) {
+        float pe[GROUP][4], qe[GROUP][4];
+#pragma unroll
+        for (int k = 0; k < GROUP; ++k) {
+            const int blk = blk0 + k * (VT / 64);
+            const int t0 = blk * BLK + lane * 4;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) { pe[k][e] = 0.f; qe[k][e] = 0.f; }
+            if (blk < P.NB) {
+                if (vec && t0 + 3 < P.V) {
+                    const float4 pv = *(const float4 *)(prow + t0);
+                    pe[k][0] = pv.x; pe[k][1] = pv.y; pe[k][2] = pv.z; pe[k][3] = pv.w;
+                    if (rounds > 0) {
+                        const float4 qv = *(const float4 *)(qrow + t0);
+                        qe[k][0] = qv.x; qe[k][1] = qv.y; qe[k][2] = qv.z; qe[k][3] = qv.w;
+                    }
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        if (t0 + e < P.V) {
+                            pe[k][e] = prow[t0 + e];
+                            if (rounds > 0) qe[k][e] = qrow[t0 + e];
+                        }
+                }
+            }
+        }
+        double sblk[GROUP];
+#pragma unroll
+        for (int k = 0; k < GROUP; ++k) {
+            double v[4];
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                double r = (double)pe[e];
-                const double qd = (double)qe[e];
-                for (int k = 0; k < rounds; ++k) {
-                    const double d = __fma_rn(-sh.s_hist[k], qd, r);
+                double r = (double)pe[k][e];                 // elements beyond V are 0 and stay 0
+                const double qd = (double)qe[k][e];
+                for (int j = 0; j < rounds; ++j) {
+                    const double d = __fma_rn(-sh.s_hist[j], qd, r);
                     r = d > 0.0 ? d : 0.0;
                 }
                 v[e] = r;
             }
-        } else {
-#pragma unroll
-            for (int e = 0; e < 4; ++e)
-                if (t0 + e < P.V) v[e] = residual_at(prow, qrow, sh.s_hist, rounds, t0 + e);
+            sblk[k] = __dadd_rn(__dadd_rn(v[0], v[1]), __dadd_rn(v[2], v[3]));
         }
-        double s = __dadd_rn(__dadd_rn(v[0], v[1]), __dadd_rn(v[2], v[3]));
 #pragma unroll
-        for (int k = 1; k < 64; k <<= 1) s = __dadd_rn(s, __shfl_xor(s, k, 64));
-        if (lane == 0) sh.heapB[P.NB + blk] = s;
+        for (int m = 1; m < 64; m <<= 1)
+#pragma unroll
+            for (int k = 0; k < GROUP; ++k) sblk[k] = __dadd_rn(sblk[k], __shfl_xor(sblk[k], m, 64));
+        if (lane == 0) {
+#pragma unroll
+            for (int k = 0; k < GROUP; ++k) {
+                const int blk = blk0 + k * (VT / 64);
+                if (blk < P.NB) sh.heapB[P.NB + blk] = sblk[k];
+            }
+        }
     }
     __syncthreads();
     for (int n = P.NB >> 1; n >= 1; n >>= 1) {

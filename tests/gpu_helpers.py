@@ -41,7 +41,6 @@ def run_attention(binding, view, ad: AttnDevice, max_prefix: int | None = None, 
     mp = ad.max_prefix if max_prefix is None else max_prefix
     ws_bytes = binding.tree_attention_workspace(ad.B, ad.H, ad.d, n, mp)
     ws = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device="cuda")
-    binding.workspace_init(ws)                      # once per allocation: the arrival counters start at zero
     if fill is not None:
         ad.out.fill_(fill)
     binding.tree_attention(view, ad.code, ad.B, ad.H, ad.d, ad.q, ad.kt, ad.vt, ad.node_stride, ad.kp, ad.vp,

@@ -102,7 +102,6 @@ def test_device_entry_points_reject_bad_arguments_before_any_launch(binding):
     assert lib.mcsd_tree_attention_workspace(1, 32, 96, 44, 1024) == 0           # d not in {64,128}
     assert lib.mcsd_tree_attention_workspace(1, 32, 128, 129, 1024) == 0         # too many nodes
     assert lib.mcsd_tree_attention_workspace(1, 32, 128, 44, 1024) > 0
-    assert lib.mcsd_workspace_init(None, 256, None) == binding.MCSD_EINVAL
     st = lib.mcsd_verify_tree(C.byref(v), 0, 1, 32000, None, one, one, 45 * 32000, 29 * 32000, one, one, 1, one, one,
                               one, None, 0, None)
     assert st == binding.MCSD_EINVAL
