@@ -28,7 +28,9 @@ N_LAYERS = 32                   # Llama-2-7B
 
 # HBM traffic per launch of the sweep kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (bytes, already
 # scaled by the copy-kernel calibration); filled from the summaries under profiles/.  None = not measured.
-MEASURED_TRAFFIC = {}
+MEASURED_TRAFFIC = {   # profiles/tree_attn_hbm_traffic_pmc.md (sweep kernel: HBM read + written)
+    "cfg2": 26_680_000, "cfg4": 664_190_000, "cfg5": 2_222_700_000,
+}
 
 
 def log(*a):
@@ -206,6 +208,9 @@ def main():
     ap.add_argument("--extra", default="cfg4,cfg5", help="other workloads whose attention roofline is reported too")
     ap.add_argument("--kernel-reps", type=int, default=64)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--traffic-calibration", action="store_true",
+                    help="only run a 1 GiB device-to-device copy a few times (the known-size kernel that the "
+                         "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run are scaled by) and exit")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build measures one GPU only (the path shards by sequence and head without any "
@@ -213,6 +218,15 @@ def main():
     import torch
     assert torch.cuda.is_available(), "bench.py needs the MI355X"
     torch.cuda.set_device(0)
+    if args.traffic_calibration:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")      # 1 GiB read + 1 GiB written per copy
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibration": "3 device-to-device copies", "bytes_read_each": src.numel() * 4,
+                          "bytes_written_each": src.numel() * 4}))
+        return
     from paper_2409_10644_amd import binding
     hip = binding.HipRuntime()
 

@@ -49,7 +49,6 @@ struct AttnParams {
     float *part_o;    // [B*H][SP][n][D]
     float *part_m;    // [B*H][SP][n]   reference maximum of the raw scores
     float *part_l;    // [B*H][SP][n]   sum of exp2((s - m) * c)
-    int dbg;
 };
 
 struct AttnPlan {
@@ -877,7 +876,6 @@ extern "C" int mcsd_tree_attention(const mcsd_mask_view_t *mask, mcsd_dtype_t dt
     p.S = pl.S; p.SP = pl.S;
     p.tps = (int32_t)((((int64_t)max_prefix + pl.T - 1) / pl.T + pl.S - 1) / pl.S);
     if (p.tps < 1) p.tps = 1;
-    p.dbg = getenv("MCSD_DBG") ? atoi(getenv("MCSD_DBG")) : 0;
     char *w = (char *)workspace;
     p.part_o = p.part_m = p.part_l = nullptr;
     if (pl.S > 1) {
