@@ -1,7 +1,7 @@
 // Tree attention for gfx950 (Sec. 2.2 of arXiv 2409.10644): every node of the candidate tree attends
 // to the prefix KV cache and to its own ancestors under the topology-aware mask.
 //
-// bf16 path.  One workgroup of 8 wavefronts per compute unit owns one (sequence, head, key split).  The tree's
+// bf16 path.  One workgroup of 4 wavefronts (two workgroups per compute unit) owns one (sequence, head, key split).  The tree's
 // queries are cut into blocks of 32 rows; a wavefront keeps one block of Q in registers for the whole sweep.  K/V
 // tiles stream from HBM straight into a ring of LDS stages (global_load_lds, 16 bytes per lane, no registers
 // in between), several tiles ahead of the one being computed, so every K/V byte leaves HBM once and is used by
@@ -43,9 +43,10 @@ struct AttnParams {
     int32_t max_prefix;
     int64_t node_stride, head_stride;
     float c;          // softmax_scale * log2(e)
-    int32_t S;        // key splits
+    int32_t S;        // key splits of the prefix
+    int32_t G;        // workgroups per (b,h): S, plus one for the tree's own keys when the bf16 sweep splits the prefix
     int32_t tps;      // tiles per split (bf16 sweep): split s owns tiles [s*tps, (s+1)*tps) of every sequence
-    int32_t SP;       // partial results per (b,h) (== S)
+    int32_t SP;       // partial results per (b,h) (== G)
     float *part_o;    // [B*H][SP][n][D]
     float *part_m;    // [B*H][SP][n]   reference maximum of the raw scores
     float *part_l;    // [B*H][SP][n]   sum of exp2((s - m) * c)
@@ -54,8 +55,9 @@ struct AttnParams {
 struct AttnPlan {
     int QBP;   // query blocks of 32 rows, rounded up to 1, 2 or 4 (bf16 path)
     int T;     // keys per tile
-    int S;     // key splits
-    int NS;    // LDS stages of the bf16 sweep: 4 when one workgroup per compute unit suffices, else 2
+    int S;     // key splits of the prefix
+    int G;     // workgroups per (b,h): S, or S + 1 when the bf16 sweep gives the tree's own keys a workgroup of their own
+    int NS;    // LDS stages of the bf16 sweep
 };
 
 __host__ __device__ inline int tile_keys_bf16(int QBP) { return QBP == 1 ? 128 : 64; }   // == SweepCfg::T
@@ -73,10 +75,10 @@ AttnPlan make_plan(int dtype, int B, int H, int n, int max_prefix)
     }
     const long bh = (long)B * H;
     const long tiles_max = (max_prefix + pl.T - 1) / pl.T;
-    // Key splits: enough workgroups for two per compute unit, at least two tiles per split, at most 8 splits
-    // (every split costs a partial result of QBP*32 rows and the second kernel has to fold them).
+    // Key splits: enough workgroups for two per compute unit, at least four tiles per split, at most 8 splits
+    // (every split costs a partial result of n rows that is written, written back and folded by the second kernel).
     long S = (512 + bh - 1) / bh;
-    if (S > tiles_max / 2) S = tiles_max / 2;
+    if (S > tiles_max / 4) S = tiles_max / 4;
     if (dtype == MCSD_BF16 && S > 8) S = 8;
     if (S < 1) S = 1;
     if (S > 64) S = 64;
@@ -84,13 +86,15 @@ AttnPlan make_plan(int dtype, int B, int H, int n, int max_prefix)
         const long v = atol(ov);
         if (v >= 1 && v <= 64) S = v;
     }
-    // few workgroups: one per compute unit with a deep ring; many: two per compute unit with a double buffer
-    pl.NS = (dtype == MCSD_BF16 && pl.QBP > 1 && bh * S <= 256) ? 4 : 2;
+    pl.NS = 2;                                              // double buffer, two workgroups per compute unit
     if (const char *ov = getenv("MCSD_ATTN_STAGES")) {      // tuning override: 2 or 4 stages
         const long v = atol(ov);
         if ((v == 2 || v == 4) && pl.QBP > 1) pl.NS = (int)v;
     }
     pl.S = (int)S;
+    // With split keys the tree's own tiles (masked, through registers) would lengthen one split's critical path:
+    // they get a workgroup of their own, which costs one more partial result.
+    pl.G = (dtype == MCSD_BF16 && S > 1) ? (int)S + 1 : (int)S;
     return pl;
 }
 
@@ -303,8 +307,8 @@ void tree_attn_bf16_kernel(const AttnParams p)
     const int total = gridDim.x;
     int wg = blockIdx.x;
     if ((total & 7) == 0) wg = (wg & 7) * (total >> 3) + (wg >> 3);
-    const int s = wg % p.S;
-    const int bhi = wg / p.S;
+    const int s = wg % p.G;
+    const int bhi = wg / p.G;
     const int h = bhi % p.H, b = bhi / p.H;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -315,11 +319,15 @@ void tree_attn_bf16_kernel(const AttnParams p)
     L = L < 0 ? 0 : (L > p.max_prefix ? p.max_prefix : L);
     const int tiles_b = (L + C::T - 1) / C::T;
     const int tps = p.tps;                                  // fixed per call: short sequences use fewer splits
-    const int t0 = min(s * tps, tiles_b), t1 = min(t0 + tps, tiles_b);
-    const int n_tree_tiles = s == 0 ? (p.n + C::T - 1) / C::T : 0;
+    const bool sep = p.G > p.S;                             // the tree's own keys have a workgroup of their own
+    const bool tree_wg = sep ? s == p.S : s == 0;
+    const int t0 = (sep && tree_wg) ? tiles_b : min(s * tps, tiles_b), t1 = min(t0 + tps, tiles_b);
+    const int n_tree_tiles = tree_wg ? (p.n + C::T - 1) / C::T : 0;
     const int n_pre = t1 - t0;
     if (n_pre + n_tree_tiles == 0) return;                  // this split has no keys
-    const int n_active = max(1, (tiles_b + tps - 1) / tps);  // splits that run for this sequence (<= S)
+    const int np = (tiles_b + tps - 1) / tps;               // prefix splits that have keys for this sequence (<= S)
+    const int n_active = sep ? np + 1 : max(1, np);         // partial results of this sequence: slots 0 .. n_active-1
+    const int slot_id = (sep && tree_wg) ? np : s;
     // leading tiles of this split that are full (only the sequence's last tile can be ragged)
     const int n_hot = (n_pre > 0 && t1 * C::T > L) ? n_pre - 1 : n_pre;
 
@@ -534,8 +542,8 @@ void tree_attn_bf16_kernel(const AttnParams p)
 
     // ---- key splits: every split writes (O, m, l) in register-fragment order (fully coalesced); a small second
     // kernel folds them (a kernel boundary is the cheapest device-wide hand-over for this little data) ----
-    if (kg == 0) {
-        float *po = p.part_o + ((bh * p.SP + s) * (int64_t)(QBP * 32 * D)) + qb * 32 * D;
+    if (kg == 0 && qrow < p.n) {                           // padded query rows are never read back
+        float *po = p.part_o + ((bh * p.SP + slot_id) * (int64_t)(QBP * 32 * D)) + qb * 32 * D;
 #pragma unroll
         for (int cb = 0; cb < C::CB; ++cb)
 #pragma unroll
@@ -546,7 +554,7 @@ void tree_attn_bf16_kernel(const AttnParams p)
                 *(f32x4_t *)(po + (((cb * 4 + j) * 2 + g) * 32 + ln) * 4) = v;
             }
         if (g == 0) {
-            const int64_t prow = (bh * p.SP + s) * (QBP * 32) + qb * 32 + ln;
+            const int64_t prow = (bh * p.SP + slot_id) * (QBP * 32) + qb * 32 + ln;
             p.part_m[prow] = qs.m_ref;
             p.part_l[prow] = l_tot;
         }
@@ -570,19 +578,41 @@ __global__ __launch_bounds__(256) void tree_attn_merge_bf16_kernel(const AttnPar
     int L = p.lens[bh / p.H];
     L = L < 0 ? 0 : (L > p.max_prefix ? p.max_prefix : L);
     const int tiles_b = (L + T - 1) / T;
-    const int n_active = max(1, (tiles_b + p.tps - 1) / p.tps);
+    const int np = (tiles_b + p.tps - 1) / p.tps;
+    const int n_active = p.G > p.S ? np + 1 : max(1, np);
     if (n_active == 1) return;                                // the sweep wrote this sequence's output itself
-    float M = -INFINITY;
-    for (int sp = 0; sp < n_active; ++sp) M = fmaxf(M, p.part_m[(bh * p.SP + sp) * (QBP * 32) + row]);
-    float den = 0.f;
+    // eight partials at a time, all loads issued before the first use; folded in slot order
+    float M = -INFINITY, den = 0.f;
     f32x4_t num = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll 4
-    for (int sp = 0; sp < n_active; ++sp) {
-        const int64_t prow = (bh * p.SP + sp) * (QBP * 32) + row;
-        const float w = fast_exp2((p.part_m[prow] - M) * p.c);   // exp2(-inf) = 0 for a split that saw no visible key
-        const f32x4_t o = *(const f32x4_t *)(p.part_o + ((bh * p.SP + sp) * (int64_t)(QBP * 32 * D)) + qb * 32 * D + pos * 4);
-        den = fmaf(w, p.part_l[prow], den);
-        num += w * o;
+    for (int s0 = 0; s0 < n_active; s0 += 8) {
+        float m[8], l[8];
+        f32x4_t o[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            m[i] = -INFINITY;
+            l[i] = 0.f;
+            o[i] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
+            if (s0 + i < n_active) {
+                const int64_t prow = (bh * p.SP + s0 + i) * (QBP * 32) + row;
+                m[i] = p.part_m[prow];
+                l[i] = p.part_l[prow];
+                o[i] = *(const f32x4_t *)(p.part_o + ((bh * p.SP + s0 + i) * (int64_t)(QBP * 32 * D)) + qb * 32 * D + pos * 4);
+            }
+        }
+        float Mn = M;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) Mn = fmaxf(Mn, m[i]);
+        if (Mn == -INFINITY) continue;                        // nothing visible so far
+        const float a = fast_exp2((M - Mn) * p.c);            // exp2(-inf) = 0 on the first group
+        den *= a;
+        num *= a;
+        M = Mn;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const float w = fast_exp2((m[i] - M) * p.c);      // 0 for a split that saw no visible key
+            den = fmaf(w, l[i], den);
+            num += w * o[i];
+        }
     }
     const f32x4_t r = num / den;
     bf16x4_t v;
@@ -778,7 +808,7 @@ size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 size_t partial_rows(const AttnPlan &pl, int dtype, int B, int H, int n)
 {
     // bf16 path: whole 32-row query blocks in register-fragment order; fp32 path: n rows
-    return (size_t)B * H * pl.S * (dtype == MCSD_BF16 ? (size_t)pl.QBP * 32 : (size_t)n);
+    return (size_t)B * H * pl.G * (dtype == MCSD_BF16 ? (size_t)pl.QBP * 32 : (size_t)n);
 }
 
 size_t workspace_bytes_for(const AttnPlan &pl, int dtype, int B, int H, int d, int n)
@@ -791,7 +821,7 @@ size_t workspace_bytes_for(const AttnPlan &pl, int dtype, int B, int H, int d, i
 template <int D, int QBP, int NS>
 void launch_sweep(const AttnParams &p, const AttnPlan &pl, hipStream_t st)
 {
-    const dim3 grid((unsigned)((size_t)pl.S * p.H * p.B));
+    const dim3 grid((unsigned)((size_t)pl.G * p.H * p.B));
     mcsd_launch(MCSD_KERNEL_ATTN_SWEEP, tree_attn_bf16_kernel<D, QBP, NS>, grid, dim3(SweepCfg<D, QBP, NS>::THREADS), st, p);
 }
 
@@ -873,7 +903,7 @@ extern "C" int mcsd_tree_attention(const mcsd_mask_view_t *mask, mcsd_dtype_t dt
     p.B = B; p.H = H; p.n = n; p.max_prefix = max_prefix;
     p.node_stride = node_stride; p.head_stride = head_stride;
     p.c = softmax_scale * 1.4426950408889634f;
-    p.S = pl.S; p.SP = pl.S;
+    p.S = pl.S; p.G = pl.G; p.SP = pl.G;
     p.tps = (int32_t)((((int64_t)max_prefix + pl.T - 1) / pl.T + pl.S - 1) / pl.S);
     if (p.tps < 1) p.tps = 1;
     char *w = (char *)workspace;
