@@ -126,14 +126,17 @@ class Step:
         return float(want[1].mean())
 
 
-def time_kernel(st, hip, kernel_id, launch, reps):
-    """Average device execution time (ms) of one library kernel over `reps` launches, from event pairs that the
-    library places around that kernel's launch."""
+def time_kernel(st, hip, kernel_id, launch, reps, warm=0):
+    """Average device execution time (ms) of one library kernel over `reps` back-to-back launches, from event
+    pairs that the library places around that kernel's launch.  `warm` untimed launches go first in the same
+    burst, so that the timed ones see the clocks of sustained work rather than the ramp out of idle."""
     b, torch = st.binding, st.torch
     pairs = [(hip.event(), hip.event()) for _ in range(reps)]
+    for i in range(warm):
+        launch(i)
     for i, (e0, e1) in enumerate(pairs):
         b.profile_next(kernel_id, e0, e1)
-        launch(i)
+        launch(warm + i)
     torch.cuda.synchronize()
     ms = [hip.elapsed_ms(e0, e1) for e0, e1 in pairs]
     for e0, e1 in pairs:
@@ -143,9 +146,9 @@ def time_kernel(st, hip, kernel_id, launch, reps):
     return sum(ms) / len(ms), ms[len(ms) // 2], ms[len(ms) // 10], ms[(len(ms) * 9) // 10]
 
 
-def roofline_of(st, hip, reps):
+def roofline_of(st, hip, reps, warm=0):
     b = st.binding
-    avg, med, p10, p90 = time_kernel(st, hip, b.KERNEL_ATTN_SWEEP, lambda i: st.attention(i), reps)
+    avg, med, p10, p90 = time_kernel(st, hip, b.KERNEL_ATTN_SWEEP, lambda i: st.attention(i), reps, warm)
     ach = st.alg_bytes / (avg * 1e-3) / 1e9
     traffic = MEASURED_TRAFFIC.get(st.w.name)
     return {"bound": "hbm", "kernel": "tree_attn_bf16_kernel" if st.w.dtype == "bf16" else "tree_attn_f32_kernel",
@@ -207,6 +210,8 @@ def main():
     ap.add_argument("--workload", default="cfg2")
     ap.add_argument("--extra", default="cfg4,cfg5", help="other workloads whose attention roofline is reported too")
     ap.add_argument("--kernel-reps", type=int, default=64)
+    ap.add_argument("--extra-reps", type=int, default=200,
+                    help="timed launches (after as many untimed ones) of each extra workload's attention")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--traffic-calibration", action="store_true",
                     help="only run a 1 GiB device-to-device copy a few times (the known-size kernel that the "
@@ -280,14 +285,13 @@ def main():
             es.check_against_oracle(rows=8)
             for i in range(3):
                 es.attention(i)
-            r = roofline_of(es, hip, max(8, args.kernel_reps // 4))
-            t0e = None
+            r = roofline_of(es, hip, args.extra_reps, warm=args.extra_reps)
             torch.cuda.synchronize()
             t0e = time.perf_counter()
-            for i in range(10):
+            for i in range(args.extra_reps):
                 es.attention(i)
             torch.cuda.synchronize()
-            call_us = (time.perf_counter() - t0e) / 10 * 1e6
+            call_us = (time.perf_counter() - t0e) / args.extra_reps * 1e6
             r["attention_call_us"] = round(call_us, 1)
             r["attn_tree_tokens_per_s"] = round(es.w.B * es.n / (call_us * 1e-6), 1)
             r["workload"] = f"{name}: B{es.w.B} N={es.n} prefix {es.w.prefix_min}-{es.w.prefix_max}"

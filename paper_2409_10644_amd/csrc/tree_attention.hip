@@ -93,8 +93,10 @@ AttnPlan make_plan(int dtype, int B, int H, int n, int max_prefix)
     }
     pl.S = (int)S;
     // With split keys the tree's own tiles (masked, through registers) would lengthen one split's critical path:
-    // they get a workgroup of their own, which costs one more partial result.
-    pl.G = (dtype == MCSD_BF16 && S > 1) ? (int)S + 1 : (int)S;
+    // they get a workgroup of their own, which costs one more partial result.  Only when all workgroups are
+    // resident at once (two per compute unit): the hardware dispatcher does not rebalance long workgroups that
+    // start behind short ones.
+    pl.G = (dtype == MCSD_BF16 && S > 1 && bh * (S + 1) <= 512) ? (int)S + 1 : (int)S;
     return pl;
 }
 
@@ -306,7 +308,7 @@ void tree_attn_bf16_kernel(const AttnParams p)
     // which read the same Q, tree K/V and mask rows and write neighbouring partial results, share one XCD's L2.
     const int total = gridDim.x;
     int wg = blockIdx.x;
-    if ((total & 7) == 0) wg = (wg & 7) * (total >> 3) + (wg >> 3);
+    if (p.G > 1 && (total & 7) == 0) wg = (wg & 7) * (total >> 3) + (wg >> 3);
     const int s = wg % p.G;
     const int bhi = wg / p.G;
     const int h = bhi % p.H, b = bhi / p.H;
@@ -387,14 +389,19 @@ void tree_attn_bf16_kernel(const AttnParams p)
         const unsigned char *vsrc = vp + (int64_t)t0 * C::TILE_K;
         // Stage numbers are compile-time constants so that the compiler can tell the stage being filled from
         // the stage being read (otherwise it makes every LDS read wait for the loads just issued).
-        auto issue_tile = [&](int it, auto stage) {
+        // Every workgroup walks its full tiles in a rotated order (soft-max does not care): workgroups that start
+        // together would otherwise sweep their equally aligned K/V streams in lock-step and crowd the same
+        // memory channels.  `nxt` is the tile the next issue fetches.
+        int nxt = (int)(((unsigned)wg * 37u) % (unsigned)n_hot);
+        auto issue_tile = [&](auto stage) {
             unsigned char *dst = ring + decltype(stage)::value * C::TILE + wave * 1024;
             static_assert(decltype(stage)::value < NS, "stage out of range");
 #pragma unroll
             for (int i = 0; i < C::NI; ++i) {
-                load_to_lds16(ksrc + (int64_t)it * C::TILE_K + goff[i], dst + i * C::WAVES * 1024);
-                load_to_lds16(vsrc + (int64_t)it * C::TILE_K + goff[i], dst + C::TILE_K + i * C::WAVES * 1024);
+                load_to_lds16(ksrc + (int64_t)nxt * C::TILE_K + goff[i], dst + i * C::WAVES * 1024);
+                load_to_lds16(vsrc + (int64_t)nxt * C::TILE_K + goff[i], dst + C::TILE_K + i * C::WAVES * 1024);
             }
+            nxt = nxt + 1 == n_hot ? 0 : nxt + 1;
         };
         auto step = [&](int it, auto stage) {
             constexpr int ST = decltype(stage)::value;
@@ -402,13 +409,13 @@ void tree_attn_bf16_kernel(const AttnParams p)
             if (NS > 2 && it + NS - 2 < n_hot) MCSD_WAIT_VMCNT((NS - 2) * C::DPT);
             else MCSD_WAIT_VMCNT(0);
             __builtin_amdgcn_s_barrier();                     // ... and everyone's; the stage of tile it-1 is free again
-            if (it + NS - 1 < n_hot) issue_tile(it + NS - 1, std::integral_constant<int, (ST + NS - 1) % NS>());
+            if (it + NS - 1 < n_hot) issue_tile(std::integral_constant<int, (ST + NS - 1) % NS>());
             attn_tile<D, QBP, NS, 0>(ring + ST * C::TILE, la, qs, p.c, g, all_keys);
         };
-        issue_tile(0, std::integral_constant<int, 0>());
+        issue_tile(std::integral_constant<int, 0>());
         if (NS > 2) {
-            if (1 < n_hot) issue_tile(1, std::integral_constant<int, 1 % NS>());
-            if (2 < n_hot) issue_tile(2, std::integral_constant<int, 2 % NS>());
+            if (1 < n_hot) issue_tile(std::integral_constant<int, 1 % NS>());
+            if (2 < n_hot) issue_tile(std::integral_constant<int, 2 % NS>());
         }
         int it = 0;
         for (; it + NS <= n_hot; it += NS) {
