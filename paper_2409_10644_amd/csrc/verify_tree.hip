@@ -2,20 +2,23 @@
 // recursive rejection sampling down the candidate tree, longest-path selection for target-initialised
 // trees, and sampling of the new token(s).
 //
-// One workgroup of 1024 lanes walks one tree (draft-initialised) or one level-1 subtree (target-initialised).
+// One workgroup of 512 lanes walks one tree (draft-initialised) or one level-1 subtree (target-initialised).
 // The residual r <- max(r - S*q, 0) is never stored: after j rejections an element is recomputed from p, q
 // and the j previous sums (a chain of j fused multiply-adds), so a round is one coalesced sweep over the
 // two vocabulary rows.  Sums over the vocabulary follow the balanced binary tree over the zero-padded
 // index space that the header specifies: a lane adds its 4 consecutive elements pairwise, 64 lanes combine
 // by butterfly (256 elements per wavefront load), and the 256-element block sums are reduced through a
-// heap in LDS which is kept for the inverse-CDF descent.  All arithmetic is binary64 with explicit fma.
+// tree whose upper levels every wavefront adds for itself (one barrier per rejection round); a heap over the
+// blocks is built in LDS only for the inverse-CDF descent.  While a context's two rows fit the workgroup's
+// registers (V <= 32768) they are read once and the residual is updated in place; the candidates' own residuals
+// live one per lane.  All arithmetic is binary64 with explicit fma.
 //
 // Compiled with -ffp-contract=off.
 #include "mcsd_internal.h"
 
 namespace {
 
-constexpr int VT = 1024;                 // threads per workgroup
+constexpr int VT = 512;                  // threads per workgroup
 constexpr int BLK = 256;                 // vocabulary elements per wavefront load
 constexpr int MAX_NB = MCSD_MAX_VOCAB / BLK;
 
@@ -32,12 +35,18 @@ struct VerifyParams {
     int32_t *cand_new;                   // [B][R][n_new]
 };
 
-struct Shared {
-    double heapB[2 * MAX_NB];            // heap over 256-element blocks: leaves at [NB, 2NB), root at 1
+template <int NBMAX, int QROW>
+struct SharedT {
+    double leaf[2][NBMAX];               // sums of the 256-element blocks, double-buffered over rejection rounds
+    double heapB[2 * NBMAX];             // heap over the blocks: leaves at [NB, 2NB), root at 1 (built for the descent only)
     double heapA[2 * BLK];               // heap inside one block, rebuilt for each descent
     double s_hist[MCSD_MAX_BRANCH + 1];  // S before each rejection round of the current context
+    float qrow[QROW];                    // register-resident path: the context's draft row, in the lanes' own order
     int lo_idx, hi_idx;
 };
+
+constexpr int GROUP = 16;                // blocks a wavefront handles at a time
+constexpr int FAST_NB = GROUP * (VT / 64);   // up to this many blocks a context's rows stay in registers
 
 // Element t of the distribution after `rounds` rejections at a context with rows prow / qrow.
 __device__ inline double residual_at(const float *prow, const float *qrow, const double *s_hist, int rounds,
@@ -54,19 +63,98 @@ __device__ inline double residual_at(const float *prow, const float *qrow, const
     return r;
 }
 
-// Builds heapB for the distribution (prow, qrow, rounds) and returns its total.  All threads call it.
-// A wavefront handles GROUP blocks of 256 elements at a time: all their loads are issued before any is used, and
-// the GROUP butterflies are independent instruction streams, so a round costs about one memory latency.
-__device__ double block_tree_sum(Shared &sh, const VerifyParams &P, const float *prow, const float *qrow,
-                                 int rounds)
+// A double from another lane of the row through the data-parallel-primitive path of the vector ALU (no LDS).
+template <int CTRL>
+__device__ inline double dpp_f64(double v)
 {
-    constexpr int GROUP = 8;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const bool vec = (((uintptr_t)prow | (uintptr_t)qrow) & 15) == 0;
-    for (int blk0 = wave; blk0 < P.NB; blk0 += GROUP * (VT / 64)) {
-        float pe[GROUP][4], qe[GROUP][4];
+    const int lo = __builtin_amdgcn_update_dpp(0, __double2loint(v), CTRL, 0xF, 0xF, false);
+    const int hi = __builtin_amdgcn_update_dpp(0, __double2hiint(v), CTRL, 0xF, 0xF, false);
+    return __hiloint2double(hi, lo);
+}
+
+// Sum over the 64 lanes in balanced-tree order (lane pairs, then pairs of pairs, ...); every lane gets the total.
+// Partner lanes: l^1 and l^2 by quad permutation; then, since all lanes of a group of 4 (8) already hold the same
+// value, the mirrored lane of the half row (row) stands in for l^4 (l^8); l^16 by swizzle; l^32 by the half-wave
+// swap, whose two results are {own, partner} in an order that the commutative addition does not care about.
+__device__ inline double wave_tree_sum(double v)
+{
+    v = __dadd_rn(v, dpp_f64<0xB1>(v));          // quad_perm [1,0,3,2]
+    v = __dadd_rn(v, dpp_f64<0x4E>(v));          // quad_perm [2,3,0,1]
+    v = __dadd_rn(v, dpp_f64<0x141>(v));         // row_half_mirror
+    v = __dadd_rn(v, dpp_f64<0x140>(v));         // row_mirror
+    {
+        const int lo = __builtin_amdgcn_ds_swizzle(__double2loint(v), 0x401F);   // lane ^ 16 inside each 32
+        const int hi = __builtin_amdgcn_ds_swizzle(__double2hiint(v), 0x401F);
+        v = __dadd_rn(v, __hiloint2double(hi, lo));
+    }
+    {
+        const auto lo = __builtin_amdgcn_permlane32_swap((unsigned)__double2loint(v), (unsigned)__double2loint(v), false, false);
+        const auto hi = __builtin_amdgcn_permlane32_swap((unsigned)__double2hiint(v), (unsigned)__double2hiint(v), false, false);
+        v = __dadd_rn(__hiloint2double((int)hi[0], (int)lo[0]), __hiloint2double((int)hi[1], (int)lo[1]));
+    }
+    return v;
+}
+
+// 4 elements of each of the wavefront's GROUP blocks (block wave + 16k): float rows -> registers; beyond V: 0.
+// The thread id is hidden from the optimiser so that offsets and bounds tests are recomputed at every use
+// instead of being kept in registers across the whole walk.
+__device__ inline void load_rows(const VerifyParams &P, const float *row, float (&dst)[GROUP][4])
+{
+    int t = threadIdx.x;
+    asm volatile("" : "+v"(t));
+    const int first = (t >> 6) * BLK + (t & 63) * 4;          // element of block `wave` held by this lane
+    if ((((uintptr_t)row & 15) | (P.V & 3)) == 0) {           // aligned rows: a float4 is inside V or outside as a whole
 #pragma unroll
         for (int k = 0; k < GROUP; ++k) {
+            const int t0 = first + k * (VT / 64) * BLK;
+            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (t0 < P.V) v = *(const float4 *)(row + t0);
+            dst[k][0] = v.x; dst[k][1] = v.y; dst[k][2] = v.z; dst[k][3] = v.w;
+        }
+    } else {
+#pragma unroll
+        for (int k = 0; k < GROUP; ++k) {
+            const int t0 = first + k * (VT / 64) * BLK;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) dst[k][e] = t0 + e < P.V ? row[t0 + e] : 0.f;
+        }
+    }
+}
+
+// Block sums of a register-resident distribution into leaf[buf] (blocks wave + 16k).  No barrier.
+template <class Shared>
+__device__ inline void store_block_sums(Shared &sh, const VerifyParams &P, const double (&r)[GROUP][4], int buf)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    double sblk[GROUP];
+#pragma unroll
+    for (int k = 0; k < GROUP; ++k) {
+        if (k % 4 == 0) __builtin_amdgcn_sched_barrier(0);      // four independent reductions in flight
+        sblk[k] = wave_tree_sum(__dadd_rn(__dadd_rn(r[k][0], r[k][1]), __dadd_rn(r[k][2], r[k][3])));
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    if (lane == 0) {
+#pragma unroll
+        for (int k = 0; k < GROUP; ++k) {
+            const int blk = wave + k * (VT / 64);
+            if (blk < P.NB) sh.leaf[buf][blk] = sblk[k];
+        }
+    }
+}
+
+// Block sums of the distribution (prow, qrow, rounds) recomputed from memory into leaf[buf]; any NB.  No barrier
+// at the end; s_hist[0 .. rounds) must be visible.
+constexpr int SGROUP = 8;                // blocks a wavefront streams at a time
+template <class Shared>
+__device__ void stream_block_sums(Shared &sh, const VerifyParams &P, const float *prow, const float *qrow,
+                                  int rounds, int buf)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const bool vec = (((uintptr_t)prow | (uintptr_t)qrow) & 15) == 0;
+    for (int blk0 = wave; blk0 < P.NB; blk0 += SGROUP * (VT / 64)) {
+        float pe[SGROUP][4], qe[SGROUP][4];
+#pragma unroll
+        for (int k = 0; k < SGROUP; ++k) {
             const int blk = blk0 + k * (VT / 64);
             const int t0 = blk * BLK + lane * 4;
 #pragma unroll
@@ -89,9 +177,9 @@ __device__ double block_tree_sum(Shared &sh, const VerifyParams &P, const float 
                 }
             }
         }
-        double sblk[GROUP];
+        double sblk[SGROUP];
 #pragma unroll
-        for (int k = 0; k < GROUP; ++k) {
+        for (int k = 0; k < SGROUP; ++k) {
             double v[4];
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
@@ -106,26 +194,53 @@ __device__ double block_tree_sum(Shared &sh, const VerifyParams &P, const float 
             sblk[k] = __dadd_rn(__dadd_rn(v[0], v[1]), __dadd_rn(v[2], v[3]));
         }
 #pragma unroll
-        for (int m = 1; m < 64; m <<= 1)
-#pragma unroll
-            for (int k = 0; k < GROUP; ++k) sblk[k] = __dadd_rn(sblk[k], __shfl_xor(sblk[k], m, 64));
+        for (int k = 0; k < SGROUP; ++k) sblk[k] = wave_tree_sum(sblk[k]);
         if (lane == 0) {
 #pragma unroll
-            for (int k = 0; k < GROUP; ++k) {
+            for (int k = 0; k < SGROUP; ++k) {
                 const int blk = blk0 + k * (VT / 64);
-                if (blk < P.NB) sh.heapB[P.NB + blk] = sblk[k];
+                if (blk < P.NB) sh.leaf[buf][blk] = sblk[k];
             }
         }
     }
+}
+
+// Total of leaf[buf][0 .. NB) in balanced-tree order, computed by every wavefront for itself (no further barrier):
+// a lane adds its NB/64 consecutive leaves as a small tree (zero-filled to PER: x + 0 is exact), then 64 lanes
+// combine.  PER = largest NB / 64 the caller can have.
+template <int PER, class Shared>
+__device__ inline double top_tree_sum(const Shared &sh, const VerifyParams &P, int buf)
+{
+    const int lane = threadIdx.x & 63;
+    const int per = P.NB >= 64 ? P.NB >> 6 : 1;                  // 1 .. PER
+    double v[PER];
+#pragma unroll
+    for (int i = 0; i < PER; ++i) {
+        const int idx = lane * per + i;
+        v[i] = (i < per && idx < P.NB) ? sh.leaf[buf][idx] : 0.0;
+    }
+#pragma unroll
+    for (int w = PER / 2; w >= 1; w >>= 1)
+#pragma unroll
+        for (int i = 0; i < w; ++i) v[i] = __dadd_rn(v[2 * i], v[2 * i + 1]);
+    return wave_tree_sum(v[0]);
+}
+
+// heapB from leaf[buf].  All threads call it; ends with a barrier.
+template <class Shared>
+__device__ void build_heap(Shared &sh, const VerifyParams &P, int buf)
+{
+    const int tid = threadIdx.x;
+    for (int i = tid; i < P.NB; i += VT) sh.heapB[P.NB + i] = sh.leaf[buf][i];
     __syncthreads();
     for (int n = P.NB >> 1; n >= 1; n >>= 1) {
-        if (tid < n) sh.heapB[n + tid] = __dadd_rn(sh.heapB[2 * (n + tid)], sh.heapB[2 * (n + tid) + 1]);
+        for (int i = tid; i < n; i += VT) sh.heapB[n + i] = __dadd_rn(sh.heapB[2 * (n + i)], sh.heapB[2 * (n + i) + 1]);
         __syncthreads();
     }
-    return sh.heapB[1];
 }
 
 // Inverse-CDF draw from the distribution whose heapB is current.  All threads call it; all return the token.
+template <class Shared>
 __device__ int tree_sample(Shared &sh, const VerifyParams &P, const float *prow, const float *qrow, int rounds,
                            float u)
 {
@@ -186,8 +301,11 @@ __device__ int tree_sample(Shared &sh, const VerifyParams &P, const float *prow,
     return t;
 }
 
+// FAST: a context's rows fit the workgroup's registers (NB <= FAST_NB).
+template <bool FAST>
 __global__ __launch_bounds__(VT) void verify_walk_kernel(const VerifyParams P)
 {
+    using Shared = SharedT<FAST ? FAST_NB : MAX_NB, FAST ? FAST_NB * BLK : 1>;
     __shared__ Shared sh;
     const int tid = threadIdx.x;
     const int root = blockIdx.x, b = blockIdx.y;
@@ -204,32 +322,91 @@ __global__ __launch_bounds__(VT) void verify_walk_kernel(const VerifyParams P)
         n_acc = 1;
         if (tid == 0) path_out[0] = root;
     }
+    const int lane = tid & 63;
     const float *term_p = nullptr, *term_q = nullptr;
-    int term_rounds = 0;
-    bool have_heap = false;
+    int term_rounds = 0, term_buf = -1;       // term_buf >= 0: leaf[term_buf] holds the terminal distribution's block sums
+    int buf = 0;
     while (level < P.t.gamma) {
         const float *prow = p + (int64_t)(cur + 1) * P.V;
         const float *qrow = q + (int64_t)(cur + 1) * P.V;
         const int cnt = P.t.b[level];
         const int first = cur < 0 ? 0 : P.t.off[level] + (cur - P.t.off[level - 1]) * cnt;
+        // candidate `lane` of this context (in every wavefront): acceptance uniform, q(x) and the residual at x,
+        // which is updated in place after every rejection
+        double uc = 0.0, qc = 0.0, rc = 0.0;
+        if (lane < cnt) {
+            int x = tokens[first + lane];
+            x = x < 0 ? 0 : (x >= P.V ? P.V - 1 : x);   // ids outside 0..V-1 are clamped, never dereferenced
+            uc = (double)ua[first + lane];
+            qc = (double)qrow[x];
+            rc = (double)prow[x];
+        }
         int rounds = 0, accepted = -1;
         double S = 1.0;
-        for (int c = 0; c < cnt; ++c) {
-            const int node = first + c;
-            int x = tokens[node];
-            x = x < 0 ? 0 : (x >= P.V ? P.V - 1 : x);   // ids outside 0..V-1 are clamped, never dereferenced
-            const double u = (double)ua[node];
-            const double rx = residual_at(prow, qrow, sh.s_hist, rounds, x);
-            if (__dmul_rn(u, __dmul_rn((double)qrow[x], S)) < rx) { accepted = node; break; }
-            __syncthreads();                 // every lane has finished reading s_hist / heaps
-            if (tid == 0) sh.s_hist[rounds] = S;
-            __syncthreads();
-            rounds += 1;
-            S = block_tree_sum(sh, P, prow, qrow, rounds);
+        // accept test of candidate c: the same value in every lane, read through one lane so that the walk is
+        // scalar control flow
+        auto accept = [&](int c) {
+            const double u = __shfl(uc, c, 64), qx = __shfl(qc, c, 64), rx = __shfl(rc, c, 64);
+            return __builtin_amdgcn_readfirstlane((int)(__dmul_rn(u, __dmul_rn(qx, S)) < rx)) != 0;
+        };
+        if (accept(0)) {
+            accepted = first;
+        } else {
+            // First rejection at this context: from here on the residual is needed.  Register-resident path: r
+            // holds this lane's 4 elements of blocks wave + 8k and is updated in place; q is parked in LDS at
+            // float4 slot k * VT + tid (read back by this lane only).
+            double r[GROUP][4];
+            float4 *qlds = (float4 *)sh.qrow + tid;
+            if constexpr (FAST) {
+                float pe[GROUP][4];
+                load_rows(P, qrow, pe);
+#pragma unroll
+                for (int k = 0; k < GROUP; ++k) qlds[k * VT] = make_float4(pe[k][0], pe[k][1], pe[k][2], pe[k][3]);
+                __builtin_amdgcn_sched_barrier(0);
+                load_rows(P, prow, pe);
+#pragma unroll
+                for (int k = 0; k < GROUP; ++k)
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) r[k][e] = (double)pe[k][e];
+            }
+            for (int c = 0;;) {
+                // candidate c was rejected: r <- max(r - S q, 0), S <- sum r
+                if (tid == 0) sh.s_hist[rounds] = S;
+                buf ^= 1;
+                if constexpr (FAST) {
+                    // four blocks at a time: the scheduler must not pull all of q into registers next to r
+#pragma unroll
+                    for (int k = 0; k < GROUP; ++k) {
+                        if (k % 4 == 0) __builtin_amdgcn_sched_barrier(0);
+                        const float4 qv = qlds[k * VT];
+                        const float qe[4] = {qv.x, qv.y, qv.z, qv.w};
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            const double d = __fma_rn(-S, (double)qe[e], r[k][e]);
+                            r[k][e] = d > 0.0 ? d : 0.0;
+                        }
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                    store_block_sums(sh, P, r, buf);
+                } else {
+                    __syncthreads();          // s_hist[rounds] visible
+                    stream_block_sums(sh, P, prow, qrow, rounds + 1, buf);
+                }
+                {
+                    const double d = __fma_rn(-S, qc, rc);
+                    rc = d > 0.0 ? d : 0.0;
+                }
+                rounds += 1;
+                __syncthreads();              // block sums (and s_hist) visible
+                S = top_tree_sum<(FAST ? FAST_NB : MAX_NB) / 64>(sh, P, buf);
+                if (++c == cnt) break;
+                if (accept(c)) { accepted = first + c; break; }
+            }
         }
         if (accepted < 0) {
-            if (S > 0.0) { term_p = prow; term_q = qrow; term_rounds = rounds; have_heap = true; }
-            else { term_p = prow; term_q = qrow; term_rounds = 0; have_heap = false; }
+            term_p = prow; term_q = qrow;
+            if (S > 0.0) { term_rounds = rounds; term_buf = rounds > 0 ? buf : -1; }
+            else { term_rounds = 0; term_buf = -1; }     // vanished residual: the context's own target row
             break;
         }
         if (tid == 0) path_out[n_acc] = accepted;
@@ -241,17 +418,21 @@ __global__ __launch_bounds__(VT) void verify_walk_kernel(const VerifyParams P)
         term_p = p + (int64_t)(cur + 1) * P.V;
         term_q = term_p;                      // never read: rounds == 0
         term_rounds = 0;
-        have_heap = false;
+        term_buf = -1;
     }
     if (tid == 0) {
         for (int l = n_acc; l < P.t.gamma; ++l) path_out[l] = -1;
         P.cand_len[(int64_t)b * P.R + root] = n_acc;
     }
     if (P.n_new > 0) {
-        if (!have_heap) {
+        if (term_buf < 0) {
+            buf ^= 1;
             __syncthreads();
-            (void)block_tree_sum(sh, P, term_p, term_q, 0);
+            stream_block_sums(sh, P, term_p, term_q, 0, buf);
+            term_buf = buf;
         }
+        __syncthreads();
+        build_heap(sh, P, term_buf);
         for (int k = 0; k < P.n_new; ++k) {
             const int t = tree_sample(sh, P, term_p, term_q, term_rounds, P.us[(int64_t)b * P.n_new + k]);
             if (tid == 0) P.cand_new[((int64_t)b * P.R + root) * P.n_new + k] = t;
@@ -324,7 +505,8 @@ extern "C" int mcsd_verify_tree(const mcsd_mask_view_t *mask, mcsd_mode_t mode, 
     hipStream_t st = (hipStream_t)hip_stream;
     if (mode == MCSD_DRAFT_INIT) {
         P.cand_path = out_path; P.cand_len = out_accept_len; P.cand_new = out_new_tokens;
-        mcsd_launch(MCSD_KERNEL_VERIFY_WALK, verify_walk_kernel, dim3(1, B), dim3(VT), st, P);
+        if (P.NB <= FAST_NB) mcsd_launch(MCSD_KERNEL_VERIFY_WALK, verify_walk_kernel<true>, dim3(1, B), dim3(VT), st, P);
+        else mcsd_launch(MCSD_KERNEL_VERIFY_WALK, verify_walk_kernel<false>, dim3(1, B), dim3(VT), st, P);
         return mcsd_hip_status(hipGetLastError());
     }
     const size_t need = mcsd_verify_tree_workspace(mask, mode, B, n_new);
@@ -336,7 +518,8 @@ extern "C" int mcsd_verify_tree(const mcsd_mask_view_t *mask, mcsd_mode_t mode, 
     P.cand_len = (int32_t *)w;
     w += align256(sizeof(int32_t) * B * R);
     P.cand_new = (int32_t *)w;
-    mcsd_launch(MCSD_KERNEL_VERIFY_WALK, verify_walk_kernel, dim3(P.R, B), dim3(VT), st, P);
+    if (P.NB <= FAST_NB) mcsd_launch(MCSD_KERNEL_VERIFY_WALK, verify_walk_kernel<true>, dim3(P.R, B), dim3(VT), st, P);
+    else mcsd_launch(MCSD_KERNEL_VERIFY_WALK, verify_walk_kernel<false>, dim3(P.R, B), dim3(VT), st, P);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return MCSD_EHIP;
     hipLaunchKernelGGL(verify_select_kernel, dim3(B), dim3(64), 0, st, P, out_path, out_accept_len, out_new_tokens);

@@ -187,6 +187,61 @@ def test_ragged_tails_and_split_boundaries(binding, oracle, H, br, L):
     H.assert_close(got, want, "bf16", f"L={L} tree {br}")
 
 
+# The split plan is made on the host from B * H and the longest allowed prefix alone, so the actual lengths can be
+# anything below it: far shorter than planned for, empty, or wildly different between sequences.  `max_prefix` may
+# exceed the cache capacity: only lens[b] keys are ever read.
+PLAN_VS_LENGTH_CASES = [
+    # (tree, B, H, d, lens, max_prefix, note)
+    ((4, 2, 2, 1), 3, 2, 128, (0, 9000, 130), 65536, "one long sequence, a short and an empty one"),
+    ((8, 2, 2, 1, 1), 4, 4, 128, (0, 70, 1000, 3000), 16384, "two tree tiles, lengths far below the plan"),
+    ((3, 2), 4, 4, 128, (5, 64, 129, 700), 32768, "one query block, 128-key tiles"),
+    ((4, 2, 2, 2), 40, 4, 64, None, 2048, "many short sequences"),
+    ((4, 2, 2, 2), 8, 8, 128, (2000, 4000, 2500, 3100, 3999, 2048, 2111, 3333), 4096, "ragged long sequences"),
+]
+
+
+@pytest.mark.parametrize("case", PLAN_VS_LENGTH_CASES, ids=[c[-1] for c in PLAN_VS_LENGTH_CASES])
+def test_lengths_unlike_the_plan(binding, oracle, H, case):
+    br, B, Hh, d, lens, max_prefix, note = case
+    w = scaled(WORKLOADS["cfg4"], B=B, H=Hh, d=d, branching=tuple(br), cfg_id=52)
+    if lens is None:
+        lens = np.random.default_rng(9).integers(0, 600, size=B)
+        lens[3] = 0
+    inp = attention_inputs(w, seed=11, lens=tuple(int(x) for x in lens))
+    ad = H.AttnDevice(inp)
+    m = binding.build_mask(br)
+    M = oracle.build_mask(br)
+    v = binding.slice_mask(m, len(br))
+    got = H.run_attention(binding, v, ad, max_prefix=max_prefix, fill=77.0)
+    if B * Hh * max(lens) <= 64 * 1500:
+        want = oracle.tree_attention(inp, M, v.n_nodes)
+        H.assert_close(got, want, "bf16", note)
+    else:
+        rng = np.random.default_rng(6)
+        for (b, h, i) in _sample_rows(rng, B, Hh, v.n_nodes, 96):
+            want = oracle.tree_attention_row(inp, M, v.n_nodes, b, h, i)
+            H.assert_close(got[b, h, i], want, "bf16", f"{note} row {(b, h, i)}")
+    again = H.run_attention(binding, v, ad, max_prefix=max_prefix)
+    assert np.array_equal(got, again), "two runs differ"
+
+
+def test_lengths_are_clamped_to_max_prefix(binding, oracle, H):
+    br = (4, 2, 2, 1)
+    w = scaled(WORKLOADS["cfg4"], B=16, H=32, branching=br, cfg_id=53)
+    lens = [300] * 16
+    inp = attention_inputs(w, seed=3, lens=lens, kv_capacity=640)
+    ad = H.AttnDevice(inp)
+    v = binding.slice_mask(binding.build_mask(br), 4)
+    ad.lens.copy_(torch.tensor([300, 5000, -3, 640] * 4, dtype=torch.int32))       # the device sees other lengths
+    got = H.run_attention(binding, v, ad, max_prefix=640)
+    seen = dict(inp, lens=np.asarray([300, 640, 0, 640] * 4, dtype=np.int32))       # ... clamped to 0 .. max_prefix
+    M = oracle.build_mask(br)
+    rng = np.random.default_rng(8)
+    for (b, h, i) in _sample_rows(rng, 16, 32, v.n_nodes, 64):
+        want = oracle.tree_attention_row(seen, M, v.n_nodes, b, h, i)
+        H.assert_close(got[b, h, i], want, "bf16", f"clamped lengths row {(b, h, i)}")
+
+
 def test_boosted_tree_keys_make_mask_errors_visible(binding, oracle, H):
     """Long prefix, but every tree key is aligned with every query, so the visible tree keys share most of the
     softmax weight equally: one wrong mask bit moves the output far beyond the tolerance."""
