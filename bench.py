@@ -213,6 +213,7 @@ def main():
     ap.add_argument("--extra-reps", type=int, default=200,
                     help="timed launches (after as many untimed ones) of each extra workload's attention")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--eager", action="store_true", help="launch the step's kernels one by one instead of replaying a HIP graph")
     ap.add_argument("--traffic-calibration", action="store_true",
                     help="only run a 1 GiB device-to-device copy a few times (the known-size kernel that the "
                          "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run are scaled by) and exit")
@@ -244,14 +245,36 @@ def main():
     alpha = st.check_against_oracle()
     log(f"[bench] {w_name}: outputs verified against the oracle (mean accepted length {alpha:.2f})")
 
+    # The 65 launches of a step are captured once into a HIP graph and replayed (the library's calls neither
+    # allocate nor synchronise, so they can be captured); --eager launches them one by one instead.
+    run_step, launch = st.step, "eager"
+    if not args.eager:
+        try:
+            side = torch.cuda.Stream()
+            side.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.stream(side):
+                st.step()
+            torch.cuda.current_stream().wait_stream(side)
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph):
+                st.step()
+            run_step, launch = graph.replay, "hip-graph"
+        except Exception as ex:
+            log(f"[bench] graph capture failed ({ex!r}); timing eager launches")
     for _ in range(args.warmup):
-        st.step()
+        run_step()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        st.step()
+        run_step()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
+    if launch == "hip-graph":                     # the replayed step must leave what the eager step leaves
+        got_v = (st.path.clone(), st.alen.clone(), st.new.clone(), st.layers[N_LAYERS % len(st.layers) - 1].out.clone())
+        st.step()
+        torch.cuda.synchronize()
+        now_v = (st.path, st.alen, st.new, st.layers[N_LAYERS % len(st.layers) - 1].out)
+        assert all(torch.equal(a, b) for a, b in zip(got_v, now_v)), "graph replay differs from eager launches"
     ms_per_step = dt / args.steps * 1e3
     value = w.B * st.n / (ms_per_step * 1e-3)
 
@@ -267,7 +290,7 @@ def main():
         "config": {"workload": f"{w_name}: B{w.B} H{w.H} d{w.d} {w.dtype} prefix {w.prefix_min}"
                                f"{'' if w.prefix_min == w.prefix_max else '-' + str(w.prefix_max)} tree {w.branching} "
                                f"N={st.n} gamma={st.gamma} V={w.V} mode={'target' if st.mode else 'draft'}-init",
-                   "layers_per_step": N_LAYERS, "kv_sets": n_sets, "verified_vs_oracle": True,
+                   "layers_per_step": N_LAYERS, "kv_sets": n_sets, "launch": launch, "verified_vs_oracle": True,
                    "mean_accept_len": round(alpha, 3)},
         "roofline": roof,
         "kernels_us": {"attn_sweep": roof["avg_launch_us"], "attn_merge": round(m_avg * 1e3, 2),

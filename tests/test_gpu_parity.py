@@ -393,3 +393,53 @@ def test_verify_special_rows(binding, oracle, H):
 def test_verify_without_new_tokens(binding, oracle, H):
     w = scaled(WORKLOADS["cfg1"], B=3, cfg_id=62)
     _check_verify(binding, oracle, H, w, DRAFT_INIT, n_new=0)
+
+
+# ------------------------------------------------------------------------------------------------
+# the whole step under HIP graph capture
+# ------------------------------------------------------------------------------------------------
+def test_step_replayed_from_a_hip_graph_matches_eager_launches(binding, oracle, H):
+    """Attention (split keys, so sweep + fold kernels) and verification captured once and replayed several times,
+    with eager work and synchronisations between the replays; every replay must leave the eager results."""
+    w = WORKLOADS["cfg2"]
+    inp = attention_inputs(w, seed=2)
+    ad = H.AttnDevice(inp)
+    v = binding.slice_mask(binding.build_mask(w.branching), w.gamma_max)
+    ws = torch.empty(max(binding.tree_attention_workspace(ad.B, ad.H, ad.d, v.n_nodes, ad.max_prefix), 256),
+                     dtype=torch.uint8, device="cuda")
+    vi = verify_inputs(w, seed=2, gamma=w.gamma_max, mode=DRAFT_INIT)
+    p, q = H.dev(vi["p_target"]), H.dev(vi["q_draft"])
+    tokens, ua, us = H.dev(vi["tokens"]), H.dev(vi["u_accept"]), H.dev(vi["u_sample"])
+    n_new = vi["u_sample"].shape[1]
+    path = torch.zeros((w.B, v.gamma), dtype=torch.int32, device="cuda")
+    alen = torch.zeros((w.B,), dtype=torch.int32, device="cuda")
+    new = torch.zeros((w.B, n_new), dtype=torch.int32, device="cuda")
+
+    def step():
+        binding.tree_attention(v, ad.code, ad.B, ad.H, ad.d, ad.q, ad.kt, ad.vt, ad.node_stride, ad.kp, ad.vp,
+                               ad.base, ad.lens, ad.head_stride, ad.max_prefix, ad.scale, ad.out, ws)
+        binding.verify_tree(v, DRAFT_INIT, w.B, w.V, tokens, p, q, vi["p_target"].shape[1] * w.V,
+                            vi["q_draft"].shape[1] * w.V, ua, us, n_new, path, alen, new, None)
+
+    step()
+    torch.cuda.synchronize()
+    want = [t.clone() for t in (ad.out, path, alen, new)]
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()
+    torch.cuda.current_stream().wait_stream(side)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    for r in range(4):
+        for t in (ad.out, path, alen, new):
+            t.fill_(-3)                                  # eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for a, b in zip(want, (ad.out, path, alen, new)):
+            assert torch.equal(a, b), f"replay {r} differs from the eager step"
+    M = oracle.build_mask(w.branching)
+    H.assert_close(ad.out[:, :, :v.n_nodes].float().cpu().numpy().astype(np.float64),
+                   oracle.tree_attention(inp, M, v.n_nodes), "bf16", "graph replay")
