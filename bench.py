@@ -29,7 +29,7 @@ N_LAYERS = 32                   # Llama-2-7B
 # HBM traffic per launch of the sweep kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (bytes, already
 # scaled by the copy-kernel calibration); filled from the summaries under profiles/.  None = not measured.
 MEASURED_TRAFFIC = {   # profiles/tree_attn_hbm_traffic_pmc.md (sweep kernel: HBM read + written)
-    "cfg2": 26_680_000, "cfg4": 664_190_000, "cfg5": 2_222_700_000,
+    "cfg2": 21_730_000, "cfg4": 664_630_000, "cfg5": 2_204_310_000,
 }
 
 
@@ -157,6 +157,39 @@ def roofline_of(st, hip, reps, warm=0):
             "flops_per_launch": int(st.alg_flops), "avg_launch_us": round(avg * 1e3, 2),
             "median_launch_us": round(med * 1e3, 2), "p10_us": round(p10 * 1e3, 2), "p90_us": round(p90 * 1e3, 2),
             "mfma_tflops": round(st.alg_flops / (avg * 1e-3) / 1e12, 1), "launches_timed": reps}
+
+
+def verify_algorithmic_bytes(st):
+    """Vocabulary rows the acceptance walk has to read, from its own result (draft-initialised mode: one walk per
+    sequence): a context with at least one rejection needs its target and draft row (2 * V * 4 bytes, read once);
+    a terminal context without rejections needs its target row for the new token (V * 4 bytes); every tested
+    candidate needs p(x), q(x), its token id and its uniform (16 bytes).  None in target-initialised mode, where
+    the walks of the losing level-1 subtrees are not part of the result."""
+    if st.mode != 0:
+        return None
+    w = st.w
+    path = st.path.cpu().numpy()
+    alen = st.alen.cpu().numpy()
+    br = list(w.branching[:st.gamma])
+    off = [0]
+    for l, b in enumerate(br):
+        off.append(off[-1] + (b if l == 0 else (off[-1] - off[-2]) * b))
+    total = 0
+    for bi in range(w.B):
+        cur = -1
+        for level in range(st.gamma):
+            cnt = br[level]
+            first = 0 if cur < 0 else off[level] + (cur - off[level - 1]) * cnt
+            if level < alen[bi]:
+                rejected = int(path[bi, level]) - first
+                total += 16 * (rejected + 1) + (2 * w.V * 4 if rejected else 0)
+                cur = int(path[bi, level])
+            else:
+                total += 16 * cnt + 2 * w.V * 4          # every child rejected: terminal context
+                break
+        else:
+            total += w.V * 4 if st.n_new else 0          # all levels accepted: bonus token from one target row
+    return total
 
 
 def cpu_baseline(st, budget_s=20.0):
@@ -296,6 +329,11 @@ def main():
         "kernels_us": {"attn_sweep": roof["avg_launch_us"], "attn_merge": round(m_avg * 1e3, 2),
                        "verify_walk": round(v_avg * 1e3, 2)},
     }
+    vb = verify_algorithmic_bytes(st)
+    if vb is not None:          # the vocabulary pass: one workgroup per sequence, latency-bound at this batch size
+        out["verify_roofline"] = {"bound": "hbm", "kernel": "verify_walk_kernel", "achieved": round(vb / (v_avg * 1e-3) / 1e9, 2),
+                                  "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(vb / (v_avg * 1e-3) / 1e9 / HBM_PEAK_GBPS, 6),
+                                  "algorithmic_bytes_per_launch": int(vb), "avg_launch_us": round(v_avg * 1e3, 2)}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(st)
     del st
