@@ -56,6 +56,10 @@ def _load():
         L.mcsd_oracle_tree_sample.argtypes = [vp, i64, C.c_float]
         L.mcsd_oracle_improvement_factor.restype = f64
         L.mcsd_oracle_improvement_factor.argtypes = [f64, f64, f64]
+        L.mcsd_oracle_commit_path.restype = C.c_int
+        L.mcsd_oracle_commit_path.argtypes = [i32, i32, i32, i32, i32, i32, i64, vp, vp, vp, vp, vp, i64, vp, vp, vp, vp]
+        L.mcsd_oracle_commit_ids.restype = C.c_int
+        L.mcsd_oracle_commit_ids.argtypes = [i32, i32, i32, vp, vp, vp, vp, i32, i32, vp, vp]
         L.mcsd_oracle_threads.restype = i32
         L.mcsd_oracle_threads.argtypes = []
         _lib = L
@@ -182,6 +186,49 @@ def verify_tree(mode: int, branching: Sequence[int], tokens: np.ndarray, p: np.n
     if rc != 0:
         raise ValueError(f"oracle verify_tree failed: {rc}")
     return path, alen, new
+
+
+def commit_path(inp: dict, gamma: int, n: int, path: np.ndarray, accept_len: np.ndarray):
+    """Appends the accepted path's tree K/V rows to a COPY of the prefix cache of `inp` (one layer, as made by
+    workloads.attention_inputs).  Returns (k_prefix, v_prefix, lens) after the update."""
+    dt = inp["dtype"]
+    kt, vt = (_check_store(inp[k], dt) for k in ("k_tree", "v_tree"))
+    kp, vp = (_check_store(inp[k], dt).copy() for k in ("k_prefix", "v_prefix"))
+    B, H, _, d = kt.shape
+    path = np.ascontiguousarray(path, dtype=np.int32)
+    alen = np.ascontiguousarray(accept_len, dtype=np.int32)
+    assert path.shape == (B, gamma) and alen.shape == (B,)
+    lens = np.ascontiguousarray(inp["lens"], dtype=np.int32)
+    base = np.ascontiguousarray(inp["seq_base"], dtype=np.int64)
+    cap = kp.shape[2]
+    assert int((lens + alen).max()) <= cap, "cache too small for the accepted path"
+    lens_out = np.zeros(B, dtype=np.int32)
+    rc = _load().mcsd_oracle_commit_path(kt.itemsize, B, H, d, gamma, n, int(inp["node_stride"]), _ptr(kt), _ptr(vt),
+                                         _ptr(kp), _ptr(vp), _ptr(base), int(inp["head_stride"]), _ptr(path),
+                                         _ptr(alen), _ptr(lens), _ptr(lens_out))
+    if rc != 0:
+        raise ValueError("oracle commit_path: bad path or length")
+    return kp, vp, lens_out
+
+
+def commit_ids(gamma: int, tokens: np.ndarray, path: np.ndarray, accept_len: np.ndarray, new_tokens: np.ndarray,
+               n_append: int):
+    """(ids int32 [B][gamma + n_append] padded with -1, n_ids int32 [B])."""
+    tokens = np.ascontiguousarray(tokens, dtype=np.int32)
+    path = np.ascontiguousarray(path, dtype=np.int32)
+    alen = np.ascontiguousarray(accept_len, dtype=np.int32)
+    new = np.ascontiguousarray(new_tokens, dtype=np.int32).reshape(tokens.shape[0], -1)
+    B, n = tokens.shape
+    n_new = new.shape[1]
+    if n_new == 0:
+        new = np.zeros((B, 1), dtype=np.int32)
+    ids = np.zeros((B, gamma + n_append), dtype=np.int32)
+    n_ids = np.zeros(B, dtype=np.int32)
+    rc = _load().mcsd_oracle_commit_ids(B, gamma, n, _ptr(tokens), _ptr(path), _ptr(alen), _ptr(new), n_new, n_append,
+                                        _ptr(ids), _ptr(n_ids))
+    if rc != 0:
+        raise ValueError("oracle commit_ids: bad argument")
+    return ids, n_ids
 
 
 def tree_sum(a: np.ndarray) -> float:

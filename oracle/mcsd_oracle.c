@@ -379,6 +379,62 @@ int mcsd_oracle_verify_tree(int32_t mode, const int32_t *branching, int32_t G, i
     return rc;
 }
 
+/* ------------------------------------------------------------------------------------------------
+ * Update after acceptance (Fig. 1 step 6): the accepted path becomes part of the prefix.
+ * One layer's tensors.  For sequence b with accepted length a = accept_len[b] and old length L = lens[b]:
+ * cache row L + j of every head receives the tree K and V row of node path[b][j] (j = 0 .. a-1, root side
+ * first); the new length is L + a.  ids[b] lists the accepted tokens in that order followed by the first
+ * n_append new tokens, padded with -1 up to gamma + n_append entries; n_ids[b] counts the entries that are set.
+ * `lens_out` may be lens itself.  Elements are moved as raw storage (elem_bytes each).
+ * ---------------------------------------------------------------------------------------------- */
+int mcsd_oracle_commit_path(int32_t elem_bytes, int32_t B, int32_t H, int32_t d, int32_t gamma, int32_t n_nodes,
+                            int64_t node_stride, const void *k_tree, const void *v_tree, void *k_prefix,
+                            void *v_prefix, const int64_t *seq_base, int64_t head_stride, const int32_t *path,
+                            const int32_t *accept_len, const int32_t *lens, int32_t *lens_out)
+{
+    const char *kt = (const char *)k_tree, *vt = (const char *)v_tree;
+    char *kp = (char *)k_prefix, *vp = (char *)v_prefix;
+    for (int32_t b = 0; b < B; ++b) {
+        const int32_t a = accept_len[b], L = lens[b];
+        if (a < 0 || a > gamma || L < 0) return -1;
+        for (int32_t j = 0; j < a; ++j) {
+            const int32_t node = path[(int64_t)b * gamma + j];
+            if (node < 0 || node >= n_nodes) return -1;
+            for (int32_t h = 0; h < H; ++h) {
+                const int64_t src = ((((int64_t)b * H + h) * node_stride + node) * d) * elem_bytes;
+                const int64_t dst = (seq_base[b] + (int64_t)h * head_stride + (int64_t)(L + j) * d) * elem_bytes;
+                memcpy(kp + dst, kt + src, (size_t)d * elem_bytes);
+                memcpy(vp + dst, vt + src, (size_t)d * elem_bytes);
+            }
+        }
+    }
+    for (int32_t b = 0; b < B; ++b) lens_out[b] = lens[b] + accept_len[b];
+    return 0;
+}
+
+/* The token ids that the accepted path adds to the input (Fig. 1 step 6). */
+int mcsd_oracle_commit_ids(int32_t B, int32_t gamma, int32_t n_nodes, const int32_t *tokens, const int32_t *path,
+                           const int32_t *accept_len, const int32_t *new_tokens, int32_t n_new, int32_t n_append,
+                           int32_t *ids, int32_t *n_ids)
+{
+    if (n_append < 0 || n_append > n_new) return -1;
+    const int32_t W = gamma + n_append;
+    for (int32_t b = 0; b < B; ++b) {
+        const int32_t a = accept_len[b];
+        if (a < 0 || a > gamma) return -1;
+        int32_t k = 0;
+        for (int32_t j = 0; j < a; ++j) {
+            const int32_t node = path[(int64_t)b * gamma + j];
+            if (node < 0 || node >= n_nodes) return -1;
+            ids[(int64_t)b * W + k++] = tokens[(int64_t)b * n_nodes + node];
+        }
+        for (int32_t j = 0; j < n_append; ++j) ids[(int64_t)b * W + k++] = new_tokens[(int64_t)b * n_new + j];
+        n_ids[b] = k;
+        for (; k < W; ++k) ids[(int64_t)b * W + k] = -1;
+    }
+    return 0;
+}
+
 /* Exposed for the tests that pin the summation order and the sampler on their own. */
 double mcsd_oracle_tree_sum(const double *a, int64_t V)
 {
