@@ -95,6 +95,16 @@ class Step:
                       vi["q_draft"].shape[1] * w.V, self.ua, self.us, self.n_new, self.path, self.alen, self.new,
                       self.vws)
 
+    def commit(self, lens_dev, ids, n_ids):
+        """Update after acceptance over all layers' caches (not part of the timed step: the row after it).  The
+        benchmark's caches are exactly prefix_max rows long, so lengths are clamped gamma rows below that."""
+        w, b = self.w, self.binding
+        L = self.layers
+        b.commit_path(self.view, L[0].code, w.B, w.H, w.d, [a.kt for a in L], [a.vt for a in L], L[0].node_stride,
+                      [a.kp for a in L], [a.vp for a in L], L[0].base, L[0].head_stride, self.cap - self.gamma, self.cap,
+                      self.path, self.alen, self.tokens, self.new, self.n_new, 1 if self.mode == 0 else 0, lens_dev,
+                      ids, n_ids)
+
     def step(self):
         self.view = self.binding.slice_mask(self.mask, self.gamma)    # O(1): the per-step slice
         for l in range(N_LAYERS):
@@ -336,6 +346,23 @@ def main():
                                   "algorithmic_bytes_per_launch": int(vb), "avg_launch_us": round(v_avg * 1e3, 2)}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(st)
+    # the row after the step: accepted path appended to every layer's cache (last: it overwrites cache rows)
+    ids = torch.zeros((w.B, st.gamma + 1), dtype=torch.int32, device="cuda")
+    n_ids = torch.zeros((w.B,), dtype=torch.int32, device="cuda")
+    lens_c = st.layers[0].lens.clone()
+
+    def commit_once(i):
+        lens_c.copy_(st.layers[0].lens)
+        st.commit(lens_c, ids, n_ids)
+    c_avg = time_kernel(st, hip, binding.KERNEL_COMMIT_COPY, commit_once, 20, warm=5)[0]
+    torch.cuda.synchronize()
+    t0c = time.perf_counter()
+    for i in range(20):
+        st.commit(lens_c, ids, n_ids)
+    torch.cuda.synchronize()
+    out["commit_path"] = {"layers_per_call": len(st.layers), "copy_kernel_us": round(c_avg * 1e3, 2),
+                          "call_us": round((time.perf_counter() - t0c) / 20 * 1e6, 1),
+                          "mean_accept_len": round(float(st.alen.float().mean().item()), 3)}
     del st
     torch.cuda.empty_cache()
 

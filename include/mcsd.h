@@ -7,7 +7,8 @@
  *   - the target model's tree-attention pass: every tree node attends to the prefix KV cache and to its
  *     own ancestors in the tree (Sec. 2.2);
  *   - multi-candidate acceptance by recursive rejection sampling, longest-path selection for
- *     target-initialised trees and sampling of the new token(s) (Sec. 2.1, Sec. 3.1, Fig. 1 steps 4-6).
+ *     target-initialised trees and sampling of the new token(s) (Sec. 2.1, Sec. 3.1, Fig. 1 steps 4-6);
+ *   - the update after acceptance: the accepted path's K/V rows join the prefix cache (Fig. 1 step 6).
  *
  * Plain C ABI.  Every pointer is marked HOST or DEVICE.  The library owns only mask handles; every
  * tensor and workspace belongs to the caller.  Device work is enqueued on the caller's HIP stream and
@@ -155,12 +156,47 @@ int mcsd_verify_tree(const mcsd_mask_view_t *mask, mcsd_mode_t mode, int32_t B, 
                      int32_t *out_new_tokens, void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /* ---------------------------------------------------------------------------------------------------
+ * Update after acceptance (Fig. 1 step 6): the accepted path becomes part of the prefix.
+ *
+ * For every sequence b with a = accept_len[b] (0..gamma) and L = prefix_lens[b] (clamped to 0..max_prefix):
+ * in each of the n_layers layers, cache row L + j of every head receives the tree K and V row of node
+ * out_path[b][j], j = 0 .. a-1 (root side first); then prefix_lens[b] becomes L + a.  out_ids[b] receives the
+ * accepted tokens tokens[b][out_path[b][j]] in that order followed by the first n_append new tokens
+ * (draft-initialised decoding appends the one new token to the input, n_append = 1; with a target-initialised tree
+ * the new tokens are the next tree's first level, n_append = 0), padded with -1; out_n_ids[b] counts the ids set.
+ *
+ * k_tree, v_tree     : HOST arrays [n_layers] of DEVICE pointers, each [B][H][node_stride][d] (read)
+ * k_prefix, v_prefix : HOST arrays [n_layers] of DEVICE pointers to the caches, addressed as in
+ *                      mcsd_tree_attention (seq_base_dev, head_stride shared by all layers); rows
+ *                      L .. L+a-1 of every head are written, nothing else
+ * capacity           : rows every (sequence, head) of the caches can hold; max_prefix + gamma <= capacity is
+ *                      required, so a write can never leave the cache
+ * out_path_dev, accept_len_dev, new_tokens_dev : as written by mcsd_verify_tree (DEVICE); tokens_dev as given to it
+ * prefix_lens_dev    : DEVICE int32 [B], read and updated in place
+ * out_ids_dev        : DEVICE int32 [B][gamma + n_append];  out_n_ids_dev: DEVICE int32 [B]
+ * Node ids outside 0..n_nodes-1 and lengths outside 0..gamma are skipped / clamped, never dereferenced.
+ * Limits: 1 <= n_layers <= MCSD_COMMIT_MAX_LAYERS per call; d*sizeof(element) a multiple of 16; tensor base
+ * addresses 16-byte aligned; node_stride*d, head_stride and seq_base multiples of 8 elements.
+ * Two launches on the stream: the copies, then the lengths and ids (so prefix_lens is updated in place).
+ * ------------------------------------------------------------------------------------------------- */
+enum { MCSD_COMMIT_MAX_LAYERS = 64 };
+
+int mcsd_commit_path(const mcsd_mask_view_t *mask, mcsd_dtype_t dtype, int32_t B, int32_t H, int32_t d,
+                     int32_t n_layers, const void *const *k_tree, const void *const *v_tree, int64_t node_stride,
+                     void *const *k_prefix, void *const *v_prefix, const int64_t *seq_base_dev,
+                     int64_t head_stride, int32_t max_prefix, int32_t capacity, const int32_t *out_path_dev,
+                     const int32_t *accept_len_dev, const int32_t *tokens_dev, const int32_t *new_tokens_dev,
+                     int32_t n_new, int32_t n_append, int32_t *prefix_lens_dev, int32_t *out_ids_dev,
+                     int32_t *out_n_ids_dev, void *hip_stream);
+
+/* ---------------------------------------------------------------------------------------------------
  * Measurement aid (not part of the method).  Arms a one-shot pair of HIP events (hipEvent_t, created by the
  * caller with timing enabled) for one of the library's kernels: the next launch of that kernel by the calling
  * process is bracketed by them, so hipEventElapsedTime(start, stop) is that kernel's own execution time on
  * the device.  The arming is consumed by that launch.  Passing NULL events disarms.  Not thread-safe.
  * ------------------------------------------------------------------------------------------------- */
-typedef enum { MCSD_KERNEL_ATTN_SWEEP = 0, MCSD_KERNEL_ATTN_MERGE = 1, MCSD_KERNEL_VERIFY_WALK = 2 } mcsd_kernel_t;
+typedef enum { MCSD_KERNEL_ATTN_SWEEP = 0, MCSD_KERNEL_ATTN_MERGE = 1, MCSD_KERNEL_VERIFY_WALK = 2,
+               MCSD_KERNEL_COMMIT_COPY = 3 } mcsd_kernel_t;
 int mcsd_profile_next(mcsd_kernel_t kernel, void *start_event, void *stop_event);
 
 #ifdef __cplusplus

@@ -16,7 +16,7 @@ MCSD_DRAFT_INIT, MCSD_TARGET_INIT = 0, 1
 
 EXPORTS = ["mcsd_strerror", "mcsd_build_mask", "mcsd_slice_mask", "mcsd_free_mask",
            "mcsd_tree_attention_workspace", "mcsd_tree_attention",
-           "mcsd_verify_tree_workspace", "mcsd_verify_tree", "mcsd_profile_next"]
+           "mcsd_verify_tree_workspace", "mcsd_verify_tree", "mcsd_commit_path", "mcsd_profile_next"]
 
 
 class MaskView(C.Structure):
@@ -65,13 +65,17 @@ def _load() -> C.CDLL:
     lib.mcsd_verify_tree.argtypes = [C.POINTER(MaskView), C.c_int, i32, i32, vp, vp, vp, i64, i64, vp, vp, i32,
                                      vp, vp, vp, vp, sz, vp]
     lib.mcsd_profile_next.restype = C.c_int
+    lib.mcsd_commit_path.restype = C.c_int
+    lib.mcsd_commit_path.argtypes = [C.POINTER(MaskView), C.c_int, i32, i32, i32, i32, C.POINTER(vp), C.POINTER(vp),
+                                     i64, C.POINTER(vp), C.POINTER(vp), vp, i64, i32, i32, vp, vp, vp, vp, i32, i32,
+                                     vp, vp, vp, vp]
     lib.mcsd_profile_next.argtypes = [C.c_int, vp, vp]
     return lib
 
 
 lib = _load()
 
-KERNEL_ATTN_SWEEP, KERNEL_ATTN_MERGE, KERNEL_VERIFY_WALK = 0, 1, 2
+KERNEL_ATTN_SWEEP, KERNEL_ATTN_MERGE, KERNEL_VERIFY_WALK, KERNEL_COMMIT_COPY = 0, 1, 2, 3
 
 
 def strerror(status: int) -> str:
@@ -161,6 +165,26 @@ def verify_tree(view: MaskView, mode: int, B: int, V: int, tokens: torch.Tensor,
                               q_batch_stride, _ptr(u_accept), _ptr(u_sample), n_new, _ptr(out_path),
                               _ptr(out_accept_len), _ptr(out_new_tokens), _ptr(workspace), ws_bytes, _stream(stream))
     _check(st, "mcsd_verify_tree")
+
+
+def _ptr_array(tensors: Sequence[torch.Tensor]):
+    return (C.c_void_p * len(tensors))(*[t.data_ptr() for t in tensors])
+
+
+def commit_path(view: MaskView, dtype: int, B: int, H: int, d: int, k_tree: Sequence[torch.Tensor],
+                v_tree: Sequence[torch.Tensor], node_stride: int, k_prefix: Sequence[torch.Tensor],
+                v_prefix: Sequence[torch.Tensor], seq_base_dev: torch.Tensor, head_stride: int, max_prefix: int,
+                capacity: int, out_path: torch.Tensor, accept_len: torch.Tensor, tokens: torch.Tensor,
+                new_tokens: Optional[torch.Tensor], n_new: int, n_append: int, prefix_lens_dev: torch.Tensor,
+                out_ids: torch.Tensor, out_n_ids: torch.Tensor, stream=None) -> None:
+    """One call for all layers: k_tree / v_tree / k_prefix / v_prefix are per-layer lists of device tensors."""
+    n_layers = len(k_tree)
+    assert len(v_tree) == len(k_prefix) == len(v_prefix) == n_layers
+    st = lib.mcsd_commit_path(C.byref(view), dtype, B, H, d, n_layers, _ptr_array(k_tree), _ptr_array(v_tree),
+                              node_stride, _ptr_array(k_prefix), _ptr_array(v_prefix), _ptr(seq_base_dev), head_stride,
+                              max_prefix, capacity, _ptr(out_path), _ptr(accept_len), _ptr(tokens), _ptr(new_tokens),
+                              n_new, n_append, _ptr(prefix_lens_dev), _ptr(out_ids), _ptr(out_n_ids), _stream(stream))
+    _check(st, "mcsd_commit_path")
 
 
 def mask_bits_host(view: MaskView):

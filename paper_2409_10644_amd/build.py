@@ -19,6 +19,7 @@ SOURCES = {
     "mask.cpp": ["-x", "hip"],
     "tree_attention.hip": [],
     "verify_tree.hip": ["-ffp-contract=off"],
+    "commit_path.hip": [],
 }
 
 

@@ -443,3 +443,99 @@ def test_step_replayed_from_a_hip_graph_matches_eager_launches(binding, oracle, 
     M = oracle.build_mask(w.branching)
     H.assert_close(ad.out[:, :, :v.n_nodes].float().cpu().numpy().astype(np.float64),
                    oracle.tree_attention(inp, M, v.n_nodes), "bf16", "graph replay")
+
+
+# ------------------------------------------------------------------------------------------------
+# update after acceptance: the accepted path joins the prefix cache (Fig. 1 step 6)
+# ------------------------------------------------------------------------------------------------
+def _commit_case(binding, oracle, H, w, mode, lens, n_layers, seed, gamma=None, explicit=None):
+    gamma = w.gamma_max if gamma is None else gamma
+    cap = int(max(lens)) + gamma + 5
+    layers_host = [attention_inputs(w, seed=seed, lens=lens, kv_capacity=cap, variant=l) for l in range(n_layers)]
+    layers = [H.AttnDevice(inp) for inp in layers_host]
+    v = binding.slice_mask(binding.build_mask(w.branching), gamma)
+    vi = verify_inputs(w, seed=seed, gamma=gamma, mode=mode)
+    path, alen, new = H.run_verify(binding, v, mode, vi)                       # numpy results of the GPU walk
+    want_v = oracle.verify_tree(mode, w.branching[:gamma], vi["tokens"], vi["p_target"], vi["q_draft"], vi["u_accept"],
+                                vi["u_sample"])
+    assert np.array_equal(path, want_v[0]) and np.array_equal(alen, want_v[1])
+    if explicit is not None:                                                   # paths chosen by hand instead
+        path, alen = explicit
+    n_new = vi["u_sample"].shape[1]
+    n_append = 1 if mode == DRAFT_INIT and n_new > 0 else 0
+    d_path, d_alen, d_new = H.dev(path), H.dev(alen), H.dev(new.reshape(w.B, -1))
+    d_tokens = H.dev(vi["tokens"])
+    lens_dev = layers[0].lens.clone()
+    ids = torch.full((w.B, gamma + n_append), -9, dtype=torch.int32, device="cuda")
+    n_ids = torch.full((w.B,), -9, dtype=torch.int32, device="cuda")
+    a0 = layers[0]
+    binding.commit_path(v, a0.code, a0.B, a0.H, a0.d, [a.kt for a in layers], [a.vt for a in layers], a0.node_stride,
+                        [a.kp for a in layers], [a.vp for a in layers], a0.base, a0.head_stride, int(max(lens)), cap,
+                        d_path, d_alen, d_tokens, d_new, n_new, n_append, lens_dev, ids, n_ids)
+    torch.cuda.synchronize()
+    for l, (inp, ad) in enumerate(zip(layers_host, layers)):
+        kp, vp, new_lens = oracle.commit_path(inp, gamma, v.n_nodes, path, alen)
+        store = torch.int16 if inp["dtype"] == "bf16" else torch.float32
+        assert np.array_equal(ad.kp.view(store).cpu().numpy().view(kp.dtype), kp), f"layer {l}: K cache differs"
+        assert np.array_equal(ad.vp.view(store).cpu().numpy().view(vp.dtype), vp), f"layer {l}: V cache differs"
+    assert np.array_equal(lens_dev.cpu().numpy(), new_lens)
+    want_ids, want_n = oracle.commit_ids(gamma, vi["tokens"], path, alen, new.reshape(w.B, -1), n_append)
+    assert np.array_equal(ids.cpu().numpy(), want_ids) and np.array_equal(n_ids.cpu().numpy(), want_n)
+    return layers_host, layers, lens_dev, path, alen
+
+
+@pytest.mark.parametrize("mode", [DRAFT_INIT, TARGET_INIT])
+@pytest.mark.parametrize("name,B,Hh", [("cfg1", 1, 4), ("cfg2", 1, 32), ("cfg4", 16, 4), ("cfg5", 8, 4)])
+def test_commit_path_bit_exact(binding, oracle, H, name, B, Hh, mode):
+    w = scaled(WORKLOADS[name], B=B, H=Hh, cfg_id=70)
+    lens = [37 + 61 * b for b in range(B)]
+    _commit_case(binding, oracle, H, w, mode, lens, n_layers=3, seed=4)
+
+
+def test_commit_path_nothing_accepted_and_full_depth(binding, oracle, H):
+    w = scaled(WORKLOADS["cfg3"], B=4, H=2, cfg_id=71)
+    parent, level = oracle.tree_tables(w.branching)
+    path = np.full((4, 8), -1, dtype=np.int32)
+    alen = np.array([0, 8, 3, 1], dtype=np.int32)
+    for b, leaf in ((1, int(np.where(level == 8)[0][-1])), (2, int(np.where(level == 3)[0][4])), (3, 2)):
+        chain = []
+        while leaf >= 0:
+            chain.append(leaf)
+            leaf = int(parent[leaf])
+        path[b, :len(chain)] = chain[::-1]
+        assert len(chain) == alen[b]
+    _commit_case(binding, oracle, H, w, DRAFT_INIT, [0, 5, 64, 9], n_layers=2, seed=1, explicit=(path, alen))
+
+
+def test_commit_then_attend_over_the_grown_cache(binding, oracle, H):
+    """The next iteration's tree attention reads the cache and the lengths exactly as the commit left them."""
+    w = scaled(WORKLOADS["cfg2"], B=2, H=4, cfg_id=72)
+    lens = [200, 77]
+    layers_host, layers, lens_dev, path, alen = _commit_case(binding, oracle, H, w, TARGET_INIT, lens, n_layers=1, seed=6)
+    inp, ad = layers_host[0], layers[0]
+    kp, vp, new_lens = oracle.commit_path(inp, w.gamma_max, w.n_nodes(), path, alen)
+    assert int(alen.min()) >= 1
+    grown = dict(inp, k_prefix=kp, v_prefix=vp, lens=new_lens)
+    ad.lens.copy_(lens_dev)
+    v = binding.slice_mask(binding.build_mask(w.branching), w.gamma_max)
+    got = H.run_attention(binding, v, ad, max_prefix=int(max(lens)) + w.gamma_max)
+    want = oracle.tree_attention(grown, oracle.build_mask(w.branching), v.n_nodes)
+    H.assert_close(got, want, "bf16", "attention after commit")
+
+
+def test_commit_path_rejects_bad_arguments(binding, H):
+    w = scaled(WORKLOADS["cfg2"], B=1, H=2, cfg_id=73)
+    inp = attention_inputs(w, seed=0, lens=[10], kv_capacity=12)
+    ad = H.AttnDevice(inp)
+    v = binding.slice_mask(binding.build_mask(w.branching), 4)
+    z = torch.zeros((1, 8), dtype=torch.int32, device="cuda")
+    args = lambda n_layers, cap, n_append: (v, ad.code, 1, 2, ad.d, [ad.kt] * n_layers, [ad.vt] * n_layers, ad.node_stride,
+                                             [ad.kp] * n_layers, [ad.vp] * n_layers, ad.base, ad.head_stride, 10, cap,
+                                             z, z, z, z, 1, n_append, ad.lens, z, z)
+    with pytest.raises(RuntimeError):
+        binding.commit_path(*args(1, 12, 1))          # capacity < max_prefix + gamma
+    with pytest.raises(RuntimeError):
+        binding.commit_path(*args(65, 14, 1))         # more layers than one call takes
+    with pytest.raises(RuntimeError):
+        binding.commit_path(*args(1, 14, 2))          # n_append > n_new
+    torch.cuda.synchronize()
