@@ -346,6 +346,26 @@ def main():
                                   "algorithmic_bytes_per_launch": int(vb), "avg_launch_us": round(v_avg * 1e3, 2)}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(st)
+    # the draft side of the loop: attention for the newest level only, a fresh slice of the mask per level
+    lvl = {}
+    for g in range(1, st.gamma + 1):
+        vg = binding.slice_mask(st.mask, g)
+        rb = int(vg.level_off_host[g - 1])
+        ad = st.layers[0]
+
+        def level_call(i, vg=vg, rb=rb):
+            a = st.layers[i % len(st.layers)]
+            binding.tree_attention_rows(vg, a.code, w.B, w.H, w.d, rb, a.q, a.kt, a.vt, a.node_stride, a.kp, a.vp, a.base,
+                                        a.lens, a.head_stride, st.cap, a.scale, a.out, st.ws)
+        for i in range(8):
+            level_call(i)
+        torch.cuda.synchronize()
+        t0l = time.perf_counter()
+        for i in range(64):
+            level_call(i)
+        torch.cuda.synchronize()
+        lvl[f"gamma{g}_rows{vg.n_nodes - rb}"] = round((time.perf_counter() - t0l) / 64 * 1e6, 1)
+    out["level_attention_call_us"] = lvl
     # the row after the step: accepted path appended to every layer's cache (last: it overwrites cache rows)
     ids = torch.zeros((w.B, st.gamma + 1), dtype=torch.int32, device="cuda")
     n_ids = torch.zeros((w.B,), dtype=torch.int32, device="cuda")

@@ -119,6 +119,22 @@ int mcsd_tree_attention(const mcsd_mask_view_t *mask, mcsd_dtype_t dtype, int32_
                         float softmax_scale, void *out, void *workspace, size_t workspace_bytes,
                         void *hip_stream);
 
+/* The same attention for the query rows row_begin .. n_nodes-1 only (0 <= row_begin < n_nodes); rows below
+ * row_begin of q are not read and those of out are not written.  Keys are unchanged: the prefix and every tree
+ * node j < n_nodes that the mask shows to the row.  This is the draft side of Fig. 1 step 3 and Sec. 3.2: the tree
+ * grows level by level, each step takes the next slice of the mask built once and needs outputs only for the newest
+ * level, row_begin = level_off_host[gamma-1].  Arguments, limits and workspace rules as above, with the workspace
+ * sized by mcsd_tree_attention_rows_workspace (never more than mcsd_tree_attention_workspace of the same shape). */
+size_t mcsd_tree_attention_rows_workspace(int32_t B, int32_t H, int32_t d, int32_t n_nodes, int32_t row_begin,
+                                          int32_t max_prefix);
+
+int mcsd_tree_attention_rows(const mcsd_mask_view_t *mask, mcsd_dtype_t dtype, int32_t B, int32_t H, int32_t d,
+                             int32_t row_begin, const void *q, const void *k_tree, const void *v_tree,
+                             int64_t node_stride, const void *k_prefix, const void *v_prefix,
+                             const int64_t *seq_base_dev, const int32_t *prefix_lens_dev, int64_t head_stride,
+                             int32_t max_prefix, float softmax_scale, void *out, void *workspace,
+                             size_t workspace_bytes, void *hip_stream);
+
 /* ---------------------------------------------------------------------------------------------------
  * Verification (Sec. 2.1; Sec. 3.1; Fig. 1 steps 4-6)
  *

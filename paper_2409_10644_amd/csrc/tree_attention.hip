@@ -40,6 +40,7 @@ struct AttnParams {
     const uint64_t *mask_bits;
     int32_t mask_words;
     int32_t B, H, n;
+    int32_t row0;     // first query row: rows row0 .. n-1 are computed (keys are always all n tree nodes)
     int32_t max_prefix;
     int64_t node_stride, head_stride;
     float c;          // softmax_scale * log2(e)
@@ -62,11 +63,11 @@ struct AttnPlan {
 
 __host__ __device__ inline int tile_keys_bf16(int QBP) { return QBP == 1 ? 128 : 64; }   // == SweepCfg::T
 
-AttnPlan make_plan(int dtype, int B, int H, int n, int max_prefix)
+AttnPlan make_plan(int dtype, int B, int H, int n_rows, int max_prefix)
 {
     AttnPlan pl;
     if (dtype == MCSD_BF16) {
-        const int qb = (n + 31) / 32;
+        const int qb = (n_rows + 31) / 32;
         pl.QBP = qb <= 1 ? 1 : (qb == 2 ? 2 : 4);
         pl.T = tile_keys_bf16(pl.QBP);
     } else {
@@ -343,7 +344,7 @@ void tree_attn_bf16_kernel(const AttnParams p)
 
     // query block of this wavefront; mask row of this lane's query (zero for padded rows)
     QBlock<D> qs;
-    const int qrow = qb * 32 + ln;
+    const int qrow = p.row0 + qb * 32 + ln;
 #pragma unroll
     for (int ks = 0; ks < C::KS; ++ks) {
         uint4 v = make_uint4(0, 0, 0, 0);
@@ -580,7 +581,8 @@ __global__ __launch_bounds__(256) void tree_attn_merge_bf16_kernel(const AttnPar
     const int64_t bh = idx / ((int64_t)POS * QBP);
     if (bh >= (int64_t)p.B * p.H) return;
     const int ln = pos & 31, g = (pos >> 5) & 1, f = pos >> 6;
-    const int row = qb * 32 + ln;
+    const int lrow = qb * 32 + ln;                            // row of the partial results
+    const int row = p.row0 + lrow;                            // tree node
     if (row >= p.n) return;
     int L = p.lens[bh / p.H];
     L = L < 0 ? 0 : (L > p.max_prefix ? p.max_prefix : L);
@@ -600,7 +602,7 @@ __global__ __launch_bounds__(256) void tree_attn_merge_bf16_kernel(const AttnPar
             l[i] = 0.f;
             o[i] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
             if (s0 + i < n_active) {
-                const int64_t prow = (bh * p.SP + s0 + i) * (QBP * 32) + row;
+                const int64_t prow = (bh * p.SP + s0 + i) * (QBP * 32) + lrow;
                 m[i] = p.part_m[prow];
                 l[i] = p.part_l[prow];
                 o[i] = *(const f32x4_t *)(p.part_o + ((bh * p.SP + s0 + i) * (int64_t)(QBP * 32 * D)) + qb * 32 * D + pos * 4);
@@ -699,7 +701,7 @@ __global__ __launch_bounds__(256) void tree_attn_f32_kernel(const AttnParams p)
         __syncthreads();
         {   // raw scores
             const int j = tid % T, i0 = tid / T;
-            for (int i = i0; i < p.n; i += 256 / T) {
+            for (int i = p.row0 + i0; i < p.n; i += 256 / T) {
                 float dot = 0.f;
 #pragma unroll 8
                 for (int cc = 0; cc < D; ++cc) dot = fmaf(sQ[i][cc], sK[j][cc], dot);
@@ -712,7 +714,7 @@ __global__ __launch_bounds__(256) void tree_attn_f32_kernel(const AttnParams p)
             }
         }
         __syncthreads();
-        if (tid < p.n) {   // online softmax of row tid
+        if (tid >= p.row0 && tid < p.n) {   // online softmax of row tid
             float mx = -INFINITY;
             for (int j = 0; j < T; ++j) mx = fmaxf(mx, sS[tid][j]);
             const float m_new = fmaxf(m_run, mx);
@@ -732,7 +734,7 @@ __global__ __launch_bounds__(256) void tree_attn_f32_kernel(const AttnParams p)
 #pragma unroll
         for (int r = 0; r < NR; ++r) {
             const int i = oi0 + RP * r;
-            if (i < p.n) {
+            if (i >= p.row0 && i < p.n) {
                 float a = acc[r] * sAlpha[i];
 #pragma unroll 8
                 for (int j = 0; j < T; ++j) a = fmaf(sS[i][j], sV[j][oc], a);
@@ -748,16 +750,16 @@ __global__ __launch_bounds__(256) void tree_attn_f32_kernel(const AttnParams p)
 #pragma unroll
         for (int r = 0; r < NR; ++r) {
             const int i = oi0 + RP * r;
-            if (i < p.n) o[(int64_t)i * D + oc] = acc[r] / sL[i];
+            if (i >= p.row0 && i < p.n) o[(int64_t)i * D + oc] = acc[r] / sL[i];
         }
     } else {
         const int64_t prow0 = (bh * p.SP + s) * p.n;
 #pragma unroll
         for (int r = 0; r < NR; ++r) {
             const int i = oi0 + RP * r;
-            if (i < p.n) p.part_o[(prow0 + i) * D + oc] = acc[r];
+            if (i >= p.row0 && i < p.n) p.part_o[(prow0 + i) * D + oc] = acc[r];
         }
-        if (tid < p.n) {
+        if (tid >= p.row0 && tid < p.n) {
             p.part_m[prow0 + tid] = m_run;
             p.part_l[prow0 + tid] = l_run;
         }
@@ -774,7 +776,7 @@ __global__ __launch_bounds__(256) void tree_attn_merge_kernel(const AttnParams p
     constexpr int ROWS = 256 / TPR;       // rows per workgroup
     const int h = blockIdx.y, b = blockIdx.z;
     const int i = blockIdx.x * ROWS + threadIdx.x / TPR, c4 = (threadIdx.x % TPR) * 4;
-    if (i >= p.n) return;
+    if (i >= p.n || i < p.row0) return;
     const int64_t bh = (int64_t)b * p.H + h;
     int L = p.lens[b];
     L = L < 0 ? 0 : (L > p.max_prefix ? p.max_prefix : L);
@@ -866,15 +868,22 @@ hipError_t launch_f32(const AttnParams &p, const AttnPlan &pl, hipStream_t st)
 
 }  // namespace
 
-extern "C" size_t mcsd_tree_attention_workspace(int32_t B, int32_t H, int32_t d, int32_t n_nodes, int32_t max_prefix)
+extern "C" size_t mcsd_tree_attention_rows_workspace(int32_t B, int32_t H, int32_t d, int32_t n_nodes,
+                                                     int32_t row_begin, int32_t max_prefix)
 {
-    if (B < 1 || H < 1 || (d != 64 && d != 128) || n_nodes < 1 || n_nodes > MCSD_ATTN_MAX_NODES || max_prefix < 0)
+    if (B < 1 || H < 1 || (d != 64 && d != 128) || n_nodes < 1 || n_nodes > MCSD_ATTN_MAX_NODES || max_prefix < 0 ||
+        row_begin < 0 || row_begin >= n_nodes)
         return 0;
     // the larger of the two dtypes' needs, so one buffer serves both
-    const AttnPlan a = make_plan(MCSD_BF16, B, H, n_nodes, max_prefix);
-    const AttnPlan f = make_plan(MCSD_F32, B, H, n_nodes, max_prefix);
+    const AttnPlan a = make_plan(MCSD_BF16, B, H, n_nodes - row_begin, max_prefix);
+    const AttnPlan f = make_plan(MCSD_F32, B, H, n_nodes - row_begin, max_prefix);
     const size_t wa = workspace_bytes_for(a, MCSD_BF16, B, H, d, n_nodes), wf = workspace_bytes_for(f, MCSD_F32, B, H, d, n_nodes);
     return wa > wf ? wa : wf;
+}
+
+extern "C" size_t mcsd_tree_attention_workspace(int32_t B, int32_t H, int32_t d, int32_t n_nodes, int32_t max_prefix)
+{
+    return mcsd_tree_attention_rows_workspace(B, H, d, n_nodes, 0, max_prefix);
 }
 
 extern "C" int mcsd_tree_attention(const mcsd_mask_view_t *mask, mcsd_dtype_t dtype, int32_t B, int32_t H, int32_t d,
@@ -884,6 +893,19 @@ extern "C" int mcsd_tree_attention(const mcsd_mask_view_t *mask, mcsd_dtype_t dt
                                    float softmax_scale, void *out, void *workspace, size_t workspace_bytes,
                                    void *hip_stream)
 {
+    return mcsd_tree_attention_rows(mask, dtype, B, H, d, 0, q, k_tree, v_tree, node_stride, k_prefix, v_prefix,
+                                    seq_base_dev, prefix_lens_dev, head_stride, max_prefix, softmax_scale, out,
+                                    workspace, workspace_bytes, hip_stream);
+}
+
+extern "C" int mcsd_tree_attention_rows(const mcsd_mask_view_t *mask, mcsd_dtype_t dtype, int32_t B, int32_t H,
+                                        int32_t d, int32_t row_begin, const void *q, const void *k_tree,
+                                        const void *v_tree, int64_t node_stride, const void *k_prefix,
+                                        const void *v_prefix, const int64_t *seq_base_dev,
+                                        const int32_t *prefix_lens_dev, int64_t head_stride, int32_t max_prefix,
+                                        float softmax_scale, void *out, void *workspace, size_t workspace_bytes,
+                                        void *hip_stream)
+{
     if (!mask || !mask->bits_dev || !q || !k_tree || !v_tree || !out || !seq_base_dev || !prefix_lens_dev)
         return MCSD_EINVAL;
     if (dtype != MCSD_F32 && dtype != MCSD_BF16) return MCSD_EINVAL;
@@ -891,6 +913,7 @@ extern "C" int mcsd_tree_attention(const mcsd_mask_view_t *mask, mcsd_dtype_t dt
     if (max_prefix > 0 && (!k_prefix || !v_prefix)) return MCSD_EINVAL;
     const int32_t n = mask->n_nodes;
     if (n < 1 || node_stride < n || head_stride < 0) return MCSD_EINVAL;
+    if (row_begin < 0 || row_begin >= n) return MCSD_EINVAL;
     if (!(softmax_scale > 0.f) || !isfinite(softmax_scale)) return MCSD_EINVAL;
     if (d != 64 && d != 128) return MCSD_EUNSUPPORTED;
     if (n > MCSD_ATTN_MAX_NODES) return MCSD_EUNSUPPORTED;
@@ -899,7 +922,7 @@ extern "C" int mcsd_tree_attention(const mcsd_mask_view_t *mask, mcsd_dtype_t dt
     if (align & 15) return MCSD_EINVAL;
     if (((node_stride * d) & 7) || (head_stride & 7)) return MCSD_EINVAL;
 
-    const AttnPlan pl = make_plan(dtype, B, H, n, max_prefix);
+    const AttnPlan pl = make_plan(dtype, B, H, n - row_begin, max_prefix);
     const size_t need = workspace_bytes_for(pl, dtype, B, H, d, n);
     if (need > 0 && (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 255))) return MCSD_EWORKSPACE;
 
@@ -907,7 +930,7 @@ extern "C" int mcsd_tree_attention(const mcsd_mask_view_t *mask, mcsd_dtype_t dt
     p.q = q; p.kt = k_tree; p.vt = v_tree; p.kp = k_prefix; p.vp = v_prefix; p.out = out;
     p.seq_base = seq_base_dev; p.lens = prefix_lens_dev;
     p.mask_bits = mask->bits_dev; p.mask_words = mask->words_per_row;
-    p.B = B; p.H = H; p.n = n; p.max_prefix = max_prefix;
+    p.B = B; p.H = H; p.n = n; p.row0 = row_begin; p.max_prefix = max_prefix;
     p.node_stride = node_stride; p.head_stride = head_stride;
     p.c = softmax_scale * 1.4426950408889634f;
     p.S = pl.S; p.G = pl.G; p.SP = pl.G;

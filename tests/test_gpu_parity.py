@@ -539,3 +539,51 @@ def test_commit_path_rejects_bad_arguments(binding, H):
     with pytest.raises(RuntimeError):
         binding.commit_path(*args(1, 14, 2))          # n_append > n_new
     torch.cuda.synchronize()
+
+
+# ------------------------------------------------------------------------------------------------
+# draft side: attention for the newest tree level only, the mask sliced anew at every level (Fig. 1 step 3, Sec. 3.2)
+# ------------------------------------------------------------------------------------------------
+def _attend_rows(binding, H, v, ad, row_begin, max_prefix, fill):
+    ws_bytes = binding.tree_attention_rows_workspace(ad.B, ad.H, ad.d, v.n_nodes, row_begin, max_prefix)
+    assert ws_bytes <= binding.tree_attention_workspace(ad.B, ad.H, ad.d, v.n_nodes, max_prefix)
+    ws = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device="cuda")
+    ad.out.fill_(fill)
+    binding.tree_attention_rows(v, ad.code, ad.B, ad.H, ad.d, row_begin, ad.q, ad.kt, ad.vt, ad.node_stride, ad.kp,
+                                ad.vp, ad.base, ad.lens, ad.head_stride, max_prefix, ad.scale, ad.out, ws)
+    torch.cuda.synchronize()
+    return ad.out.float().cpu().numpy().astype(np.float64)
+
+
+@pytest.mark.parametrize("name,B,Hh,lens", [("cfg3", 1, 32, None), ("cfg5", 2, 4, (700, 33)), ("cfg1", 1, 4, None),
+                                            ("cfg4", 16, 32, None)])
+def test_level_by_level_attention_with_a_fresh_slice_per_level(binding, oracle, H, name, B, Hh, lens):
+    w = scaled(WORKLOADS[name], B=B, H=Hh, cfg_id=80)
+    if name == "cfg4":
+        w = scaled(w, prefix_min=64, prefix_max=512)
+    inp = attention_inputs(w, seed=8, lens=lens)
+    ad = H.AttnDevice(inp)
+    m = binding.build_mask(w.branching)                      # once, for the deepest tree
+    M = oracle.build_mask(w.branching)
+    for g in range(1, w.gamma_max + 1):
+        v = binding.slice_mask(m, g)
+        row_begin = int(v.level_off_host[g - 1])
+        out = _attend_rows(binding, H, v, ad, row_begin, ad.max_prefix, fill=55.0)
+        want = oracle.tree_attention(inp, M, v.n_nodes)
+        H.assert_close(out[:, :, row_begin:v.n_nodes], want[:, :, row_begin:], w.dtype, f"{name} level {g}")
+        assert np.all(out[:, :, :row_begin] == 55.0) and np.all(out[:, :, v.n_nodes:] == 55.0), "rows outside the level touched"
+
+
+@pytest.mark.parametrize("row_begin", [0, 1, 31, 32, 33, 64, 100, 119])
+def test_attention_rows_any_first_row(binding, oracle, H, row_begin):
+    w = scaled(WORKLOADS["cfg5"], B=1, H=8, cfg_id=81)
+    inp = attention_inputs(w, seed=row_begin, lens=(1500,))
+    ad = H.AttnDevice(inp)
+    v = binding.slice_mask(binding.build_mask(w.branching), w.gamma_max)
+    out = _attend_rows(binding, H, v, ad, row_begin, 1500, fill=-4.0)
+    want = oracle.tree_attention(inp, oracle.build_mask(w.branching), v.n_nodes)
+    H.assert_close(out[:, :, row_begin:v.n_nodes], want[:, :, row_begin:], "bf16", f"rows from {row_begin}")
+    assert np.all(out[:, :, :row_begin] == -4.0)
+    with pytest.raises(binding.McsdError):
+        binding.tree_attention_rows(v, ad.code, 1, 8, ad.d, v.n_nodes, ad.q, ad.kt, ad.vt, ad.node_stride, ad.kp, ad.vp,
+                                    ad.base, ad.lens, ad.head_stride, 1500, ad.scale, ad.out, None)
