@@ -390,6 +390,48 @@ def test_verify_special_rows(binding, oracle, H):
                 assert np.array_equal(a, b_), (name, mode, a, b_)
 
 
+@pytest.mark.parametrize("mode", [DRAFT_INIT, TARGET_INIT])
+def test_verify_fork_shaped_tree_width_16_depth_5(binding, oracle, H, mode):
+    """The paper's dynamic setting: 16 candidates at the root (up to 16 rejection rounds there), chains below."""
+    w = scaled(WORKLOADS["fork"], B=4)
+    _check_verify(binding, oracle, H, w, mode)
+    _check_verify(binding, oracle, H, w, mode, gamma=3, seed=5)
+
+
+@pytest.mark.parametrize("mode", [DRAFT_INIT, TARGET_INIT])
+def test_verify_greedy_target_rows(binding, oracle, H, mode):
+    """Temperature 0 (Sec. 4.1): one-hot target rows.  A candidate is accepted iff it is the target's arg-max, and
+    the new token is the arg-max of the row the walk ends on; the general rule must reduce to that."""
+    w = scaled(WORKLOADS["cfg2"], B=6, V=5000, cfg_id=63)
+    vi = verify_inputs(w, seed=3, mode=mode)
+    p = vi["p_target"]
+    top = p.argmax(-1)
+    hot = np.zeros_like(p)
+    np.put_along_axis(hot, top[..., None], 1.0, axis=-1)
+    tokens = vi["tokens"].copy()
+    # make some candidates hit the arg-max of their context so that paths of several lengths occur
+    parent, _ = oracle.tree_tables(w.branching)
+    rng = np.random.default_rng(12)
+    for b in range(w.B):
+        for node in range(tokens.shape[1]):
+            if rng.random() < 0.45:
+                tokens[b, node] = top[b, 1 + parent[node]]
+    vi = dict(vi, p_target=hot, tokens=tokens)
+    v = binding.slice_mask(binding.build_mask(w.branching), w.gamma_max)
+    path, alen, new = H.run_verify(binding, v, mode, vi)
+    want = oracle.verify_tree(mode, w.branching, tokens, hot, vi["q_draft"], vi["u_accept"], vi["u_sample"])
+    for a, b_ in zip((path, alen, new), want):
+        assert np.array_equal(a, b_)
+    assert len(set(alen.tolist())) > 1
+    for b in range(w.B):
+        start = 1 if mode == TARGET_INIT else 0           # level-1 nodes of a target-initialised tree are untested
+        for j in range(start, alen[b]):
+            ctx = -1 if j == 0 else path[b, j - 1]
+            assert tokens[b, path[b, j]] == top[b, 1 + ctx]
+        last = path[b, alen[b] - 1] if alen[b] else -1
+        assert np.all(new[b] == top[b, 1 + last])
+
+
 def test_verify_without_new_tokens(binding, oracle, H):
     w = scaled(WORKLOADS["cfg1"], B=3, cfg_id=62)
     _check_verify(binding, oracle, H, w, DRAFT_INIT, n_new=0)

@@ -427,3 +427,39 @@ def test_workload_generator_shapes_and_acceptance(oracle):
     assert alen.min() >= 0 and alen.max() <= 4 and new.min() >= 0 and new.max() < 2000
     for b in range(8):
         assert np.all(path[b, :alen[b]] >= 0) and np.all(path[b, alen[b]:] == -1)
+
+
+def test_one_hot_target_rows_reduce_to_arg_max_matching(oracle):
+    """Greedy decoding (temperature 0, Sec. 4.1): with one-hot target rows the rejection rule accepts a candidate
+    exactly when it is the target's arg-max, whatever the draft row and the uniform, and the new token is the
+    arg-max of the row the walk ends on."""
+    rng = np.random.default_rng(21)
+    br, V, B = (3, 2, 2), 50, 40
+    parent, level = oracle.tree_tables(br)
+    N, Nin = len(parent), int((level < 3).sum())
+    top = rng.integers(0, V, size=(B, 1 + N))
+    p = np.zeros((B, 1 + N, V), dtype=np.float32)
+    np.put_along_axis(p, top[..., None], 1.0, axis=-1)
+    q = rng.random((B, 1 + Nin, V)).astype(np.float32)
+    q /= q.sum(-1, keepdims=True)
+    tokens = rng.integers(0, V, size=(B, N)).astype(np.int32)
+    for b in range(B):
+        for node in range(N):
+            if rng.random() < 0.5:
+                tokens[b, node] = top[b, 1 + parent[node]]
+    ua = rng.random((B, N), dtype=np.float32)
+    us = rng.random((B, 1), dtype=np.float32)
+    path, alen, new = oracle.verify_tree(0, br, tokens, p, q.astype(np.float32), ua, us)
+    for b in range(B):
+        # textbook greedy walk: first child (in node order) whose token is the arg-max of its context
+        cur, want = -1, []
+        for lv in range(3):
+            kids = [n for n in range(N) if parent[n] == cur and level[n] == lv + 1]
+            hit = [n for n in kids if tokens[b, n] == top[b, 1 + cur]]
+            if not hit:
+                break
+            cur = hit[0]
+            want.append(cur)
+        assert alen[b] == len(want) and path[b, :len(want)].tolist() == want
+        assert new[b, 0] == top[b, 1 + cur]
+    assert len(set(alen.tolist())) >= 3
