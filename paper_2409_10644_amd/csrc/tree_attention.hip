@@ -88,10 +88,6 @@ AttnPlan make_plan(int dtype, int B, int H, int n_rows, int max_prefix)
         if (v >= 1 && v <= 64) S = v;
     }
     pl.NS = 2;                                              // double buffer, two workgroups per compute unit
-    if (const char *ov = getenv("MCSD_ATTN_STAGES")) {      // tuning override: 2 or 4 stages
-        const long v = atol(ov);
-        if ((v == 2 || v == 4) && pl.QBP > 1) pl.NS = (int)v;
-    }
     pl.S = (int)S;
     // With split keys the tree's own tiles (masked, through registers) would lengthen one split's critical path:
     // they get a workgroup of their own, which costs one more partial result.  Only when all workgroups are
@@ -274,10 +270,26 @@ __device__ inline void attn_tile(const unsigned char *stage, const LaneAddr la, 
     const float mc = (qs.m_ref == -INFINITY ? 0.f : qs.m_ref) * c;
     u32x4_t pb[U][2];
     float psum = 0.f;
+    // With one block per wavefront the exponentials of its second half of keys (registers 8..15, the operand of the
+    // second k-step pair) run in the shadow of the first half's PV MFMAs.
 #pragma unroll
-    for (int r = 0; r < 16; r += 2) softmax_exp2(sacc[0], r, c, mc, psum, pb[0]);
+    for (int r = 0; r < (U == 1 ? 8 : 16); r += 2) softmax_exp2(sacc[0], r, c, mc, psum, pb[0]);
     __builtin_amdgcn_sched_barrier(0);
     // O^T[c][query] += V^T[c][key] * P^T[key][query]
+    if (U == 1) {
+#pragma unroll
+        for (int cb = 0; cb < C::CB; ++cb) {
+            qs.o[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[0][0][cb], __builtin_bit_cast(bf16x8_t, pb[0][0]), qs.o[cb], 0, 0, 0);
+            if (C::CB == 4) softmax_exp2(sacc[0], 8 + 2 * cb, c, mc, psum, pb[0]);
+            else { softmax_exp2(sacc[0], 8 + 4 * cb, c, mc, psum, pb[0]); softmax_exp2(sacc[0], 10 + 4 * cb, c, mc, psum, pb[0]); }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+#pragma unroll
+        for (int cb = 0; cb < C::CB; ++cb)
+            qs.o[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[0][1][cb], __builtin_bit_cast(bf16x8_t, pb[0][1]), qs.o[cb], 0, 0, 0);
+        qs.l_run += psum;
+        return;
+    }
     if (U == 2) {
         read_v(1);
         __builtin_amdgcn_sched_barrier(0);
@@ -379,12 +391,12 @@ void tree_attn_bf16_kernel(const AttnParams p)
     // ---- full prefix tiles: HBM -> LDS directly, one tile ahead of the compute ----
     if (n_hot > 0) {
         // lane's source offset inside a tile for instruction i: row G*RPI + lane/CPR, logical chunk (lane%CPR)^swz(row)
-        int goff[C::NI];
+        uint32_t goff[C::NI];
 #pragma unroll
         for (int i = 0; i < C::NI; ++i) {
             const int G = i * C::WAVES + wave;
             const int r = G * C::RPI + lane / C::CPR;
-            goff[i] = r * C::RB + (((lane % C::CPR) ^ swz<D>(r)) * 16);
+            goff[i] = (uint32_t)(r * C::RB + (((lane % C::CPR) ^ swz<D>(r)) * 16));
         }
         const unsigned char *ksrc = kp + (int64_t)t0 * C::TILE_K;
         const unsigned char *vsrc = vp + (int64_t)t0 * C::TILE_K;
@@ -394,43 +406,49 @@ void tree_attn_bf16_kernel(const AttnParams p)
         // together would otherwise sweep their equally aligned K/V streams in lock-step and crowd the same
         // memory channels.  `nxt` is the tile the next issue fetches.
         int nxt = (int)(((unsigned)wg * 37u) % (unsigned)n_hot);
-        auto issue_tile = [&](auto stage) {
+        // load number i (0 .. DPT-1) of tile `nxt` into a stage: even i fetch K row groups, odd i the same of V
+        // (uniform tile base + 32-bit lane offset: the load takes its base from scalar registers)
+        const unsigned char *kbase = ksrc + (int64_t)nxt * C::TILE_K, *vbase = vsrc + (int64_t)nxt * C::TILE_K;
+        auto issue_load = [&](int i, auto stage) {
             unsigned char *dst = ring + decltype(stage)::value * C::TILE + wave * 1024;
             static_assert(decltype(stage)::value < NS, "stage out of range");
-#pragma unroll
-            for (int i = 0; i < C::NI; ++i) {
-                load_to_lds16(ksrc + (int64_t)nxt * C::TILE_K + goff[i], dst + i * C::WAVES * 1024);
-                load_to_lds16(vsrc + (int64_t)nxt * C::TILE_K + goff[i], dst + C::TILE_K + i * C::WAVES * 1024);
-            }
-            nxt = nxt + 1 == n_hot ? 0 : nxt + 1;
+            load_to_lds16(((i & 1) ? vbase : kbase) + goff[i >> 1], dst + (i & 1) * C::TILE_K + (i >> 1) * C::WAVES * 1024);
         };
-        auto step = [&](int it, auto stage) {
+        auto advance = [&]() {
+            nxt = nxt + 1 == n_hot ? 0 : nxt + 1;
+            kbase = ksrc + (int64_t)nxt * C::TILE_K;
+            vbase = vsrc + (int64_t)nxt * C::TILE_K;
+        };
+        auto issue_tile = [&](auto stage) {
+#pragma unroll
+            for (int i = 0; i < C::DPT; ++i) issue_load(i, stage);
+            advance();
+        };
+        auto step = [&](int it, auto stage, auto prefetching) {
             constexpr int ST = decltype(stage)::value;
+            constexpr bool PF = decltype(prefetching)::value;    // a later tile is fetched into the stage just freed
             // this wavefront's part of tile `it` has landed once at most NS-2 later tiles are outstanding
-            if (NS > 2 && it + NS - 2 < n_hot) MCSD_WAIT_VMCNT((NS - 2) * C::DPT);
-            else MCSD_WAIT_VMCNT(0);
+            MCSD_WAIT_VMCNT(0);
             __builtin_amdgcn_s_barrier();                     // ... and everyone's; the stage of tile it-1 is free again
-            if (it + NS - 1 < n_hot) issue_tile(std::integral_constant<int, (ST + NS - 1) % NS>());
+            // (spreading these loads over the tile's MFMAs instead of issuing them in one burst was measured: no gain)
+            if (PF) issue_tile(std::integral_constant<int, (ST + NS - 1) % NS>());
             attn_tile<D, QBP, NS, 0>(ring + ST * C::TILE, la, qs, p.c, g, all_keys);
         };
-        issue_tile(std::integral_constant<int, 0>());
-        if (NS > 2) {
-            if (1 < n_hot) issue_tile(std::integral_constant<int, 1 % NS>());
-            if (2 < n_hot) issue_tile(std::integral_constant<int, 2 % NS>());
-        }
+        static_assert(NS == 2, "the step sequence below is written for a double buffer");
+        using S0 = std::integral_constant<int, 0>;
+        using S1 = std::integral_constant<int, 1>;
+        issue_tile(S0());
+        // all steps but the last fetch the next tile while they compute
         int it = 0;
-        for (; it + NS <= n_hot; it += NS) {
-            step(it, std::integral_constant<int, 0>());
-            step(it + 1, std::integral_constant<int, 1>());
-            if (NS > 2) {
-                step(it + 2, std::integral_constant<int, 2 % NS>());
-                step(it + 3, std::integral_constant<int, 3 % NS>());
-            }
+        for (; it + 2 < n_hot; it += 2) {
+            step(it, S0(), std::true_type());
+            step(it + 1, S1(), std::true_type());
         }
-        if (it < n_hot) step(it, std::integral_constant<int, 0>());
-        if (NS > 2) {
-            if (it + 1 < n_hot) step(it + 1, std::integral_constant<int, 1>());
-            if (it + 2 < n_hot) step(it + 2, std::integral_constant<int, 2 % NS>());
+        if (it + 1 < n_hot) {
+            step(it, S0(), std::true_type());
+            step(it + 1, S1(), std::false_type());
+        } else {
+            step(it, S0(), std::false_type());
         }
         MCSD_WAIT_VMCNT(0);
     }
@@ -845,8 +863,8 @@ template <int D>
 hipError_t launch_bf16(const AttnParams &p, const AttnPlan &pl, hipStream_t st)
 {
     if (pl.QBP == 1) launch_sweep<D, 1, 2>(p, pl, st);
-    else if (pl.QBP == 2) { if (pl.NS == 4) launch_sweep<D, 2, 4>(p, pl, st); else launch_sweep<D, 2, 2>(p, pl, st); }
-    else { if (pl.NS == 4) launch_sweep<D, 4, 4>(p, pl, st); else launch_sweep<D, 4, 2>(p, pl, st); }
+    else if (pl.QBP == 2) launch_sweep<D, 2, 2>(p, pl, st);
+    else launch_sweep<D, 4, 2>(p, pl, st);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || pl.S == 1) return e;
     if (pl.QBP == 1) launch_merge<D, 1>(p, pl, st);
