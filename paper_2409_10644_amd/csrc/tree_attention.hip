@@ -79,7 +79,8 @@ AttnPlan make_plan(int dtype, int B, int H, int n_rows, int max_prefix)
     // Key splits: enough workgroups for two per compute unit, at least four tiles per split, at most 8 splits
     // (every split costs a partial result of n rows that is written, written back and folded by the second kernel).
     long S = (512 + bh - 1) / bh;
-    if (S > tiles_max / 4) S = tiles_max / 4;
+    const long min_tiles = dtype == MCSD_BF16 ? 4 : 1;     // the vector-ALU path is slow per tile: split it all the way
+    if (S > tiles_max / min_tiles) S = tiles_max / min_tiles;
     if (dtype == MCSD_BF16 && S > 8) S = 8;
     if (S < 1) S = 1;
     if (S > 64) S = 64;
@@ -688,10 +689,10 @@ __global__ __launch_bounds__(256) void tree_attn_f32_kernel(const AttnParams p)
     const float *vp = (const float *)p.vp + pre0;
 
     for (int idx = tid; idx < p.n * D; idx += 256) sQ[idx / D][idx % D] = q[idx];
+    if (tid < NMAX) { sM[tid] = -INFINITY; sL[tid] = 0.f; }     // running maximum / denominator of every row
     float acc[NR];
 #pragma unroll
     for (int r = 0; r < NR; ++r) acc[r] = 0.f;
-    float m_run = -INFINITY, l_run = 0.f;     // state of row `tid` (threads tid < n)
     const int oc = tid % D, oi0 = tid / D;
 
     for (int it = 0; it < n_iter; ++it) {
@@ -717,7 +718,7 @@ __global__ __launch_bounds__(256) void tree_attn_f32_kernel(const AttnParams p)
             sV[row][col] = ok ? vsrc[idx] : 0.f;
         }
         __syncthreads();
-        {   // raw scores
+        {   // scores and online soft-max: the 32 lanes of a half wavefront own one row at a time, one key each
             const int j = tid % T, i0 = tid / T;
             for (int i = p.row0 + i0; i < p.n; i += 256 / T) {
                 float dot = 0.f;
@@ -728,25 +729,25 @@ __global__ __launch_bounds__(256) void tree_attn_f32_kernel(const AttnParams p)
                     const int col = tree_col0 + j;
                     vis = vis && ((p.mask_bits[(int64_t)i * p.mask_words + (col >> 6)] >> (col & 63)) & 1ull);
                 }
-                sS[i][j] = vis ? dot : -INFINITY;
+                const float sc = vis ? dot : -INFINITY;
+                float mx = sc;
+#pragma unroll
+                for (int m = 1; m < T; m <<= 1) mx = fmaxf(mx, __shfl_xor(mx, m, 64));
+                const float m_old = sM[i];
+                const float m_new = fmaxf(m_old, mx);
+                const float mc = (m_new == -INFINITY ? 0.f : m_new) * p.c;
+                const float pv = exp2f(fmaf(sc, p.c, -mc));
+                float psum = pv;
+#pragma unroll
+                for (int m = 1; m < T; m <<= 1) psum += __shfl_xor(psum, m, 64);
+                sS[i][j] = pv;
+                if (j == 0) {
+                    const float alpha = exp2f(fmaf(m_old, p.c, -mc));
+                    sAlpha[i] = alpha;
+                    sL[i] = sL[i] * alpha + psum;
+                    sM[i] = m_new;
+                }
             }
-        }
-        __syncthreads();
-        if (tid >= p.row0 && tid < p.n) {   // online softmax of row tid
-            float mx = -INFINITY;
-            for (int j = 0; j < T; ++j) mx = fmaxf(mx, sS[tid][j]);
-            const float m_new = fmaxf(m_run, mx);
-            const float mc = (m_new == -INFINITY ? 0.f : m_new) * p.c;
-            const float alpha = exp2f(fmaf(m_run, p.c, -mc));
-            float psum = 0.f;
-            for (int j = 0; j < T; ++j) {
-                const float pv = exp2f(fmaf(sS[tid][j], p.c, -mc));
-                sS[tid][j] = pv;
-                psum += pv;
-            }
-            l_run = l_run * alpha + psum;
-            m_run = m_new;
-            sAlpha[tid] = alpha;
         }
         __syncthreads();
 #pragma unroll
@@ -760,8 +761,6 @@ __global__ __launch_bounds__(256) void tree_attn_f32_kernel(const AttnParams p)
             }
         }
     }
-    __syncthreads();
-    if (tid < p.n) { sL[tid] = l_run; sM[tid] = m_run; }
     __syncthreads();
     if (p.SP == 1) {
         float *o = (float *)p.out + bh * p.node_stride * D;
@@ -778,8 +777,8 @@ __global__ __launch_bounds__(256) void tree_attn_f32_kernel(const AttnParams p)
             if (i >= p.row0 && i < p.n) p.part_o[(prow0 + i) * D + oc] = acc[r];
         }
         if (tid >= p.row0 && tid < p.n) {
-            p.part_m[prow0 + tid] = m_run;
-            p.part_l[prow0 + tid] = l_run;
+            p.part_m[prow0 + tid] = sM[tid];
+            p.part_l[prow0 + tid] = sL[tid];
         }
     }
 }
