@@ -48,6 +48,10 @@ struct SharedT {
 constexpr int GROUP = 16;                // blocks a wavefront handles at a time
 constexpr int FAST_NB = GROUP * (VT / 64);   // up to this many blocks a context's rows stay in registers
 
+// max(d, 0) as one instruction.  d is never NaN here, and the sign of a zero result never reaches a decision
+// (zeros only enter sums, products and comparisons with 0), so this equals "d > 0 ? d : 0" for every use below.
+__device__ inline double pos_part(double d) { return __builtin_fmax(d, 0.0); }
+
 // Element t of the distribution after `rounds` rejections at a context with rows prow / qrow.
 __device__ inline double residual_at(const float *prow, const float *qrow, const double *s_hist, int rounds,
                                      int t)
@@ -57,7 +61,7 @@ __device__ inline double residual_at(const float *prow, const float *qrow, const
         const double qv = (double)qrow[t];
         for (int k = 0; k < rounds; ++k) {
             const double d = __fma_rn(-s_hist[k], qv, r);
-            r = d > 0.0 ? d : 0.0;
+            r = pos_part(d);
         }
     }
     return r;
@@ -95,6 +99,44 @@ __device__ inline double wave_tree_sum(double v)
     return v;
 }
 
+// The same reduction for N independent values at once, level by level: the N chains (each level waits for a
+// cross-lane move) overlap instead of running one after the other.
+template <int N>
+__device__ inline void wave_tree_sum_n(double (&v)[N])
+{
+    double t[N];
+#pragma unroll
+    for (int i = 0; i < N; ++i) t[i] = dpp_f64<0xB1>(v[i]);
+#pragma unroll
+    for (int i = 0; i < N; ++i) v[i] = __dadd_rn(v[i], t[i]);
+#pragma unroll
+    for (int i = 0; i < N; ++i) t[i] = dpp_f64<0x4E>(v[i]);
+#pragma unroll
+    for (int i = 0; i < N; ++i) v[i] = __dadd_rn(v[i], t[i]);
+#pragma unroll
+    for (int i = 0; i < N; ++i) t[i] = dpp_f64<0x141>(v[i]);
+#pragma unroll
+    for (int i = 0; i < N; ++i) v[i] = __dadd_rn(v[i], t[i]);
+#pragma unroll
+    for (int i = 0; i < N; ++i) t[i] = dpp_f64<0x140>(v[i]);
+#pragma unroll
+    for (int i = 0; i < N; ++i) v[i] = __dadd_rn(v[i], t[i]);
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+        const int lo = __builtin_amdgcn_ds_swizzle(__double2loint(v[i]), 0x401F);
+        const int hi = __builtin_amdgcn_ds_swizzle(__double2hiint(v[i]), 0x401F);
+        t[i] = __hiloint2double(hi, lo);
+    }
+#pragma unroll
+    for (int i = 0; i < N; ++i) v[i] = __dadd_rn(v[i], t[i]);
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+        const auto lo = __builtin_amdgcn_permlane32_swap((unsigned)__double2loint(v[i]), (unsigned)__double2loint(v[i]), false, false);
+        const auto hi = __builtin_amdgcn_permlane32_swap((unsigned)__double2hiint(v[i]), (unsigned)__double2hiint(v[i]), false, false);
+        v[i] = __dadd_rn(__hiloint2double((int)hi[0], (int)lo[0]), __hiloint2double((int)hi[1], (int)lo[1]));
+    }
+}
+
 // 4 elements of each of the wavefront's GROUP blocks (block wave + 16k): float rows -> registers; beyond V: 0.
 // The thread id is hidden from the optimiser so that offsets and bounds tests are recomputed at every use
 // instead of being kept in registers across the whole walk.
@@ -128,10 +170,9 @@ __device__ inline void store_block_sums(Shared &sh, const VerifyParams &P, const
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     double sblk[GROUP];
 #pragma unroll
-    for (int k = 0; k < GROUP; ++k) {
-        if (k % 4 == 0) __builtin_amdgcn_sched_barrier(0);      // four independent reductions in flight
-        sblk[k] = wave_tree_sum(__dadd_rn(__dadd_rn(r[k][0], r[k][1]), __dadd_rn(r[k][2], r[k][3])));
-    }
+    for (int k = 0; k < GROUP; ++k) sblk[k] = __dadd_rn(__dadd_rn(r[k][0], r[k][1]), __dadd_rn(r[k][2], r[k][3]));
+    __builtin_amdgcn_sched_barrier(0);
+    wave_tree_sum_n<GROUP>(sblk);
     __builtin_amdgcn_sched_barrier(0);
     if (lane == 0) {
 #pragma unroll
@@ -187,7 +228,7 @@ __device__ void stream_block_sums(Shared &sh, const VerifyParams &P, const float
                 const double qd = (double)qe[k][e];
                 for (int j = 0; j < rounds; ++j) {
                     const double d = __fma_rn(-sh.s_hist[j], qd, r);
-                    r = d > 0.0 ? d : 0.0;
+                    r = pos_part(d);
                 }
                 v[e] = r;
             }
@@ -374,19 +415,27 @@ __global__ __launch_bounds__(VT) void verify_walk_kernel(const VerifyParams P)
                 if (tid == 0) sh.s_hist[rounds] = S;
                 buf ^= 1;
                 if constexpr (FAST) {
-                    // four blocks at a time: the scheduler must not pull all of q into registers next to r
+                    // four blocks at a time, the next four's q read from LDS while these are updated (the scheduler
+                    // must neither pull all of q into registers next to r nor wait for each read in turn)
+                    float4 qv[2][4];
 #pragma unroll
-                    for (int k = 0; k < GROUP; ++k) {
-                        if (k % 4 == 0) __builtin_amdgcn_sched_barrier(0);
-                        const float4 qv = qlds[k * VT];
-                        const float qe[4] = {qv.x, qv.y, qv.z, qv.w};
+                    for (int k = 0; k < 4; ++k) qv[0][k] = qlds[k * VT];
 #pragma unroll
-                        for (int e = 0; e < 4; ++e) {
-                            const double d = __fma_rn(-S, (double)qe[e], r[k][e]);
-                            r[k][e] = d > 0.0 ? d : 0.0;
+                    for (int k0 = 0; k0 < GROUP; k0 += 4) {
+                        if (k0 + 4 < GROUP) {
+#pragma unroll
+                            for (int k = 0; k < 4; ++k) qv[(k0 / 4 + 1) & 1][k] = qlds[(k0 + 4 + k) * VT];
                         }
+                        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                        for (int k = 0; k < 4; ++k) {
+                            const float4 q4 = qv[(k0 / 4) & 1][k];
+                            const float qe[4] = {q4.x, q4.y, q4.z, q4.w};
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) r[k0 + k][e] = pos_part(__fma_rn(-S, (double)qe[e], r[k0 + k][e]));
+                        }
+                        __builtin_amdgcn_sched_barrier(0);
                     }
-                    __builtin_amdgcn_sched_barrier(0);
                     store_block_sums(sh, P, r, buf);
                 } else {
                     __syncthreads();          // s_hist[rounds] visible
@@ -394,7 +443,7 @@ __global__ __launch_bounds__(VT) void verify_walk_kernel(const VerifyParams P)
                 }
                 {
                     const double d = __fma_rn(-S, qc, rc);
-                    rc = d > 0.0 ? d : 0.0;
+                    rc = pos_part(d);
                 }
                 rounds += 1;
                 __syncthreads();              // block sums (and s_hist) visible
