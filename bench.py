@@ -408,6 +408,28 @@ def main():
             torch.cuda.empty_cache()
         except Exception as ex:      # an extra workload must not lose the headline line
             extra[name] = {"error": repr(ex)}
+    # yardstick: what the HBM of this machine delivers to a plain read-only streaming kernel (4 GiB buffer)
+    try:
+        buf = torch.empty(4 << 30, dtype=torch.uint8, device="cuda")
+        buf.fill_(1)
+        sink = torch.zeros(16, dtype=torch.uint8, device="cuda")
+
+        class _S:      # what time_kernel needs of a Step
+            pass
+        ss = _S()
+        ss.binding, ss.torch = binding, torch
+        per_grid = {}
+        for wgs in (256, 512, 2048, 8192):      # the rate depends on how the grid's stride falls on the memory channels
+            s_avg = time_kernel(ss, hip, binding.KERNEL_STREAM_READ, lambda i: binding.stream_read(buf, sink, wgs), 10, warm=10)[0]
+            per_grid[wgs] = round(buf.numel() / (s_avg * 1e-3) / 1e9, 1)
+        gbps = max(per_grid.values())
+        out["stream_read_probe"] = {"GB/s": gbps, "frac_of_peak": round(gbps / HBM_PEAK_GBPS, 4), "bytes": buf.numel(),
+                                    "GB/s_by_workgroups": per_grid}
+        for r in [out["roofline"]] + [v for v in extra.values() if "achieved" in v]:
+            r["frac_of_stream_read"] = round(r["achieved"] / gbps, 4)
+        del buf
+    except Exception as ex:
+        out["stream_read_probe"] = {"error": repr(ex)}
     if extra:
         out["other_workloads"] = extra
     print(json.dumps(out), flush=True)

@@ -212,8 +212,15 @@ int mcsd_commit_path(const mcsd_mask_view_t *mask, mcsd_dtype_t dtype, int32_t B
  * the device.  The arming is consumed by that launch.  Passing NULL events disarms.  Not thread-safe.
  * ------------------------------------------------------------------------------------------------- */
 typedef enum { MCSD_KERNEL_ATTN_SWEEP = 0, MCSD_KERNEL_ATTN_MERGE = 1, MCSD_KERNEL_VERIFY_WALK = 2,
-               MCSD_KERNEL_COMMIT_COPY = 3 } mcsd_kernel_t;
+               MCSD_KERNEL_COMMIT_COPY = 3, MCSD_KERNEL_STREAM_READ = 4 } mcsd_kernel_t;
 int mcsd_profile_next(mcsd_kernel_t kernel, void *start_event, void *stop_event);
+
+/* Measurement aid (not part of the method).  Reads `bytes` (>= 16, rounded down to 16) from src_dev (DEVICE,
+ * 16-byte aligned) with a plain grid-strided streaming kernel and discards them; sink_dev is 16 bytes of DEVICE
+ * memory that is written only if the data has one particular value.  Timed on a buffer much larger than the caches
+ * it gives the read bandwidth this machine's HBM delivers to the simplest reader.  workgroups: grid size in
+ * workgroups of 256 lanes, 0 for the default of 1024. */
+int mcsd_stream_read(const void *src_dev, size_t bytes, void *sink_dev, int32_t workgroups, void *hip_stream);
 
 #ifdef __cplusplus
 }

@@ -17,7 +17,7 @@ MCSD_DRAFT_INIT, MCSD_TARGET_INIT = 0, 1
 EXPORTS = ["mcsd_strerror", "mcsd_build_mask", "mcsd_slice_mask", "mcsd_free_mask",
            "mcsd_tree_attention_workspace", "mcsd_tree_attention",
            "mcsd_tree_attention_rows_workspace", "mcsd_tree_attention_rows",
-           "mcsd_verify_tree_workspace", "mcsd_verify_tree", "mcsd_commit_path", "mcsd_profile_next"]
+           "mcsd_verify_tree_workspace", "mcsd_verify_tree", "mcsd_commit_path", "mcsd_profile_next", "mcsd_stream_read"]
 
 
 class MaskView(C.Structure):
@@ -76,12 +76,14 @@ def _load() -> C.CDLL:
                                      i64, C.POINTER(vp), C.POINTER(vp), vp, i64, i32, i32, vp, vp, vp, vp, i32, i32,
                                      vp, vp, vp, vp]
     lib.mcsd_profile_next.argtypes = [C.c_int, vp, vp]
+    lib.mcsd_stream_read.restype = C.c_int
+    lib.mcsd_stream_read.argtypes = [vp, C.c_size_t, vp, i32, vp]
     return lib
 
 
 lib = _load()
 
-KERNEL_ATTN_SWEEP, KERNEL_ATTN_MERGE, KERNEL_VERIFY_WALK, KERNEL_COMMIT_COPY = 0, 1, 2, 3
+KERNEL_ATTN_SWEEP, KERNEL_ATTN_MERGE, KERNEL_VERIFY_WALK, KERNEL_COMMIT_COPY, KERNEL_STREAM_READ = 0, 1, 2, 3, 4
 
 
 def strerror(status: int) -> str:
@@ -208,6 +210,11 @@ def commit_path(view: MaskView, dtype: int, B: int, H: int, d: int, k_tree: Sequ
                               max_prefix, capacity, _ptr(out_path), _ptr(accept_len), _ptr(tokens), _ptr(new_tokens),
                               n_new, n_append, _ptr(prefix_lens_dev), _ptr(out_ids), _ptr(out_n_ids), _stream(stream))
     _check(st, "mcsd_commit_path")
+
+
+def stream_read(src: torch.Tensor, sink: torch.Tensor, workgroups: int = 0, stream=None) -> None:
+    _check(lib.mcsd_stream_read(_ptr(src), src.numel() * src.element_size(), _ptr(sink), workgroups, _stream(stream)),
+           "mcsd_stream_read")
 
 
 def mask_bits_host(view: MaskView):
