@@ -40,6 +40,7 @@ struct AttnParams {
     const uint64_t *mask_bits;
     int32_t mask_words;
     int32_t B, H, n;
+    int32_t pair_cus; // > 0: compute units, and the grid is one workgroup per (b,h), two per compute unit (see the kernel)
     int32_t row0;     // first query row: rows row0 .. n-1 are computed (keys are always all n tree nodes)
     int32_t max_prefix;
     int64_t node_stride, head_stride;
@@ -324,10 +325,30 @@ void tree_attn_bf16_kernel(const AttnParams p)
     int wg = blockIdx.x;
     if (p.G > 1 && (total & 7) == 0) wg = (wg & 7) * (total >> 3) + (wg >> 3);
     const int s = wg % p.G;
-    const int bhi = wg / p.G;
+    int bhi = wg / p.G;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    if (p.pair_cus > 0) {
+        // One workgroup per (sequence, head), exactly two per compute unit.  On this machine workgroups i and
+        // i + #CUs of such a grid land on the same compute unit (measured; nothing but speed depends on it): give
+        // that pair the heads of a long and of a short sequence, so that every compute unit has about the same
+        // number of keys to stream however ragged the batch is.  Sequences are ranked by length here (B <= 64).
+        __shared__ int32_t s_len[64], s_seq_at[64];
+        if (tid < p.B) {
+            const int Lt = p.lens[tid];
+            s_len[tid] = Lt < 0 ? 0 : (Lt > p.max_prefix ? p.max_prefix : Lt);
+        }
+        __syncthreads();
+        if (tid < p.B) {
+            int rank = 0;
+            for (int o = 0; o < p.B; ++o) rank += (s_len[o] > s_len[tid]) || (s_len[o] == s_len[tid] && o < tid);
+            s_seq_at[rank] = tid;
+        }
+        __syncthreads();
+        const int r = wg < p.pair_cus ? wg : total + p.pair_cus - 1 - wg;      // rank i with rank total-1-i
+        bhi = s_seq_at[r / p.H] * p.H + r % p.H;
+    }
     const int h = bhi % p.H, b = bhi / p.H;
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int g = lane >> 5, ln = lane & 31;
     const int qb = wave % QBP, kg = wave / QBP;
 
@@ -951,6 +972,19 @@ extern "C" int mcsd_tree_attention_rows(const mcsd_mask_view_t *mask, mcsd_dtype
     p.node_stride = node_stride; p.head_stride = head_stride;
     p.c = softmax_scale * 1.4426950408889634f;
     p.S = pl.S; p.G = pl.G; p.SP = pl.G;
+    p.pair_cus = 0;
+    if (dtype == MCSD_BF16 && pl.G == 1 && B <= 64) {
+        static int n_cus = 0;                                  // compute units of the current device, asked once
+        if (n_cus == 0) {
+            int dev = 0, v = 0;
+            if (hipGetDevice(&dev) == hipSuccess && hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess)
+                n_cus = v > 0 ? v : -1;
+        }
+        if (n_cus > 0 && (long)B * H == 2L * n_cus) p.pair_cus = n_cus;
+        if (const char *ov = getenv("MCSD_ATTN_PAIRING")) {  // tuning override: 0 keeps the natural order
+            if (atol(ov) == 0) p.pair_cus = 0;
+        }
+    }
     p.tps = (int32_t)((((int64_t)max_prefix + pl.T - 1) / pl.T + pl.S - 1) / pl.S);
     if (p.tps < 1) p.tps = 1;
     char *w = (char *)workspace;
