@@ -119,11 +119,20 @@ __device__ inline s16x4_t lds_read_tr16(const unsigned char *p)
     return __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4_t __attribute__((address_space(3))) *)(p));
 }
 
-// 16 bytes per lane from global memory straight into LDS: lane l lands at lds_base + 16*l (lds_base uniform).
-__device__ inline void load_to_lds16(const void *gsrc, void *lds_base)
+// 16 bytes per lane from global memory straight into LDS: lane l reads gbase + voff and lands at lds_base + 16*l
+// (gbase and lds_base uniform).  Written as assembly on purpose: the compiler knows nothing about where such a
+// load writes in LDS unless alias information happens to survive inlining, and otherwise makes the next LDS
+// read wait for it (vmcnt(0)), which serialises the stream with the compute.  Here it is just an opaque
+// instruction; the kernel waits for it itself (MCSD_WAIT_VMCNT + barrier) before anyone reads the stage.
+// An untracked load can only make compiler-placed vmcnt waits longer, never shorter (loads retire in order).
+// M0 carries the LDS address; nothing else in these kernels uses M0 (the toolchain rejects it as a clobber).
+__device__ inline void load_to_lds16(const void *gbase, uint32_t voff, void *lds_base)
 {
-    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)gsrc,
-                                     (__attribute__((address_space(3))) void *)lds_base, 16, 0, 0);
+    const uint32_t lds_addr = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void *)lds_base;
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :
+                 : "s"(lds_addr), "v"(voff), "s"(gbase)
+                 : "memory");
 }
 
 // s_waitcnt vmcnt(N) only (expcnt / lgkmcnt left at their maxima)
@@ -326,7 +335,8 @@ void tree_attn_bf16_kernel(const AttnParams p)
     if (p.G > 1 && (total & 7) == 0) wg = (wg & 7) * (total >> 3) + (wg >> 3);
     const int s = wg % p.G;
     int bhi = wg / p.G;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // the same in all lanes: keep it in a scalar register
     if (p.pair_cus > 0) {
         // One workgroup per (sequence, head), exactly two per compute unit.  On this machine workgroups i and
         // i + #CUs of such a grid land on the same compute unit (measured; nothing but speed depends on it): give
@@ -434,7 +444,7 @@ void tree_attn_bf16_kernel(const AttnParams p)
         auto issue_load = [&](int i, auto stage) {
             unsigned char *dst = ring + decltype(stage)::value * C::TILE + wave * 1024;
             static_assert(decltype(stage)::value < NS, "stage out of range");
-            load_to_lds16(((i & 1) ? vbase : kbase) + goff[i >> 1], dst + (i & 1) * C::TILE_K + (i >> 1) * C::WAVES * 1024);
+            load_to_lds16((i & 1) ? vbase : kbase, goff[i >> 1], dst + (i & 1) * C::TILE_K + (i >> 1) * C::WAVES * 1024);
         };
         auto advance = [&]() {
             nxt = nxt + 1 == n_hot ? 0 : nxt + 1;
