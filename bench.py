@@ -255,6 +255,8 @@ def main():
     ap.add_argument("--kernel-reps", type=int, default=64)
     ap.add_argument("--extra-reps", type=int, default=200,
                     help="timed launches (after as many untimed ones) of each extra workload's attention")
+    ap.add_argument("--verify-batch", type=int, default=128,
+                    help="sequences of the batched verification section (0 skips it)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--eager", action="store_true", help="launch the step's kernels one by one instead of replaying a HIP graph")
     ap.add_argument("--traffic-calibration", action="store_true",
@@ -408,6 +410,45 @@ def main():
             torch.cuda.empty_cache()
         except Exception as ex:      # an extra workload must not lose the headline line
             extra[name] = {"error": repr(ex)}
+    # the vocabulary pass at a batch that fills half the chip's compute units (one workgroup per sequence)
+    if args.verify_batch > 0:
+        try:
+            from workloads import scaled, verify_inputs
+            import oracle
+            sys.path.insert(0, os.path.join(ROOT, "tests"))
+            import gpu_helpers as H
+            wb = scaled(WORKLOADS[w_name], B=args.verify_batch)
+            vi = verify_inputs(wb, seed=1, mode=0)
+            vv = binding.slice_mask(binding.build_mask(wb.branching), wb.gamma_max)
+            got = H.run_verify(binding, vv, 0, vi)
+            want = oracle.verify_tree(0, wb.branching, vi["tokens"], vi["p_target"], vi["q_draft"], vi["u_accept"], vi["u_sample"])
+            assert all((a == b).all() for a, b in zip(got, want)), "batched verification differs from the oracle"
+            dp, dq = H.dev(vi["p_target"]), H.dev(vi["q_draft"])
+            dt_, dua, dus = H.dev(vi["tokens"]), H.dev(vi["u_accept"]), H.dev(vi["u_sample"])
+            o_path = torch.zeros((wb.B, vv.gamma), dtype=torch.int32, device="cuda")
+            o_len = torch.zeros((wb.B,), dtype=torch.int32, device="cuda")
+            o_new = torch.zeros((wb.B, 1), dtype=torch.int32, device="cuda")
+
+            class _V:
+                pass
+            vs = _V()
+            vs.binding, vs.torch = binding, torch
+            vs.mode, vs.w, vs.gamma, vs.n_new, vs.path, vs.alen = 0, wb, vv.gamma, 1, o_path, o_len
+
+            def vcall(i):
+                binding.verify_tree(vv, 0, wb.B, wb.V, dt_, dp, dq, vi["p_target"].shape[1] * wb.V, vi["q_draft"].shape[1] * wb.V,
+                                    dua, dus, 1, o_path, o_len, o_new, None)
+            vb_avg = time_kernel(vs, hip, binding.KERNEL_VERIFY_WALK, vcall, 30, warm=10)[0]
+            vbytes = verify_algorithmic_bytes(vs)
+            extra["verify_batch%d" % wb.B] = {
+                "bound": "hbm", "kernel": "verify_walk_kernel", "achieved": round(vbytes / (vb_avg * 1e-3) / 1e9, 1),
+                "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(vbytes / (vb_avg * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+                "algorithmic_bytes_per_launch": int(vbytes), "avg_launch_us": round(vb_avg * 1e3, 2),
+                "sequences_per_s": round(wb.B / (vb_avg * 1e-3), 1), "mean_accept_len": round(float(got[1].mean()), 3),
+                "verified_vs_oracle": True, "workload": f"{w_name} verification, B={wb.B}, V={wb.V}"}
+            del dp, dq
+        except Exception as ex:
+            extra["verify_batch"] = {"error": repr(ex)}
     # yardstick: what the HBM of this machine delivers to a plain read-only streaming kernel (4 GiB buffer)
     try:
         buf = torch.empty(4 << 30, dtype=torch.uint8, device="cuda")
