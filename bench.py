@@ -255,6 +255,8 @@ def main():
     ap.add_argument("--kernel-reps", type=int, default=64)
     ap.add_argument("--extra-reps", type=int, default=200,
                     help="timed launches (after as many untimed ones) of each extra workload's attention")
+    ap.add_argument("--gqa-kv-heads", type=int, default=8,
+                    help="key/value heads of the grouped-query variant of cfg4 (0 skips that section)")
     ap.add_argument("--verify-batch", type=int, default=128,
                     help="sequences of the batched verification section (0 skips it)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -410,6 +412,61 @@ def main():
             torch.cuda.empty_cache()
         except Exception as ex:      # an extra workload must not lose the headline line
             extra[name] = {"error": repr(ex)}
+    # grouped-query variant of the ragged batch (beyond the paper's multi-head shape): 32 query heads on 8 kv heads
+    if args.gqa_kv_heads > 0 and "cfg4" in args.extra:
+        try:
+            from workloads import scaled, attention_inputs, prefix_lens
+            sys.path.insert(0, os.path.join(ROOT, "tests"))
+            import gpu_helpers as H
+            import oracle
+            import numpy as np
+            wq = WORKLOADS["cfg4"]
+            Hkv = args.gqa_kv_heads
+            wk = scaled(wq, H=Hkv, cfg_id=wq.cfg_id + 100)
+            lens = prefix_lens(wq, 0)
+            qi = attention_inputs(wq, seed=0, lens=lens, kv_capacity=int(wq.prefix_max))
+            ki = attention_inputs(wk, seed=0, lens=lens, kv_capacity=int(wq.prefix_max))
+            aq, ak = H.AttnDevice(qi), H.AttnDevice(ki)
+            vg = binding.slice_mask(binding.build_mask(wq.branching), wq.gamma_max)
+            n = vg.n_nodes
+            wsb = binding.tree_attention_gqa_workspace(wq.B, wq.H, Hkv, wq.d, n, 0, int(wq.prefix_max))
+            wsg = torch.empty(max(wsb, 256), dtype=torch.uint8, device="cuda")
+
+            def gcall(i):
+                binding.tree_attention_gqa(vg, 1, wq.B, wq.H, Hkv, wq.d, 0, aq.q, ak.kt, ak.vt, ak.node_stride, ak.kp, ak.vp,
+                                           ak.base, ak.lens, ak.head_stride, int(wq.prefix_max), aq.scale, aq.out, wsg)
+            gcall(0)
+            torch.cuda.synchronize()
+            G = wq.H // Hkv
+            cap = ki["k_prefix"].shape[2]
+            rep_ = dict(qi, k_tree=np.repeat(ki["k_tree"], G, axis=1), v_tree=np.repeat(ki["v_tree"], G, axis=1),
+                        k_prefix=np.repeat(ki["k_prefix"], G, axis=1), v_prefix=np.repeat(ki["v_prefix"], G, axis=1),
+                        head_stride=cap * wq.d, seq_base=(np.arange(wq.B, dtype=np.int64) * (wq.H * cap * wq.d)))
+            got = aq.out[:, :, :n].float().cpu().numpy().astype(np.float64)
+            M = oracle.build_mask(wq.branching)
+            rng = np.random.default_rng(2)
+            for _ in range(8):
+                b_, h_, i_ = int(rng.integers(wq.B)), int(rng.integers(wq.H)), int(rng.integers(n))
+                H.assert_close(got[b_, h_, i_], oracle.tree_attention_row(rep_, M, n, b_, h_, i_), "bf16", "bench gqa")
+
+            class _G:
+                pass
+            gs = _G()
+            gs.binding, gs.torch = binding, torch
+            g_avg, g_med, g_p10, g_p90 = time_kernel(gs, hip, binding.KERNEL_ATTN_SWEEP, gcall, args.extra_reps, warm=args.extra_reps)
+            gbytes = sum(2 * wq.d * (Hkv * (2 * int(L) + 2 * n) + wq.H * 2 * n) for L in lens)
+            gflops = sum(wq.H * 4 * n * (int(L) + n) * wq.d for L in lens)
+            extra["cfg4_gqa"] = {"bound": "mfma", "kernel": "tree_attn_bf16_kernel", "achieved": round(gflops / (g_avg * 1e-3) / 1e12, 1),
+                                 "peak": 2500.0, "unit": "TFLOP/s", "frac": round(gflops / (g_avg * 1e-3) / 1e12 / 2500.0, 4),
+                                 "traffic": None, "flops_per_launch": int(gflops), "algorithmic_bytes_per_launch": int(gbytes),
+                                 "hbm_GBps": round(gbytes / (g_avg * 1e-3) / 1e9, 1), "avg_launch_us": round(g_avg * 1e3, 2),
+                                 "p10_us": round(g_p10 * 1e3, 2), "p90_us": round(g_p90 * 1e3, 2), "launches_timed": args.extra_reps,
+                                 "verified_vs_oracle": True,
+                                 "workload": f"cfg4 with {wq.H} query heads on {Hkv} key/value heads (B{wq.B} N={n})"}
+            del aq, ak
+            torch.cuda.empty_cache()
+        except Exception as ex:
+            extra["cfg4_gqa"] = {"error": repr(ex)}
     # the vocabulary pass at a batch that fills half the chip's compute units (one workgroup per sequence)
     if args.verify_batch > 0:
         try:
@@ -466,7 +523,7 @@ def main():
         gbps = max(per_grid.values())
         out["stream_read_probe"] = {"GB/s": gbps, "frac_of_peak": round(gbps / HBM_PEAK_GBPS, 4), "bytes": buf.numel(),
                                     "GB/s_by_workgroups": per_grid}
-        for r in [out["roofline"]] + [v for v in extra.values() if "achieved" in v]:
+        for r in [out["roofline"]] + [v for v in extra.values() if v.get("bound") == "hbm"]:
             r["frac_of_stream_read"] = round(r["achieved"] / gbps, 4)
         del buf
     except Exception as ex:

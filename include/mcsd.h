@@ -135,6 +135,24 @@ int mcsd_tree_attention_rows(const mcsd_mask_view_t *mask, mcsd_dtype_t dtype, i
                              int32_t max_prefix, float softmax_scale, void *out, void *workspace,
                              size_t workspace_bytes, void *hip_stream);
 
+/* Grouped-query attention (beyond the paper's Llama-2-7B multi-head shape): H_q query heads share H_kv key/value
+ * heads, H_q a multiple of H_kv; query head h uses key/value head h / (H_q / H_kv).
+ * q, out         : DEVICE [B][H_q][node_stride][d]
+ * k_tree, v_tree : DEVICE [B][H_kv][node_stride][d]
+ * k_prefix, v_prefix : element (b,kvh,j,c) at seq_base[b] + kvh*head_stride + j*d + c
+ * Everything else as mcsd_tree_attention_rows (which is the H_q == H_kv case).  On the bf16 path up to four query
+ * blocks of one key/value head (4, 2 or 1 query heads, depending on the number of rows) are served by one
+ * workgroup, so that head's K/V bytes leave HBM once for all of them. */
+size_t mcsd_tree_attention_gqa_workspace(int32_t B, int32_t H_q, int32_t H_kv, int32_t d, int32_t n_nodes,
+                                         int32_t row_begin, int32_t max_prefix);
+
+int mcsd_tree_attention_gqa(const mcsd_mask_view_t *mask, mcsd_dtype_t dtype, int32_t B, int32_t H_q, int32_t H_kv,
+                            int32_t d, int32_t row_begin, const void *q, const void *k_tree, const void *v_tree,
+                            int64_t node_stride, const void *k_prefix, const void *v_prefix,
+                            const int64_t *seq_base_dev, const int32_t *prefix_lens_dev, int64_t head_stride,
+                            int32_t max_prefix, float softmax_scale, void *out, void *workspace,
+                            size_t workspace_bytes, void *hip_stream);
+
 /* ---------------------------------------------------------------------------------------------------
  * Verification (Sec. 2.1; Sec. 3.1; Fig. 1 steps 4-6)
  *

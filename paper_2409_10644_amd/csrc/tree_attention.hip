@@ -39,7 +39,12 @@ struct AttnParams {
     const int32_t *lens;
     const uint64_t *mask_bits;
     int32_t mask_words;
-    int32_t B, H, n;
+    int32_t B, H, n;  // H: workgroup units per sequence (bf16 sweep: kv heads x chunks of query heads; fp32: query heads)
+    int32_t Hq, Hkv;  // query heads, key/value heads (Hq = grp * Hkv)
+    int32_t grp;      // query heads that share one key/value head
+    int32_t hpw;      // query heads one workgroup of the bf16 sweep serves (they share its K/V stream)
+    int32_t bph;      // 32-row query blocks per query head in a workgroup (1, 2 or 4); QBP = bph * hpw
+    int32_t chunks;   // grp / hpw: workgroup units per key/value head
     int32_t pair_cus; // > 0: compute units, and the grid is one workgroup per (b,h), two per compute unit (see the kernel)
     int32_t row0;     // first query row: rows row0 .. n-1 are computed (keys are always all n tree nodes)
     int32_t max_prefix;
@@ -55,6 +60,8 @@ struct AttnParams {
 };
 
 struct AttnPlan {
+    int bph, hpw, chunks;  // bf16: query blocks per head, heads per workgroup, units per kv head (see AttnParams)
+    int units;             // workgroup units per sequence: kv heads x chunks (bf16), query heads (fp32)
     int QBP;   // query blocks of 32 rows, rounded up to 1, 2 or 4 (bf16 path)
     int T;     // keys per tile
     int S;     // key splits of the prefix
@@ -64,18 +71,30 @@ struct AttnPlan {
 
 __host__ __device__ inline int tile_keys_bf16(int QBP) { return QBP == 1 ? 128 : 64; }   // == SweepCfg::T
 
-AttnPlan make_plan(int dtype, int B, int H, int n_rows, int max_prefix)
+AttnPlan make_plan(int dtype, int B, int Hq, int Hkv, int n_rows, int max_prefix)
 {
     AttnPlan pl;
+    const int grp = Hq / Hkv;
     if (dtype == MCSD_BF16) {
         const int qb = (n_rows + 31) / 32;
-        pl.QBP = qb <= 1 ? 1 : (qb == 2 ? 2 : 4);
+        pl.bph = qb <= 1 ? 1 : (qb == 2 ? 2 : 4);
+        // grouped-query attention: as many query heads of one kv head as fit the workgroup's four query blocks
+        // share its K/V stream (so those bytes leave HBM once for all of them)
+        pl.hpw = 1;
+        for (int c = 4 / pl.bph; c > 1; c >>= 1)
+            if (grp % c == 0) { pl.hpw = c; break; }
+        pl.QBP = pl.bph * pl.hpw;
+        pl.chunks = grp / pl.hpw;
+        pl.units = Hkv * pl.chunks;
         pl.T = tile_keys_bf16(pl.QBP);
     } else {
+        pl.bph = pl.hpw = 1;
+        pl.chunks = grp;
+        pl.units = Hq;
         pl.QBP = 1;
         pl.T = 32;
     }
-    const long bh = (long)B * H;
+    const long bh = (long)B * pl.units;
     const long tiles_max = (max_prefix + pl.T - 1) / pl.T;
     // Key splits: enough workgroups for two per compute unit, at least four tiles per split, at most 8 splits
     // (every split costs a partial result of n rows that is written, written back and folded by the second kernel).
@@ -378,17 +397,20 @@ void tree_attn_bf16_kernel(const AttnParams p)
     // leading tiles of this split that are full (only the sequence's last tile can be ragged)
     const int n_hot = (n_pre > 0 && t1 * C::T > L) ? n_pre - 1 : n_pre;
 
-    const int64_t bh = (int64_t)b * p.H + h;
-    const __bf16 *q = (const __bf16 *)p.q + bh * p.node_stride * D;
-    const __bf16 *kt = (const __bf16 *)p.kt + bh * p.node_stride * D;
-    const __bf16 *vt = (const __bf16 *)p.vt + bh * p.node_stride * D;
-    const int64_t pre0 = p.seq_base[b] + (int64_t)h * p.head_stride;
+    const int64_t bh = (int64_t)b * p.H + h;                 // workgroup unit: indexes the partial results
+    const int kvh = h / p.chunks;                              // key/value head of this unit
+    const int hq = kvh * p.grp + (h % p.chunks) * p.hpw + qb / p.bph;   // query head of this wavefront's block
+    const int64_t bh_kv = (int64_t)b * p.Hkv + kvh, bh_q = (int64_t)b * p.Hq + hq;
+    const __bf16 *q = (const __bf16 *)p.q + bh_q * p.node_stride * D;
+    const __bf16 *kt = (const __bf16 *)p.kt + bh_kv * p.node_stride * D;
+    const __bf16 *vt = (const __bf16 *)p.vt + bh_kv * p.node_stride * D;
+    const int64_t pre0 = p.seq_base[b] + (int64_t)kvh * p.head_stride;
     const unsigned char *kp = (const unsigned char *)((const __bf16 *)p.kp + pre0);
     const unsigned char *vp = (const unsigned char *)((const __bf16 *)p.vp + pre0);
 
     // query block of this wavefront; mask row of this lane's query (zero for padded rows)
     QBlock<D> qs;
-    const int qrow = p.row0 + qb * 32 + ln;
+    const int qrow = p.row0 + (qb % p.bph) * 32 + ln;
 #pragma unroll
     for (int ks = 0; ks < C::KS; ++ks) {
         uint4 v = make_uint4(0, 0, 0, 0);
@@ -582,7 +604,7 @@ void tree_attn_bf16_kernel(const AttnParams p)
     auto store_out = [&]() {
         if (qrow >= p.n) return;
         const float inv = 1.f / l_tot;
-        __bf16 *o = (__bf16 *)p.out + (bh * p.node_stride + qrow) * D;
+        __bf16 *o = (__bf16 *)p.out + (bh_q * p.node_stride + qrow) * D;
 #pragma unroll
         for (int cb = 0; cb < C::CB; ++cb)
 #pragma unroll
@@ -632,8 +654,10 @@ __global__ __launch_bounds__(256) void tree_attn_merge_bf16_kernel(const AttnPar
     if (bh >= (int64_t)p.B * p.H) return;
     const int ln = pos & 31, g = (pos >> 5) & 1, f = pos >> 6;
     const int lrow = qb * 32 + ln;                            // row of the partial results
-    const int row = p.row0 + lrow;                            // tree node
+    const int row = p.row0 + (qb % p.bph) * 32 + ln;          // tree node
     if (row >= p.n) return;
+    const int unit = (int)(bh % p.H);
+    const int64_t bh_q = (bh / p.H) * p.Hq + (unit / p.chunks) * p.grp + (unit % p.chunks) * p.hpw + qb / p.bph;
     int L = p.lens[bh / p.H];
     L = L < 0 ? 0 : (L > p.max_prefix ? p.max_prefix : L);
     const int tiles_b = (L + T - 1) / T;
@@ -678,7 +702,7 @@ __global__ __launch_bounds__(256) void tree_attn_merge_bf16_kernel(const AttnPar
 #pragma unroll
     for (int e = 0; e < 4; ++e) v[e] = (__bf16)r[e];
     const int c = (f / 4) * 32 + 8 * (f % 4) + 4 * g;
-    *(bf16x4_t *)((__bf16 *)p.out + (bh * p.node_stride + row) * D + c) = v;
+    *(bf16x4_t *)((__bf16 *)p.out + (bh_q * p.node_stride + row) * D + c) = v;
 }
 
 // ---------------------------------------------------------------------------------------------------
@@ -711,11 +735,13 @@ __global__ __launch_bounds__(256) void tree_attn_f32_kernel(const AttnParams p)
     const int n_iter = n_pre + n_tree_tiles;
     if (n_iter == 0) return;
 
-    const int64_t bh = (int64_t)b * p.H + h;
+    const int64_t bh = (int64_t)b * p.H + h;                 // query head
+    const int kvh = h / p.grp;
+    const int64_t bh_kv = (int64_t)b * p.Hkv + kvh;
     const float *q = (const float *)p.q + bh * p.node_stride * D;
-    const float *kt = (const float *)p.kt + bh * p.node_stride * D;
-    const float *vt = (const float *)p.vt + bh * p.node_stride * D;
-    const int64_t pre0 = p.seq_base[b] + (int64_t)h * p.head_stride;
+    const float *kt = (const float *)p.kt + bh_kv * p.node_stride * D;
+    const float *vt = (const float *)p.vt + bh_kv * p.node_stride * D;
+    const int64_t pre0 = p.seq_base[b] + (int64_t)kvh * p.head_stride;
     const float *kp = (const float *)p.kp + pre0;
     const float *vp = (const float *)p.vp + pre0;
 
@@ -862,16 +888,16 @@ __global__ __launch_bounds__(256) void tree_attn_merge_kernel(const AttnParams p
 size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 // workspace: [part_m] [part_l] [part_o]; nothing when the keys are not split
-size_t partial_rows(const AttnPlan &pl, int dtype, int B, int H, int n)
+size_t partial_rows(const AttnPlan &pl, int dtype, int B, int n)
 {
-    // bf16 path: whole 32-row query blocks in register-fragment order; fp32 path: n rows
-    return (size_t)B * H * pl.G * (dtype == MCSD_BF16 ? (size_t)pl.QBP * 32 : (size_t)n);
+    // per workgroup unit and split; bf16 path: whole 32-row query blocks in register-fragment order; fp32 path: n rows
+    return (size_t)B * pl.units * pl.G * (dtype == MCSD_BF16 ? (size_t)pl.QBP * 32 : (size_t)n);
 }
 
-size_t workspace_bytes_for(const AttnPlan &pl, int dtype, int B, int H, int d, int n)
+size_t workspace_bytes_for(const AttnPlan &pl, int dtype, int B, int d, int n)
 {
     if (pl.S == 1) return 0;
-    const size_t rows = partial_rows(pl, dtype, B, H, n);
+    const size_t rows = partial_rows(pl, dtype, B, n);
     return 2 * align256(rows * sizeof(float)) + align256(rows * d * sizeof(float));
 }
 
@@ -916,22 +942,28 @@ hipError_t launch_f32(const AttnParams &p, const AttnPlan &pl, hipStream_t st)
 
 }  // namespace
 
+extern "C" size_t mcsd_tree_attention_gqa_workspace(int32_t B, int32_t H_q, int32_t H_kv, int32_t d, int32_t n_nodes,
+                                                    int32_t row_begin, int32_t max_prefix)
+{
+    if (B < 1 || H_q < 1 || H_kv < 1 || H_q % H_kv != 0 || (d != 64 && d != 128) || n_nodes < 1 ||
+        n_nodes > MCSD_ATTN_MAX_NODES || max_prefix < 0 || row_begin < 0 || row_begin >= n_nodes)
+        return 0;
+    // the larger of the two dtypes' needs, so one buffer serves both
+    const AttnPlan a = make_plan(MCSD_BF16, B, H_q, H_kv, n_nodes - row_begin, max_prefix);
+    const AttnPlan f = make_plan(MCSD_F32, B, H_q, H_kv, n_nodes - row_begin, max_prefix);
+    const size_t wa = workspace_bytes_for(a, MCSD_BF16, B, d, n_nodes), wf = workspace_bytes_for(f, MCSD_F32, B, d, n_nodes);
+    return wa > wf ? wa : wf;
+}
+
 extern "C" size_t mcsd_tree_attention_rows_workspace(int32_t B, int32_t H, int32_t d, int32_t n_nodes,
                                                      int32_t row_begin, int32_t max_prefix)
 {
-    if (B < 1 || H < 1 || (d != 64 && d != 128) || n_nodes < 1 || n_nodes > MCSD_ATTN_MAX_NODES || max_prefix < 0 ||
-        row_begin < 0 || row_begin >= n_nodes)
-        return 0;
-    // the larger of the two dtypes' needs, so one buffer serves both
-    const AttnPlan a = make_plan(MCSD_BF16, B, H, n_nodes - row_begin, max_prefix);
-    const AttnPlan f = make_plan(MCSD_F32, B, H, n_nodes - row_begin, max_prefix);
-    const size_t wa = workspace_bytes_for(a, MCSD_BF16, B, H, d, n_nodes), wf = workspace_bytes_for(f, MCSD_F32, B, H, d, n_nodes);
-    return wa > wf ? wa : wf;
+    return mcsd_tree_attention_gqa_workspace(B, H, H, d, n_nodes, row_begin, max_prefix);
 }
 
 extern "C" size_t mcsd_tree_attention_workspace(int32_t B, int32_t H, int32_t d, int32_t n_nodes, int32_t max_prefix)
 {
-    return mcsd_tree_attention_rows_workspace(B, H, d, n_nodes, 0, max_prefix);
+    return mcsd_tree_attention_gqa_workspace(B, H, H, d, n_nodes, 0, max_prefix);
 }
 
 extern "C" int mcsd_tree_attention(const mcsd_mask_view_t *mask, mcsd_dtype_t dtype, int32_t B, int32_t H, int32_t d,
@@ -954,6 +986,21 @@ extern "C" int mcsd_tree_attention_rows(const mcsd_mask_view_t *mask, mcsd_dtype
                                         float softmax_scale, void *out, void *workspace, size_t workspace_bytes,
                                         void *hip_stream)
 {
+    return mcsd_tree_attention_gqa(mask, dtype, B, H, H, d, row_begin, q, k_tree, v_tree, node_stride, k_prefix,
+                                   v_prefix, seq_base_dev, prefix_lens_dev, head_stride, max_prefix, softmax_scale, out,
+                                   workspace, workspace_bytes, hip_stream);
+}
+
+extern "C" int mcsd_tree_attention_gqa(const mcsd_mask_view_t *mask, mcsd_dtype_t dtype, int32_t B, int32_t H_q,
+                                       int32_t H_kv, int32_t d, int32_t row_begin, const void *q, const void *k_tree,
+                                       const void *v_tree, int64_t node_stride, const void *k_prefix,
+                                       const void *v_prefix, const int64_t *seq_base_dev,
+                                       const int32_t *prefix_lens_dev, int64_t head_stride, int32_t max_prefix,
+                                       float softmax_scale, void *out, void *workspace, size_t workspace_bytes,
+                                       void *hip_stream)
+{
+    const int32_t H = H_q;
+    if (H_kv < 1 || H_q < 1 || H_q % H_kv != 0) return MCSD_EINVAL;
     if (!mask || !mask->bits_dev || !q || !k_tree || !v_tree || !out || !seq_base_dev || !prefix_lens_dev)
         return MCSD_EINVAL;
     if (dtype != MCSD_F32 && dtype != MCSD_BF16) return MCSD_EINVAL;
@@ -970,15 +1017,16 @@ extern "C" int mcsd_tree_attention_rows(const mcsd_mask_view_t *mask, mcsd_dtype
     if (align & 15) return MCSD_EINVAL;
     if (((node_stride * d) & 7) || (head_stride & 7)) return MCSD_EINVAL;
 
-    const AttnPlan pl = make_plan(dtype, B, H, n - row_begin, max_prefix);
-    const size_t need = workspace_bytes_for(pl, dtype, B, H, d, n);
+    const AttnPlan pl = make_plan(dtype, B, H_q, H_kv, n - row_begin, max_prefix);
+    const size_t need = workspace_bytes_for(pl, dtype, B, d, n);
     if (need > 0 && (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 255))) return MCSD_EWORKSPACE;
 
     AttnParams p;
     p.q = q; p.kt = k_tree; p.vt = v_tree; p.kp = k_prefix; p.vp = v_prefix; p.out = out;
     p.seq_base = seq_base_dev; p.lens = prefix_lens_dev;
     p.mask_bits = mask->bits_dev; p.mask_words = mask->words_per_row;
-    p.B = B; p.H = H; p.n = n; p.row0 = row_begin; p.max_prefix = max_prefix;
+    p.B = B; p.H = pl.units; p.n = n; p.row0 = row_begin; p.max_prefix = max_prefix;
+    p.Hq = H_q; p.Hkv = H_kv; p.grp = H_q / H_kv; p.hpw = pl.hpw; p.bph = pl.bph; p.chunks = pl.chunks;
     p.node_stride = node_stride; p.head_stride = head_stride;
     p.c = softmax_scale * 1.4426950408889634f;
     p.S = pl.S; p.G = pl.G; p.SP = pl.G;
@@ -990,7 +1038,7 @@ extern "C" int mcsd_tree_attention_rows(const mcsd_mask_view_t *mask, mcsd_dtype
             if (hipGetDevice(&dev) == hipSuccess && hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess)
                 n_cus = v > 0 ? v : -1;
         }
-        if (n_cus > 0 && (long)B * H == 2L * n_cus) p.pair_cus = n_cus;
+        if (n_cus > 0 && (long)B * pl.units == 2L * n_cus) p.pair_cus = n_cus;
         if (const char *ov = getenv("MCSD_ATTN_PAIRING")) {  // tuning override: 0 keeps the natural order
             if (atol(ov) == 0) p.pair_cus = 0;
         }
@@ -1000,7 +1048,7 @@ extern "C" int mcsd_tree_attention_rows(const mcsd_mask_view_t *mask, mcsd_dtype
     char *w = (char *)workspace;
     p.part_o = p.part_m = p.part_l = nullptr;
     if (pl.S > 1) {
-        const size_t rows = partial_rows(pl, dtype, B, H, n);
+        const size_t rows = partial_rows(pl, dtype, B, n);
         p.part_m = (float *)w;
         w += align256(rows * sizeof(float));
         p.part_l = (float *)w;

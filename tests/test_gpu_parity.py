@@ -629,3 +629,78 @@ def test_attention_rows_any_first_row(binding, oracle, H, row_begin):
     with pytest.raises(binding.McsdError):
         binding.tree_attention_rows(v, ad.code, 1, 8, ad.d, v.n_nodes, ad.q, ad.kt, ad.vt, ad.node_stride, ad.kp, ad.vp,
                                     ad.base, ad.lens, ad.head_stride, 1500, ad.scale, ad.out, None)
+
+
+# ------------------------------------------------------------------------------------------------
+# grouped-query attention: several query heads share the K/V of one head
+# ------------------------------------------------------------------------------------------------
+def _gqa_case(binding, oracle, H, br, B, Hq, Hkv, d, dtype, lens, max_prefix=None, row_begin=0, seed=0):
+    wq = scaled(WORKLOADS["cfg2"], B=B, H=Hq, d=d, dtype=dtype, branching=tuple(br), cfg_id=90)
+    wk = scaled(wq, H=Hkv, cfg_id=91)
+    qi = attention_inputs(wq, seed=seed, lens=lens)               # q of all query heads
+    ki = attention_inputs(wk, seed=seed, lens=lens)               # K/V of the shared heads
+    G = Hq // Hkv
+    cap = ki["k_prefix"].shape[2]
+    # what the oracle sees: plain multi-head attention with every K/V head repeated for its G query heads
+    rep = dict(qi, k_tree=np.repeat(ki["k_tree"], G, axis=1), v_tree=np.repeat(ki["v_tree"], G, axis=1),
+               k_prefix=np.repeat(ki["k_prefix"], G, axis=1), v_prefix=np.repeat(ki["v_prefix"], G, axis=1),
+               head_stride=cap * d, seq_base=(np.arange(B, dtype=np.int64) * (Hq * cap * d)))
+    aq, ak = H.AttnDevice(qi), H.AttnDevice(ki)
+    m = binding.build_mask(br)
+    v = binding.slice_mask(m, len(br))
+    mp = ak.max_prefix if max_prefix is None else max_prefix
+    ws_bytes = binding.tree_attention_gqa_workspace(B, Hq, Hkv, d, v.n_nodes, row_begin, mp)
+    ws = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device="cuda")
+    aq.out.fill_(31.0)
+    binding.tree_attention_gqa(v, aq.code, B, Hq, Hkv, d, row_begin, aq.q, ak.kt, ak.vt, ak.node_stride, ak.kp, ak.vp,
+                               ak.base, ak.lens, ak.head_stride, mp, aq.scale, aq.out, ws)
+    torch.cuda.synchronize()
+    got = aq.out.float().cpu().numpy().astype(np.float64)
+    want = oracle.tree_attention(rep, oracle.build_mask(br), v.n_nodes)
+    H.assert_close(got[:, :, row_begin:v.n_nodes], want[:, :, row_begin:], dtype, f"gqa {Hq}/{Hkv} tree {br}")
+    assert np.all(got[:, :, :row_begin] == 31.0) and np.all(got[:, :, v.n_nodes:] == 31.0)
+
+
+@pytest.mark.parametrize("Hq,Hkv", [(8, 8), (8, 4), (8, 2), (8, 1), (12, 4), (6, 2)])
+@pytest.mark.parametrize("br,dtype,d", [((4, 2, 2, 1), "bf16", 128), ((3, 2), "bf16", 128), ((8, 2, 2, 1, 1), "bf16", 128),
+                                        ((3, 2, 2, 1, 1, 1, 1, 1), "bf16", 64), ((4, 2, 2, 2), "bf16", 64),
+                                        ((2, 2, 2), "f32", 64)])
+def test_grouped_query_attention(binding, oracle, H, br, dtype, d, Hq, Hkv):
+    _gqa_case(binding, oracle, H, br, 2, Hq, Hkv, d, dtype, lens=(150, 37))
+
+
+def test_grouped_query_attention_split_keys_and_levels(binding, oracle, H):
+    # long prefix with few heads: the keys are split over workgroups and folded; then the newest level only
+    _gqa_case(binding, oracle, H, (4, 2, 2, 1), 1, 8, 2, 128, "bf16", lens=(2000,))
+    _gqa_case(binding, oracle, H, (4, 2, 2, 1), 1, 8, 2, 128, "bf16", lens=(2000,), row_begin=28)
+    _gqa_case(binding, oracle, H, (8, 2, 2, 1, 1), 2, 16, 4, 128, "bf16", lens=(900, 1300), row_begin=88)
+    _gqa_case(binding, oracle, H, (2, 2, 2), 1, 4, 2, 64, "f32", lens=(300,), row_begin=6)
+
+
+def test_grouped_query_attention_llama3_like_batch(binding, oracle, H):
+    """32 query heads on 8 key/value heads, 16 ragged sequences (the pairing mode's grid: 16 x 8 x 4 = 512 units)."""
+    br = (4, 2, 2, 2)
+    B, Hq, Hkv, d = 16, 32, 8, 128
+    rng = np.random.default_rng(3)
+    lens = tuple(int(x) for x in rng.integers(40, 700, size=B))
+    wq = scaled(WORKLOADS["cfg4"], B=B, H=Hq, cfg_id=92)
+    wk = scaled(wq, H=Hkv, cfg_id=93)
+    qi, ki = attention_inputs(wq, seed=1, lens=lens), attention_inputs(wk, seed=1, lens=lens)
+    G, cap = Hq // Hkv, ki["k_prefix"].shape[2]
+    rep = dict(qi, k_tree=np.repeat(ki["k_tree"], G, axis=1), v_tree=np.repeat(ki["v_tree"], G, axis=1),
+               k_prefix=np.repeat(ki["k_prefix"], G, axis=1), v_prefix=np.repeat(ki["v_prefix"], G, axis=1),
+               head_stride=cap * d, seq_base=(np.arange(B, dtype=np.int64) * (Hq * cap * d)))
+    aq, ak = H.AttnDevice(qi), H.AttnDevice(ki)
+    v = binding.slice_mask(binding.build_mask(br), 4)
+    ws = torch.empty(max(binding.tree_attention_gqa_workspace(B, Hq, Hkv, d, v.n_nodes, 0, 700), 256), dtype=torch.uint8,
+                     device="cuda")
+    binding.tree_attention_gqa(v, aq.code, B, Hq, Hkv, d, 0, aq.q, ak.kt, ak.vt, ak.node_stride, ak.kp, ak.vp, ak.base,
+                               ak.lens, ak.head_stride, 700, aq.scale, aq.out, ws)
+    torch.cuda.synchronize()
+    got = aq.out[:, :, :v.n_nodes].float().cpu().numpy().astype(np.float64)
+    M = oracle.build_mask(br)
+    for (b, h, i) in _sample_rows(np.random.default_rng(5), B, Hq, v.n_nodes, 128):
+        H.assert_close(got[b, h, i], oracle.tree_attention_row(rep, M, v.n_nodes, b, h, i), "bf16", f"gqa row {(b, h, i)}")
+    with pytest.raises(binding.McsdError):
+        binding.tree_attention_gqa(v, aq.code, B, Hq, 5, d, 0, aq.q, ak.kt, ak.vt, ak.node_stride, ak.kp, ak.vp, ak.base,
+                                   ak.lens, ak.head_stride, 700, aq.scale, aq.out, ws)
