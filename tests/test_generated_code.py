@@ -1,0 +1,72 @@
+"""Checks on the machine code hipcc generates for the tree-attention sweep (no GPU needed: the kernels are only
+compiled).  Two properties that correctness or speed depend on and that a compiler update could silently break:
+  - the LDS address register M0 is written by the kernel's own assembly (direct-to-LDS loads) and the compiler was
+    not told; so no compiler-generated instruction may use M0;
+  - in the steady-state loop of every sweep instantiation the only waits on the vector-memory counter are the
+    kernel's own, one per tile, next to its barrier: an additional compiler-placed wait would make the LDS reads of
+    the tile being computed wait for the loads of the next tile."""
+import os
+import re
+import shutil
+import subprocess
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+
+
+@pytest.fixture(scope="module")
+def sweep_asm(tmp_path_factory):
+    if not (os.path.exists(HIPCC) or shutil.which(HIPCC)):
+        pytest.skip("hipcc not available")
+    out = tmp_path_factory.mktemp("asm") / "tree_attention.s"
+    csrc = os.path.join(ROOT, "paper_2409_10644_amd", "csrc")
+    cmd = [HIPCC, "--offload-arch=gfx950", "-O3", "-std=c++17", "-I", os.path.join(ROOT, "include"), "-I", csrc,
+           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-S", "--cuda-device-only", "-o", str(out),
+           os.path.join(csrc, "tree_attention.hip")]
+    subprocess.run(cmd, check=True, capture_output=True)
+    return out.read_text().split("\n")
+
+
+def _functions(lines):
+    starts = [(i, l.split(":")[0]) for i, l in enumerate(lines) if re.match(r"^_Z\w+:", l)]
+    for (i0, name), (i1, _) in zip(starts, starts[1:] + [(len(lines), "")]):
+        yield name, lines[i0:i1]
+
+
+def test_m0_is_only_touched_by_the_kernels_own_assembly(sweep_asm):
+    inside, seen = False, 0
+    for l in sweep_asm:
+        if "#ASMSTART" in l:
+            inside = True
+        elif "#ASMEND" in l:
+            inside = False
+        elif re.search(r"\bm0\b", l.split(";")[0]):
+            assert inside, f"compiler-generated use of M0: {l.strip()}"
+            seen += 1
+    assert seen > 0
+
+
+def test_steady_state_loops_wait_for_memory_once_per_tile(sweep_asm):
+    checked = 0
+    for name, body in _functions(sweep_asm):
+        if "tree_attn_bf16_kernel" not in name:
+            continue
+        labels = {m.group(1): i for i, l in enumerate(body) if (m := re.match(r"^(\.LBB\d+_\d+):", l))}
+        loops = []
+        for i, l in enumerate(body):
+            m = re.search(r"s_c?branch\w*\s+(\.LBB\d+_\d+)", l)
+            if m and m.group(1) in labels and labels[m.group(1)] < i:
+                loop = body[labels[m.group(1)]:i + 1]
+                if any("global_load_lds" in x for x in loop) and any("v_mfma" in x for x in loop):
+                    loops.append(loop)
+        assert loops, f"no streaming loop found in {name}"
+        loop = min(loops, key=len)                                   # the innermost one
+        code = [x.split(";")[0] for x in loop]
+        waits = sum("vmcnt" in x for x in code)
+        barriers = sum("s_barrier" in x for x in code)
+        assert barriers == 2 and waits == 2, f"{name}: {waits} vmcnt waits, {barriers} barriers in the two-tile loop"
+        assert not any("scratch_" in x for x in code), f"{name}: register spills inside the streaming loop"
+        checked += 1
+    assert checked == 6          # head_dim 64 / 128 x 1, 2, 4 query blocks
