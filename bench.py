@@ -29,7 +29,7 @@ N_LAYERS = 32                   # Llama-2-7B
 # HBM traffic per launch of the sweep kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (bytes, already
 # scaled by the copy-kernel calibration); filled from the summaries under profiles/.  None = not measured.
 MEASURED_TRAFFIC = {   # profiles/tree_attn_hbm_traffic_pmc.md (sweep kernel: HBM read + written)
-    "cfg2": 21_730_000, "cfg4": 664_630_000, "cfg5": 2_204_310_000,
+    "cfg2": 21_790_000, "cfg4": 664_670_000, "cfg5": 2_205_450_000,
 }
 
 
