@@ -399,12 +399,13 @@ __global__ __launch_bounds__(VT) void verify_walk_kernel(const VerifyParams P)
             double r[GROUP][4];
             float4 *qlds = (float4 *)sh.qrow + tid;
             if constexpr (FAST) {
-                float pe[GROUP][4];
-                load_rows(P, qrow, pe);
-#pragma unroll
-                for (int k = 0; k < GROUP; ++k) qlds[k * VT] = make_float4(pe[k][0], pe[k][1], pe[k][2], pe[k][3]);
-                __builtin_amdgcn_sched_barrier(0);
+                float pe[GROUP][4], qe[GROUP][4];             // both rows in flight at once: one memory latency
+                load_rows(P, qrow, qe);
                 load_rows(P, prow, pe);
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int k = 0; k < GROUP; ++k) qlds[k * VT] = make_float4(qe[k][0], qe[k][1], qe[k][2], qe[k][3]);
+                __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                 for (int k = 0; k < GROUP; ++k)
 #pragma unroll
