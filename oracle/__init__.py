@@ -60,6 +60,12 @@ def _load():
         L.mcsd_oracle_commit_path.argtypes = [i32, i32, i32, i32, i32, i32, i64, vp, vp, vp, vp, vp, i64, vp, vp, vp, vp]
         L.mcsd_oracle_commit_ids.restype = C.c_int
         L.mcsd_oracle_commit_ids.argtypes = [i32, i32, i32, vp, vp, vp, vp, i32, i32, vp, vp]
+        L.mcsd_oracle_decision_features.restype = C.c_int
+        L.mcsd_oracle_decision_features.argtypes = [i64, i32, vp, vp]
+        L.mcsd_oracle_mlp.restype = f64
+        L.mcsd_oracle_mlp.argtypes = [i32, vp, vp, vp, vp]
+        L.mcsd_oracle_early_stop.restype = i32
+        L.mcsd_oracle_early_stop.argtypes = [vp, i32, f64]
         L.mcsd_oracle_threads.restype = i32
         L.mcsd_oracle_threads.argtypes = []
         _lib = L
@@ -229,6 +235,43 @@ def commit_ids(gamma: int, tokens: np.ndarray, path: np.ndarray, accept_len: np.
     if rc != 0:
         raise ValueError("oracle commit_ids: bad argument")
     return ids, n_ids
+
+
+def decision_features(rows: np.ndarray, k: int) -> np.ndarray:
+    """Concat(Topk(y), Ent(y)) of every distribution: rows fp32 [M][V] -> binary64 [M][k+1]."""
+    rows = np.ascontiguousarray(rows, dtype=np.float32)
+    M, V = rows.shape
+    out = np.zeros((M, k + 1), dtype=np.float64)
+    for m in range(M):
+        if _load().mcsd_oracle_decision_features(V, int(k), _ptr(rows[m]), _ptr(out[m])) != 0:
+            raise ValueError("oracle decision_features: bad argument")
+    return out
+
+
+def mlp(weights: Sequence[np.ndarray], biases: Sequence[np.ndarray], X: np.ndarray) -> np.ndarray:
+    """Decision-model output for every row of X (binary64 [M][width0]); weights[l] fp32 [out_l][in_l]."""
+    n = len(weights)
+    assert len(biases) == n and n >= 1
+    ws = [np.ascontiguousarray(w, dtype=np.float32) for w in weights]
+    bs = [np.ascontiguousarray(b, dtype=np.float32) for b in biases]
+    width = [ws[0].shape[1]] + [w.shape[0] for w in ws]
+    for l in range(n):
+        assert ws[l].shape == (width[l + 1], width[l]) and bs[l].shape == (width[l + 1],), (l, ws[l].shape)
+    assert width[-1] == 1
+    X = np.ascontiguousarray(X, dtype=np.float64)
+    assert X.ndim == 2 and X.shape[1] == width[0]
+    warr = np.asarray(width, dtype=np.int32)
+    wp = (C.c_void_p * n)(*[_ptr(w) for w in ws])
+    bp = (C.c_void_p * n)(*[_ptr(b) for b in bs])
+    return np.array([_load().mcsd_oracle_mlp(n, _ptr(warr), wp, bp, _ptr(X[m])) for m in range(X.shape[0])],
+                    dtype=np.float64)
+
+
+def early_stop(P: np.ndarray, beta: float) -> np.ndarray:
+    """P binary64 [B][W] -> int32 [B]: 1 where every candidate sequence is predicted below beta."""
+    P = np.ascontiguousarray(P, dtype=np.float64)
+    B, W = P.shape
+    return np.array([_load().mcsd_oracle_early_stop(_ptr(P[b]), W, float(beta)) for b in range(B)], dtype=np.int32)
 
 
 def tree_sum(a: np.ndarray) -> float:

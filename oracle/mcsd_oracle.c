@@ -11,6 +11,7 @@
  *   O2  tree attention: every tree node attends to the whole prefix and to its own ancestors (Sec. 2.2)
  *   O3  multi-candidate verification: recursive rejection sampling over the tree, longest-path
  *       selection for target-initialised trees, sampling of the new token(s)    (Sec. 2.1, Sec. 3.1, Fig. 1 steps 4-6)
+ *   O4  early-stop decision models: Topk/entropy features, the two MLPs, the stop rule   (Sec. 3.3)
  *
  * Arithmetic is IEEE-754 binary64 throughout (compile with -ffp-contract=off, never -ffast-math).
  * Where the paper is silent the reading is stated next to the code.
@@ -433,6 +434,76 @@ int mcsd_oracle_commit_ids(int32_t B, int32_t gamma, int32_t n_nodes, const int3
         for (; k < W; ++k) ids[(int64_t)b * W + k] = -1;
     }
     return 0;
+}
+
+/* ------------------------------------------------------------------------------------------------
+ * O4  Early-stop decision models (Sec. 3.3; threshold beta = 0.4 in the caption of Fig. 2).
+ *
+ * After every draft-generation turn a small MLP predicts, for each candidate sequence, the probability
+ * that the target model will accept it; draft generation stops early iff every sequence of the tree is
+ * predicted below beta.  Two models: type 1 is a three-layer MLP on the draft model's hidden state of the
+ * newest token; type 2 is a two-layer MLP on Concat(Topk(y), Ent(y)) of the draft model's output
+ * distribution y for that token.
+ *
+ * Readings where Sec. 3.3 is silent: an "n-layer MLP" is n affine maps with ReLU between them and a
+ * logistic sigmoid after the last, so the output is a probability that can be compared with beta;
+ * Topk(y) is the k largest probabilities in descending order (values, duplicates kept; zeros when the
+ * row has fewer than k entries); Ent(y) is the Shannon entropy in nats with 0 ln 0 = 0; "lower than
+ * the threshold" is strict.  Weights are inputs (the trained ones are not published).
+ * ---------------------------------------------------------------------------------------------- */
+static int cmp_float_desc(const void *a, const void *b)
+{
+    const float x = *(const float *)a, y = *(const float *)b;
+    return (x < y) - (x > y);
+}
+
+/* x[0..k-1] = Topk(y), x[k] = Ent(y) for one distribution y[0..V-1]. */
+int mcsd_oracle_decision_features(int64_t V, int32_t k, const float *y, double *x)
+{
+    if (V < 1 || k < 0) return -1;
+    float *sorted = (float *)malloc(sizeof(float) * (size_t)V);
+    memcpy(sorted, y, sizeof(float) * (size_t)V);
+    qsort(sorted, (size_t)V, sizeof(float), cmp_float_desc);
+    for (int32_t i = 0; i < k; ++i) x[i] = i < V ? (double)sorted[i] : 0.0;
+    free(sorted);
+    double h = 0.0;
+    for (int64_t v = 0; v < V; ++v)
+        if (y[v] > 0.0f) h -= (double)y[v] * log((double)y[v]);
+    x[k] = h;
+    return 0;
+}
+
+/* P = sigmoid(A_n(relu(... relu(A_1 x)))) with A_l z = weight[l] z + bias[l]; weight[l] is row-major
+ * [width[l+1]][width[l]], width[0] inputs, width[n_layers] = 1. */
+double mcsd_oracle_mlp(int32_t n_layers, const int32_t *width, const float *const *weight, const float *const *bias,
+                       const double *x)
+{
+    int32_t wmax = 1;
+    for (int32_t l = 0; l <= n_layers; ++l) if (width[l] > wmax) wmax = width[l];
+    double *cur = (double *)malloc(sizeof(double) * (size_t)wmax);
+    double *nxt = (double *)malloc(sizeof(double) * (size_t)wmax);
+    memcpy(cur, x, sizeof(double) * (size_t)width[0]);
+    for (int32_t l = 0; l < n_layers; ++l) {
+        const int32_t n_in = width[l], n_out = width[l + 1];
+        for (int32_t j = 0; j < n_out; ++j) {
+            double s = (double)bias[l][j];
+            for (int32_t i = 0; i < n_in; ++i) s += (double)weight[l][(int64_t)j * n_in + i] * cur[i];
+            nxt[j] = (l + 1 < n_layers && s < 0.0) ? 0.0 : s;
+        }
+        double *t = cur; cur = nxt; nxt = t;
+    }
+    const double z = cur[0];
+    free(cur);
+    free(nxt);
+    return 1.0 / (1.0 + exp(-z));
+}
+
+/* 1 iff all W candidate sequences of a tree are predicted below beta (then draft generation stops). */
+int32_t mcsd_oracle_early_stop(const double *P, int32_t W, double beta)
+{
+    for (int32_t w = 0; w < W; ++w)
+        if (!(P[w] < beta)) return 0;
+    return 1;
 }
 
 /* Exposed for the tests that pin the summation order and the sampler on their own. */

@@ -24,7 +24,7 @@ DRAFT_INIT = 0
 TARGET_INIT = 1
 
 # tensor ids for the random streams
-_T_LENS, _T_Q, _T_KT, _T_VT, _T_KP, _T_VP, _T_PL, _T_QL, _T_TOK, _T_UA, _T_US = range(11)
+_T_LENS, _T_Q, _T_KT, _T_VT, _T_KP, _T_VP, _T_PL, _T_QL, _T_TOK, _T_UA, _T_US, _T_MLP, _T_HID = range(13)
 
 
 @dataclass(frozen=True)
@@ -219,3 +219,26 @@ def verify_inputs(w: Workload, seed: int = 0, gamma: Optional[int] = None, mode:
     us = _rng(seed, w.cfg_id, _T_US, g).random((w.B, n_new), dtype=np.float32)
     return dict(p_target=p, q_draft=q, tokens=tokens, u_accept=ua, u_sample=us, gamma=g, mode=md,
                 n_new=int(n_new), N=N, Nin=Nin)
+
+
+def mlp_weights(widths: Sequence[int], seed: int = 0, stream: int = 0, gain: float = 2.0,
+                out_bias: float = 0.0) -> Tuple[list, list]:
+    """Random stand-ins for the trained weights of an early-stop decision model (Sec. 3.3; the trained ones are
+    not published).  widths = (inputs, hidden..., 1); layer l gets weight fp32 [widths[l+1]][widths[l]] ~
+    N(0, gain / fan_in) and bias ~ N(0, 0.1^2); `out_bias` is added to the last bias (it moves the outputs
+    relative to the threshold)."""
+    assert len(widths) >= 2 and widths[-1] == 1
+    rng = _rng(seed, 100, _T_MLP, stream)
+    ws, bs = [], []
+    for l in range(len(widths) - 1):
+        fan_in, fan_out = int(widths[l]), int(widths[l + 1])
+        ws.append(rng.standard_normal((fan_out, fan_in), dtype=np.float32) * np.float32(np.sqrt(gain / fan_in)))
+        bs.append(rng.standard_normal(fan_out, dtype=np.float32) * np.float32(0.1))
+    bs[-1] = bs[-1] + np.float32(out_bias)
+    return ws, bs
+
+
+def hidden_states(B: int, W: int, width: int, seed: int = 0, stream: int = 0) -> np.ndarray:
+    """Stand-in for the draft model's last hidden state of the newest token of each of the W candidate
+    sequences of B trees: fp32 [B][W][width] ~ N(0, 1)."""
+    return _rng(seed, 100, _T_HID, stream).standard_normal((B, W, width), dtype=np.float32)
