@@ -259,6 +259,8 @@ def main():
                     help="key/value heads of the grouped-query variant of cfg4 (0 skips that section)")
     ap.add_argument("--verify-batch", type=int, default=128,
                     help="sequences of the batched verification section (0 skips it)")
+    ap.add_argument("--decision-batch", type=int, default=64,
+                    help="trees per call in the early-stop decision-model section (0 = skip)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--eager", action="store_true", help="launch the step's kernels one by one instead of replaying a HIP graph")
     ap.add_argument("--traffic-calibration", action="store_true",
@@ -506,6 +508,74 @@ def main():
             del dp, dq
         except Exception as ex:
             extra["verify_batch"] = {"error": repr(ex)}
+    # early-stop decision models (Sec. 3.3) on the newest contexts of fork-shaped trees of width 16: one tree, and a
+    # batch whose rows (4 distinct copies, > 512 MB) cannot stay in the last-level cache between launches
+    if args.decision_batch > 0:
+        try:
+            import numpy as np
+            from workloads import hidden_states, mlp_weights, scaled, verify_inputs
+            import oracle
+            k, Wd, beta = 10, 16, 0.4
+            Bd = args.decision_batch
+            wd = scaled(WORKLOADS["fork"], B=Bd, branching=(Wd, 1))
+            q = verify_inputs(wd, seed=1, mode=0)["q_draft"]                  # [Bd][1 + 16][V]; rows 1.. are the new contexts
+            V = wd.V
+            ws, bs = mlp_weights((k + 1, 64, 1), seed=0, out_bias=-0.3)
+            mlp2 = binding.make_mlp([torch.from_numpy(a).cuda() for a in ws], [torch.from_numpy(a).cuda() for a in bs])
+            wbytes = sum(a.nbytes for a in ws + bs)
+            copies = 4
+            rows = torch.from_numpy(np.ascontiguousarray(q[:, 1:])).cuda().repeat(copies, 1, 1)   # [copies*Bd][16][V]
+            prob = torch.zeros((copies * Bd, Wd), dtype=torch.float32, device="cuda")
+            stop = torch.zeros((copies * Bd,), dtype=torch.int32, device="cuda")
+
+            class _D:
+                pass
+            ds = _D()
+            ds.binding, ds.torch = binding, torch
+            nb = min(Bd, 4)
+            want = oracle.mlp(ws, bs, oracle.decision_features(q[:nb, 1:].reshape(nb * Wd, V), k)).reshape(nb, Wd)
+            for trees, tag in ((1, "1"), (copies * Bd, str(copies * Bd))):
+                def dcall(i, trees=trees):
+                    binding.early_stop_distribution(mlp2, trees, Wd, V, k, rows, Wd * V, V, beta, None, prob, stop)
+                dcall(0)
+                torch.cuda.synchronize()
+                nchk = min(nb, trees)
+                gotp = prob[:nchk].cpu().numpy()
+                assert np.abs(gotp - want[:nchk]).max() <= 1e-5, "decision model differs from the oracle"
+                assert stop[:nchk].cpu().tolist() == [int((gotp[b] < np.float32(beta)).all()) for b in range(nchk)]
+                d_avg = time_kernel(ds, hip, binding.KERNEL_DECISION, dcall, 30, warm=10)[0]
+                t0 = time.perf_counter()
+                for i in range(50):
+                    dcall(i)
+                torch.cuda.synchronize()
+                call_us = (time.perf_counter() - t0) / 50 * 1e6
+                dbytes = trees * Wd * V * 4 + wbytes
+                extra["early_stop_distribution_trees" + tag] = {
+                    "bound": "hbm", "kernel": "decision_distribution_kernel", "achieved": round(dbytes / (d_avg * 1e-3) / 1e9, 1),
+                    "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(dbytes / (d_avg * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+                    "algorithmic_bytes_per_launch": int(dbytes), "avg_launch_us": round(d_avg * 1e3, 2),
+                    "call_us": round(call_us, 1), "verified_vs_oracle": True,
+                    "workload": f"{trees} fork tree(s) of width {Wd}, V={V}, top-{k} + entropy, MLP {k + 1}-64-1, beta {beta}"}
+            del rows
+            hw = (768, 256, 64, 1)                                          # hidden width of the 68M draft model
+            ws1, bs1 = mlp_weights(hw, seed=1, out_bias=-0.4)
+            mlp1 = binding.make_mlp([torch.from_numpy(a).cuda() for a in ws1], [torch.from_numpy(a).cuda() for a in bs1])
+            hx = hidden_states(Bd, Wd, hw[0], seed=1)
+            hxd = torch.from_numpy(hx).cuda()
+
+            def hcall(i):
+                binding.early_stop_hidden(mlp1, Bd, Wd, hxd, Wd * hw[0], hw[0], beta, prob, stop)
+            hcall(0)
+            torch.cuda.synchronize()
+            want1 = oracle.mlp(ws1, bs1, hx[:nb].reshape(nb * Wd, hw[0]).astype(np.float64)).reshape(nb, Wd)
+            assert np.abs(prob[:nb].cpu().numpy() - want1).max() <= 1e-6, "hidden-state decision model differs from the oracle"
+            h_avg = time_kernel(ds, hip, binding.KERNEL_DECISION, hcall, 30, warm=10)[0]
+            extra["early_stop_hidden_trees%d" % Bd] = {
+                "kernel": "decision_hidden_kernel", "avg_launch_us": round(h_avg * 1e3, 2), "verified_vs_oracle": True,
+                "bytes_per_launch": int(hx.nbytes + sum(a.nbytes for a in ws1 + bs1)),
+                "workload": f"{Bd} trees of width {Wd}, hidden width {hw[0]}, MLP {'-'.join(map(str, hw))} (latency-bound)"}
+        except Exception as ex:
+            extra["early_stop"] = {"error": repr(ex)}
     # yardstick: what the HBM of this machine delivers to a plain read-only streaming kernel (4 GiB buffer)
     try:
         buf = torch.empty(4 << 30, dtype=torch.uint8, device="cuda")

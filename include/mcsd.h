@@ -224,13 +224,57 @@ int mcsd_commit_path(const mcsd_mask_view_t *mask, mcsd_dtype_t dtype, int32_t B
                      int32_t *out_n_ids_dev, void *hip_stream);
 
 /* ---------------------------------------------------------------------------------------------------
+ * Early-stop decision models (Sec. 3.3; threshold beta = 0.4 in the caption of Fig. 2)
+ *
+ * After a draft-generation turn a small MLP predicts, for each of the W candidate sequences of each of B trees,
+ * the probability that the target model accepts it; stop[b] = 1 iff every sequence of tree b is predicted below
+ * beta (strictly), which ends draft generation for that tree before the maximum depth.
+ *   mcsd_early_stop_distribution : type 2, input Concat(Topk(y), Ent(y)) of the draft model's output distribution
+ *                                  y for the newest token: the k largest probabilities, largest first (values,
+ *                                  duplicates kept, zeros when V < k), then the Shannon entropy in nats
+ *                                  (0 ln 0 = 0); k + 1 inputs
+ *   mcsd_early_stop_hidden       : type 1, input the draft model's hidden state of the newest token
+ * An n-layer MLP is n affine maps with ReLU between them and a logistic sigmoid after the last (Sec. 3.3 gives the
+ * layer counts, two for type 2 and three for type 1, and nothing else; weights are the caller's).  Dot products
+ * are accumulated in binary64; the entropy uses an fp32 logarithm per entry and a binary64 sum.
+ *
+ * mlp             : HOST struct; weight[l] / bias[l] are DEVICE fp32 arrays, weight[l] row-major
+ *                   [width[l+1]][width[l]] (one row per output unit), width[0] = inputs, width[n_layers] = 1
+ * draft_rows_dev  : DEVICE fp32; the distribution of sequence w of tree b starts at b*batch_stride + w*row_stride
+ *                   (elements), V entries >= 0 (NaNs are ignored by Topk)
+ * hidden_dev      : DEVICE fp32; same addressing, width[0] entries per row
+ * features_dev    : DEVICE fp32 [B][W][k+1], the MLP's inputs rounded to fp32, or NULL
+ * prob_dev        : DEVICE fp32 [B][W];   stop_dev : DEVICE int32 [B], decided from the fp32 values in prob_dev
+ *                   (a NaN probability counts as not below beta)
+ * Limits: 1 <= k <= MCSD_DECISION_MAX_K, 1 <= V <= MCSD_MAX_VOCAB, 1 <= n_layers <= MCSD_MLP_MAX_LAYERS, widths
+ * after the first <= MCSD_MLP_MAX_WIDTH, hidden-state width <= MCSD_MLP_MAX_INPUTS.  B = 0 is a no-op.
+ * Two launches on the stream (probabilities, then the stop flags); no workspace.
+ * ------------------------------------------------------------------------------------------------- */
+enum { MCSD_DECISION_MAX_K = 16, MCSD_MLP_MAX_LAYERS = 3, MCSD_MLP_MAX_WIDTH = 512, MCSD_MLP_MAX_INPUTS = 8192 };
+
+typedef struct mcsd_mlp {
+    int32_t n_layers;
+    int32_t width[MCSD_MLP_MAX_LAYERS + 1];
+    const float *weight[MCSD_MLP_MAX_LAYERS];
+    const float *bias[MCSD_MLP_MAX_LAYERS];
+} mcsd_mlp_t;
+
+int mcsd_early_stop_distribution(const mcsd_mlp_t *mlp, int32_t B, int32_t W, int32_t V, int32_t k,
+                                 const float *draft_rows_dev, int64_t batch_stride, int64_t row_stride, float beta,
+                                 float *features_dev, float *prob_dev, int32_t *stop_dev, void *hip_stream);
+
+int mcsd_early_stop_hidden(const mcsd_mlp_t *mlp, int32_t B, int32_t W, const float *hidden_dev,
+                           int64_t batch_stride, int64_t row_stride, float beta, float *prob_dev, int32_t *stop_dev,
+                           void *hip_stream);
+
+/* ---------------------------------------------------------------------------------------------------
  * Measurement aid (not part of the method).  Arms a one-shot pair of HIP events (hipEvent_t, created by the
  * caller with timing enabled) for one of the library's kernels: the next launch of that kernel by the calling
  * process is bracketed by them, so hipEventElapsedTime(start, stop) is that kernel's own execution time on
  * the device.  The arming is consumed by that launch.  Passing NULL events disarms.  Not thread-safe.
  * ------------------------------------------------------------------------------------------------- */
 typedef enum { MCSD_KERNEL_ATTN_SWEEP = 0, MCSD_KERNEL_ATTN_MERGE = 1, MCSD_KERNEL_VERIFY_WALK = 2,
-               MCSD_KERNEL_COMMIT_COPY = 3, MCSD_KERNEL_STREAM_READ = 4 } mcsd_kernel_t;
+               MCSD_KERNEL_COMMIT_COPY = 3, MCSD_KERNEL_STREAM_READ = 4, MCSD_KERNEL_DECISION = 5 } mcsd_kernel_t;
 int mcsd_profile_next(mcsd_kernel_t kernel, void *start_event, void *stop_event);
 
 /* Measurement aid (not part of the method).  Reads `bytes` (>= 16, rounded down to 16) from src_dev (DEVICE,

@@ -18,7 +18,9 @@ EXPORTS = ["mcsd_strerror", "mcsd_build_mask", "mcsd_slice_mask", "mcsd_free_mas
            "mcsd_tree_attention_workspace", "mcsd_tree_attention",
            "mcsd_tree_attention_rows_workspace", "mcsd_tree_attention_rows",
            "mcsd_tree_attention_gqa_workspace", "mcsd_tree_attention_gqa",
-           "mcsd_verify_tree_workspace", "mcsd_verify_tree", "mcsd_commit_path", "mcsd_profile_next", "mcsd_stream_read"]
+           "mcsd_verify_tree_workspace", "mcsd_verify_tree", "mcsd_commit_path", "mcsd_early_stop_distribution",
+           "mcsd_early_stop_hidden", "mcsd_profile_next", "mcsd_stream_read"]
+DECISION_MAX_K, MLP_MAX_LAYERS, MLP_MAX_WIDTH, MLP_MAX_INPUTS = 16, 3, 512, 8192
 
 
 class MaskView(C.Structure):
@@ -29,6 +31,12 @@ class MaskView(C.Structure):
                 ("parent_host", C.POINTER(C.c_int32)), ("parent_dev", C.c_void_p),
                 ("level_host", C.POINTER(C.c_int32)), ("level_off_host", C.POINTER(C.c_int32)),
                 ("branching_host", C.POINTER(C.c_int32))]
+
+
+class Mlp(C.Structure):
+    """mcsd_mlp_t"""
+    _fields_ = [("n_layers", C.c_int32), ("width", C.c_int32 * (MLP_MAX_LAYERS + 1)),
+                ("weight", C.c_void_p * MLP_MAX_LAYERS), ("bias", C.c_void_p * MLP_MAX_LAYERS)]
 
 
 class McsdError(RuntimeError):
@@ -82,6 +90,11 @@ def _load() -> C.CDLL:
                                      i64, C.POINTER(vp), C.POINTER(vp), vp, i64, i32, i32, vp, vp, vp, vp, i32, i32,
                                      vp, vp, vp, vp]
     lib.mcsd_profile_next.argtypes = [C.c_int, vp, vp]
+    lib.mcsd_early_stop_distribution.restype = C.c_int
+    lib.mcsd_early_stop_distribution.argtypes = [C.POINTER(Mlp), i32, i32, i32, i32, vp, i64, i64, C.c_float, vp, vp,
+                                                 vp, vp]
+    lib.mcsd_early_stop_hidden.restype = C.c_int
+    lib.mcsd_early_stop_hidden.argtypes = [C.POINTER(Mlp), i32, i32, vp, i64, i64, C.c_float, vp, vp, vp]
     lib.mcsd_stream_read.restype = C.c_int
     lib.mcsd_stream_read.argtypes = [vp, C.c_size_t, vp, i32, vp]
     return lib
@@ -90,6 +103,7 @@ def _load() -> C.CDLL:
 lib = _load()
 
 KERNEL_ATTN_SWEEP, KERNEL_ATTN_MERGE, KERNEL_VERIFY_WALK, KERNEL_COMMIT_COPY, KERNEL_STREAM_READ = 0, 1, 2, 3, 4
+KERNEL_DECISION = 5
 
 
 def strerror(status: int) -> str:
@@ -234,6 +248,36 @@ def commit_path(view: MaskView, dtype: int, B: int, H: int, d: int, k_tree: Sequ
                               max_prefix, capacity, _ptr(out_path), _ptr(accept_len), _ptr(tokens), _ptr(new_tokens),
                               n_new, n_append, _ptr(prefix_lens_dev), _ptr(out_ids), _ptr(out_n_ids), _stream(stream))
     _check(st, "mcsd_commit_path")
+
+
+def make_mlp(weights: Sequence[torch.Tensor], biases: Sequence[torch.Tensor]) -> Mlp:
+    """mcsd_mlp_t for per-layer device tensors weight[l] fp32 [out_l][in_l], bias[l] fp32 [out_l]."""
+    n = len(weights)
+    if not (1 <= n <= MLP_MAX_LAYERS and len(biases) == n):
+        raise McsdError(MCSD_EINVAL, "make_mlp")
+    m = Mlp()
+    m.n_layers = n
+    m.width[0] = weights[0].shape[1]
+    for l in range(n):
+        m.width[l + 1] = weights[l].shape[0]
+        m.weight[l] = weights[l].data_ptr()
+        m.bias[l] = biases[l].data_ptr()
+    m._keep = (list(weights), list(biases))       # the struct holds raw pointers
+    return m
+
+
+def early_stop_distribution(mlp: Mlp, B: int, W: int, V: int, k: int, draft_rows: torch.Tensor, batch_stride: int,
+                            row_stride: int, beta: float, features: Optional[torch.Tensor], prob: torch.Tensor,
+                            stop: torch.Tensor, stream=None) -> None:
+    _check(lib.mcsd_early_stop_distribution(C.byref(mlp), B, W, V, k, _ptr(draft_rows), batch_stride, row_stride,
+                                            beta, _ptr(features), _ptr(prob), _ptr(stop), _stream(stream)),
+           "mcsd_early_stop_distribution")
+
+
+def early_stop_hidden(mlp: Mlp, B: int, W: int, hidden: torch.Tensor, batch_stride: int, row_stride: int,
+                      beta: float, prob: torch.Tensor, stop: torch.Tensor, stream=None) -> None:
+    _check(lib.mcsd_early_stop_hidden(C.byref(mlp), B, W, _ptr(hidden), batch_stride, row_stride, beta, _ptr(prob),
+                                      _ptr(stop), _stream(stream)), "mcsd_early_stop_hidden")
 
 
 def stream_read(src: torch.Tensor, sink: torch.Tensor, workgroups: int = 0, stream=None) -> None:

@@ -20,6 +20,7 @@ SOURCES = {
     "tree_attention.hip": [],
     "verify_tree.hip": ["-ffp-contract=off"],
     "commit_path.hip": [],
+    "decision.hip": [],
     "probe.hip": [],
 }
 

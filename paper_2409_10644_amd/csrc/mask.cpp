@@ -6,11 +6,11 @@
 
 #include "mcsd_internal.h"
 
-McsdProfileSlot g_mcsd_profile[5] = {{nullptr, nullptr}, {nullptr, nullptr}, {nullptr, nullptr}};
+McsdProfileSlot g_mcsd_profile[6] = {};
 
 extern "C" int mcsd_profile_next(mcsd_kernel_t kernel, void *start_event, void *stop_event)
 {
-    if ((int)kernel < 0 || (int)kernel > 4) return MCSD_EINVAL;
+    if ((int)kernel < 0 || (int)kernel > 5) return MCSD_EINVAL;
     if ((start_event == nullptr) != (stop_event == nullptr)) return MCSD_EINVAL;
     g_mcsd_profile[(int)kernel].start = (hipEvent_t)start_event;
     g_mcsd_profile[(int)kernel].stop = (hipEvent_t)stop_event;

@@ -31,7 +31,7 @@ static inline int mcsd_hip_status(hipError_t e) { return e == hipSuccess ? MCSD_
 
 // One-shot profiling events per kernel (see mcsd_profile_next); defined in mask.cpp.
 struct McsdProfileSlot { hipEvent_t start, stop; };
-extern McsdProfileSlot g_mcsd_profile[5];
+extern McsdProfileSlot g_mcsd_profile[6];
 
 // Launch `kernel` on `st`; if a profiling pair is armed for `which`, bracket the launch with it and disarm.
 template <typename... Args, typename... Actual>

@@ -114,3 +114,46 @@ def test_device_entry_points_reject_bad_arguments_before_any_launch(binding):
     st = lib.mcsd_verify_tree(C.byref(v), 1, 1, 32000, one, one, one, 45 * 32000, 29 * 32000, one, one, 4, one, one,
                               one, None, 0, None)
     assert st == binding.MCSD_EWORKSPACE                                          # target-init needs a workspace
+
+
+def test_early_stop_entry_points_reject_bad_arguments_before_any_launch(binding):
+    lib, one = binding.lib, C.c_void_p(256)
+
+    def mlp(widths, null_layer=None):
+        m = binding.Mlp()
+        m.n_layers = len(widths) - 1
+        for i, w in enumerate(widths):
+            m.width[i] = w
+        for l in range(m.n_layers):
+            m.weight[l] = None if l == null_layer else 256
+            m.bias[l] = 256
+        return m
+
+    def dist(m, B=1, W=16, V=32000, k=10, rows=one, prob=one, stop=one):
+        return lib.mcsd_early_stop_distribution(C.byref(m) if m is not None else None, B, W, V, k, rows, 17 * V, V, 0.4,
+                                                None, prob, stop, None)
+
+    ok = mlp((11, 64, 1))
+    assert dist(None) == binding.MCSD_EINVAL
+    assert dist(mlp((12, 64, 1))) == binding.MCSD_EINVAL                  # inputs must be k + 1
+    assert dist(mlp((11, 64, 2))) == binding.MCSD_EINVAL                  # one output
+    assert dist(mlp((11, 64, 1), null_layer=1)) == binding.MCSD_EINVAL
+    assert dist(mlp((11, 513, 1))) == binding.MCSD_EUNSUPPORTED           # hidden width limit
+    assert dist(mlp((18, 64, 1)), k=17) == binding.MCSD_EUNSUPPORTED      # k limit
+    assert dist(mlp((1, 64, 1)), k=0) == binding.MCSD_EINVAL
+    assert dist(ok, V=300000) == binding.MCSD_EUNSUPPORTED
+    assert dist(ok, W=0) == binding.MCSD_EINVAL
+    assert dist(ok, rows=None) == binding.MCSD_EINVAL
+    assert dist(ok, prob=None) == binding.MCSD_EINVAL
+    assert dist(ok, stop=None) == binding.MCSD_EINVAL
+    assert dist(ok, B=0, rows=None) == binding.MCSD_OK                    # nothing to do, nothing touched
+
+    def hid(m, B=1, W=16, x=one):
+        return lib.mcsd_early_stop_hidden(C.byref(m), B, W, x, 16 * 768, 768, 0.4, one, one, None)
+
+    assert hid(mlp((768, 256, 64, 1)), x=None) == binding.MCSD_EINVAL
+    assert hid(mlp((8193, 256, 64, 1))) == binding.MCSD_EUNSUPPORTED
+    m4 = mlp((768, 256, 64, 1))
+    m4.n_layers = 4
+    assert hid(m4) == binding.MCSD_EINVAL
+    assert hid(mlp((768, 256, 64, 1)), B=0, x=None) == binding.MCSD_OK
