@@ -261,6 +261,7 @@ def main():
                     help="sequences of the batched verification section (0 skips it)")
     ap.add_argument("--decision-batch", type=int, default=64,
                     help="trees per call in the early-stop decision-model section (0 = skip)")
+    ap.add_argument("--no-fp8kv", action="store_true", help="skip the fp8 prefix-cache variants of cfg4 / cfg5")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--eager", action="store_true", help="launch the step's kernels one by one instead of replaying a HIP graph")
     ap.add_argument("--traffic-calibration", action="store_true",
@@ -469,6 +470,61 @@ def main():
             torch.cuda.empty_cache()
         except Exception as ex:
             extra["cfg4_gqa"] = {"error": repr(ex)}
+    # the same sweeps over an fp8 (E4M3) prefix cache (beyond the paper's bf16 setting): half the prefix bytes
+    if not args.no_fp8kv:
+        for name in [x for x in args.extra.split(",") if x in ("cfg4", "cfg5")]:
+            try:
+                import numpy as np
+                from workloads import attention_inputs, prefix_lens
+                import oracle
+                sys.path.insert(0, os.path.join(ROOT, "tests"))
+                import gpu_helpers as H
+                w8 = WORKLOADS[name]
+                lens = prefix_lens(w8, 0)
+                cap = int(w8.prefix_max)
+                inp8 = attention_inputs(w8, seed=0, kv_capacity=cap, kv_fp8=(0.5, 0.25))
+                q8, kt8, vt8 = (H.dev(inp8[k], "bf16") for k in ("q", "k_tree", "v_tree"))
+                kp8, vp8 = torch.from_numpy(inp8["k_prefix"]).cuda(), torch.from_numpy(inp8["v_prefix"]).cuda()
+                lens8 = H.dev(np.ascontiguousarray(inp8["lens"], dtype=np.int32))
+                base8 = H.dev(np.ascontiguousarray(inp8["seq_base"], dtype=np.int64))
+                out8 = torch.zeros_like(q8)
+                v8 = binding.slice_mask(binding.build_mask(w8.branching), w8.gamma_max)
+                n8 = v8.n_nodes
+                ws8 = torch.empty(max(binding.tree_attention_fp8kv_workspace(w8.B, w8.H, w8.H, n8, 0, cap), 256),
+                                  dtype=torch.uint8, device="cuda")
+
+                def fcall(i):
+                    binding.tree_attention_fp8kv(v8, w8.B, w8.H, w8.H, 0, q8, kt8, vt8, inp8["node_stride"],
+                                                 kp8, vp8, inp8["k_scale"], inp8["v_scale"], base8, lens8, inp8["head_stride"],
+                                                 cap, float(np.float32(inp8["scale"])), out8, ws8)
+                fcall(0)
+                torch.cuda.synchronize()
+                got8 = out8[:, :, :n8].float().cpu().numpy().astype(np.float64)
+                M8 = oracle.build_mask(w8.branching)
+                rng8 = np.random.default_rng(3)
+                for _ in range(8):
+                    b_, h_, i_ = int(rng8.integers(w8.B)), int(rng8.integers(w8.H)), int(rng8.integers(n8))
+                    H.assert_close(got8[b_, h_, i_], oracle.tree_attention_row_fp8kv(inp8, M8, n8, b_, h_, i_), "bf16", "bench fp8kv")
+
+                class _F:
+                    pass
+                fs = _F()
+                fs.binding, fs.torch = binding, torch
+                f_avg, f_med, f_p10, f_p90 = time_kernel(fs, hip, binding.KERNEL_ATTN_SWEEP, fcall, args.extra_reps, warm=args.extra_reps)
+                fbytes = sum(w8.H * w8.d * (2 * int(L) * 1 + 4 * n8 * 2) for L in lens)
+                fflops = sum(w8.H * 4 * n8 * (int(L) + n8) * w8.d for L in lens)
+                extra[name + "_fp8kv"] = {
+                    "bound": "hbm", "kernel": "tree_attn_bf16_kernel<fp8 prefix>", "achieved": round(fbytes / (f_avg * 1e-3) / 1e9, 1),
+                    "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(fbytes / (f_avg * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+                    "traffic": None, "algorithmic_bytes_per_launch": int(fbytes), "flops_per_launch": int(fflops),
+                    "avg_launch_us": round(f_avg * 1e3, 2), "p10_us": round(f_p10 * 1e3, 2), "p90_us": round(f_p90 * 1e3, 2),
+                    "mfma_tflops": round(fflops / (f_avg * 1e-3) / 1e12, 1), "launches_timed": args.extra_reps,
+                    "attn_tree_tokens_per_s": round(w8.B * n8 / (f_avg * 1e-3), 1), "verified_vs_oracle": True,
+                    "workload": f"{name} with the prefix cache in fp8 E4M3 (B{w8.B} N={n8})"}
+                del kp8, vp8
+                torch.cuda.empty_cache()
+            except Exception as ex:
+                extra[name + "_fp8kv"] = {"error": repr(ex)}
     # the vocabulary pass at a batch that fills half the chip's compute units (one workgroup per sequence)
     if args.verify_batch > 0:
         try:

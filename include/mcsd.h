@@ -154,6 +154,32 @@ int mcsd_tree_attention_gqa(const mcsd_mask_view_t *mask, mcsd_dtype_t dtype, in
                             size_t workspace_bytes, void *hip_stream);
 
 /* ---------------------------------------------------------------------------------------------------
+ * Tree attention over a quantised prefix cache (beyond the paper's bf16 setting; same operation, Sec. 2.2).
+ *
+ * As mcsd_tree_attention_gqa with dtype MCSD_BF16 and d = 128, except that the prefix K/V cache holds 8-bit
+ * floating point: the OCP E4M3 format (1 sign, 4 exponent bits with bias 7, 3 mantissa bits, no infinities,
+ * S.1111.111 = NaN, largest finite value 448).  A stored key stands for stored * k_scale, a stored value for
+ * stored * v_scale (one scale each per call; k_scale > 0).  q, k_tree, v_tree and out stay bf16: the tree's own
+ * keys and values are fresh activations.  Conversion to bf16 is exact, so results differ from the bf16 entry point
+ * on the same (representable) values only by the rounding of P * v_scale.
+ *
+ * k_prefix_fp8, v_prefix_fp8 : DEVICE uint8, element (b, kv head, j, c) at seq_base[b] + h*head_stride + j*128 + c,
+ *                              in elements = bytes; head_stride and every seq_base[b] multiples of 16
+ * workspace                  : DEVICE, mcsd_tree_attention_fp8kv_workspace(...) bytes, 256-byte aligned
+ * Everything else as in mcsd_tree_attention_gqa.  Errors: the same, and MCSD_EINVAL for a scale that is not
+ * finite or a k_scale <= 0.
+ * ------------------------------------------------------------------------------------------------- */
+size_t mcsd_tree_attention_fp8kv_workspace(int32_t B, int32_t H_q, int32_t H_kv, int32_t n_nodes, int32_t row_begin,
+                                           int32_t max_prefix);
+
+int mcsd_tree_attention_fp8kv(const mcsd_mask_view_t *mask, int32_t B, int32_t H_q, int32_t H_kv, int32_t row_begin,
+                              const void *q, const void *k_tree, const void *v_tree, int64_t node_stride,
+                              const void *k_prefix_fp8, const void *v_prefix_fp8, float k_scale, float v_scale,
+                              const int64_t *seq_base_dev, const int32_t *prefix_lens_dev, int64_t head_stride,
+                              int32_t max_prefix, float softmax_scale, void *out, void *workspace,
+                              size_t workspace_bytes, void *hip_stream);
+
+/* ---------------------------------------------------------------------------------------------------
  * Verification (Sec. 2.1; Sec. 3.1; Fig. 1 steps 4-6)
  *
  * Recursive rejection sampling down the tree.  At a context with target row p and draft row q the

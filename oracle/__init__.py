@@ -48,6 +48,14 @@ def _load():
         L.mcsd_oracle_tree_attention_row.restype = None
         L.mcsd_oracle_tree_attention_row.argtypes = [i32, i32, i32, i32, i64, vp, vp, vp, vp, vp, vp, vp, i64,
                                                      f64, vp, i64, i32, i32, i32, vp]
+        L.mcsd_oracle_fp8_e4m3_value.restype = f64
+        L.mcsd_oracle_fp8_e4m3_value.argtypes = [C.c_uint8]
+        L.mcsd_oracle_tree_attention_fp8kv.restype = None
+        L.mcsd_oracle_tree_attention_fp8kv.argtypes = [i32, i32, i32, i32, i64, vp, vp, vp, vp, vp, f64, f64, vp, vp, i64,
+                                                       f64, vp, i64, vp]
+        L.mcsd_oracle_tree_attention_row_fp8kv.restype = None
+        L.mcsd_oracle_tree_attention_row_fp8kv.argtypes = [i32, i32, i32, i64, vp, vp, vp, vp, vp, f64, f64, vp, vp, i64,
+                                                           f64, vp, i64, i32, i32, i32, vp]
         L.mcsd_oracle_verify_tree.restype = C.c_int
         L.mcsd_oracle_verify_tree.argtypes = [i32, vp, i32, i32, i32, vp, vp, vp, i64, i64, vp, vp, i32, vp, vp, vp]
         L.mcsd_oracle_tree_sum.restype = f64
@@ -162,6 +170,46 @@ def tree_attention_row(inp: dict, M: np.ndarray, n: int, b: int, h: int, i: int)
                                            _ptr(vt), _ptr(kp), _ptr(vp), _ptr(base), _ptr(lens),
                                            int(inp["head_stride"]), float(np.float32(inp["scale"])), _ptr(M),
                                            M.shape[1], b, h, i, _ptr(out))
+    return out
+
+
+def fp8_e4m3_value(code: int) -> float:
+    """The number an 8-bit E4M3 code stands for (NaN for S.1111.111)."""
+    return float(_load().mcsd_oracle_fp8_e4m3_value(int(code) & 255))
+
+
+def _fp8_args(inp: dict):
+    q, kt, vt = (_check_store(inp[k], "bf16") for k in ("q", "k_tree", "v_tree"))
+    kp, vp = (np.ascontiguousarray(inp[k]) for k in ("k_prefix", "v_prefix"))
+    assert kp.dtype == np.uint8 and vp.dtype == np.uint8 and inp["dtype"] == "bf16"
+    lens = np.ascontiguousarray(inp["lens"], dtype=np.int32)
+    base = np.ascontiguousarray(inp["seq_base"], dtype=np.int64)
+    return q, kt, vt, kp, vp, lens, base
+
+
+def tree_attention_fp8kv(inp: dict, M: np.ndarray, n: int) -> np.ndarray:
+    """All outputs, binary64 [B][H][n][d], for an input dict as made by workloads.attention_inputs(kv_fp8=True)."""
+    q, kt, vt, kp, vp, lens, base = _fp8_args(inp)
+    B, H, _, d = q.shape
+    M = np.ascontiguousarray(M, dtype=np.uint8)
+    out = np.zeros((B, H, n, d), dtype=np.float64)
+    _load().mcsd_oracle_tree_attention_fp8kv(B, H, d, n, int(inp["node_stride"]), _ptr(q), _ptr(kt), _ptr(vt), _ptr(kp),
+                                             _ptr(vp), float(np.float32(inp["k_scale"])), float(np.float32(inp["v_scale"])),
+                                             _ptr(base), _ptr(lens), int(inp["head_stride"]),
+                                             float(np.float32(inp["scale"])), _ptr(M), M.shape[1], _ptr(out))
+    return out
+
+
+def tree_attention_row_fp8kv(inp: dict, M: np.ndarray, n: int, b: int, h: int, i: int) -> np.ndarray:
+    q, kt, vt, kp, vp, lens, base = _fp8_args(inp)
+    _, H, _, d = q.shape
+    M = np.ascontiguousarray(M, dtype=np.uint8)
+    out = np.zeros(d, dtype=np.float64)
+    _load().mcsd_oracle_tree_attention_row_fp8kv(H, d, n, int(inp["node_stride"]), _ptr(q), _ptr(kt), _ptr(vt), _ptr(kp),
+                                                 _ptr(vp), float(np.float32(inp["k_scale"])),
+                                                 float(np.float32(inp["v_scale"])), _ptr(base), _ptr(lens),
+                                                 int(inp["head_stride"]), float(np.float32(inp["scale"])), _ptr(M),
+                                                 M.shape[1], b, h, i, _ptr(out))
     return out
 
 

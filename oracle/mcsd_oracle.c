@@ -107,23 +107,36 @@ void mcsd_oracle_slice_mask(const uint8_t *M, int64_t n_full, int64_t n, uint8_t
  * Inputs are fp32 (dtype 0) or bfloat16 bit patterns (dtype 1); both convert to binary64 exactly.
  * Layouts: q, k_tree, v_tree [B][H][node_stride][d]; prefix K/V: element (b,h,j,c) at
  * seq_base[b] + h*head_stride + j*d + c.
+ * A quantised prefix cache (beyond the paper's bf16 setting) stores 8-bit floating point, dtype 2: the OCP
+ * "E4M3" format, 1 sign, 4 exponent (bias 7) and 3 mantissa bits, no infinities, S.1111.111 = NaN, largest
+ * finite value 448; a stored value stands for stored * k_scale (keys) or stored * v_scale (values).
  * ---------------------------------------------------------------------------------------------- */
+double mcsd_oracle_fp8_e4m3_value(uint8_t code)
+{
+    const int sign = code >> 7, e = (code >> 3) & 15, m = code & 7;
+    double v;
+    if (e == 15 && m == 7) return NAN;
+    if (e == 0) v = ldexp((double)m / 8.0, -6);             /* subnormal: m/8 * 2^(1-bias) */
+    else v = ldexp(1.0 + (double)m / 8.0, e - 7);
+    return sign ? -v : v;
+}
+
 static double load_elem(const void *p, int64_t idx, int32_t dtype)
 {
     if (dtype == 0) return (double)((const float *)p)[idx];
+    if (dtype == 2) return mcsd_oracle_fp8_e4m3_value(((const uint8_t *)p)[idx]);
     uint32_t bits = (uint32_t)((const uint16_t *)p)[idx] << 16;   /* bfloat16 = upper half of a binary32 */
     float f;
     memcpy(&f, &bits, sizeof f);
     return (double)f;
 }
 
-/* One output row o_i (d values) for one (b, h, i). */
-void mcsd_oracle_tree_attention_row(int32_t dtype, int32_t H, int32_t d, int32_t n, int64_t node_stride,
-                                    const void *q, const void *k_tree, const void *v_tree,
-                                    const void *k_prefix, const void *v_prefix,
-                                    const int64_t *seq_base, const int32_t *lens, int64_t head_stride,
-                                    double scale, const uint8_t *M, int64_t mask_stride,
-                                    int32_t b, int32_t h, int32_t i, double *out_row)
+/* One output row o_i (d values) for one (b, h, i); the prefix cache has its own element type and scales. */
+static void attention_row(int32_t dtype, int32_t kv_dtype, double k_scale, double v_scale, int32_t H, int32_t d,
+                          int32_t n, int64_t node_stride, const void *q, const void *k_tree, const void *v_tree,
+                          const void *k_prefix, const void *v_prefix, const int64_t *seq_base, const int32_t *lens,
+                          int64_t head_stride, double scale, const uint8_t *M, int64_t mask_stride, int32_t b,
+                          int32_t h, int32_t i, double *out_row)
 {
     const int64_t L = lens[b];
     const int64_t tree0 = ((int64_t)b * H + h) * node_stride * d;          /* (b,h,0,0) in q/k_tree/v_tree */
@@ -141,7 +154,7 @@ void mcsd_oracle_tree_attention_row(int32_t dtype, int32_t H, int32_t d, int32_t
         for (int32_t c = 0; c < d; ++c) {
             double qc = load_elem(q, tree0 + (int64_t)i * d + c, dtype);
             double kc = tree ? load_elem(k_tree, tree0 + jj * d + c, dtype)
-                             : load_elem(k_prefix, pre0 + jj * d + c, dtype);
+                             : k_scale * load_elem(k_prefix, pre0 + jj * d + c, kv_dtype);
             dot += qc * kc;
         }
         s[j] = scale * dot;
@@ -160,12 +173,49 @@ void mcsd_oracle_tree_attention_row(int32_t dtype, int32_t H, int32_t d, int32_t
         const double w = s[j] / denom;
         for (int32_t c = 0; c < d; ++c) {
             double vc = tree ? load_elem(v_tree, tree0 + jj * d + c, dtype)
-                             : load_elem(v_prefix, pre0 + jj * d + c, dtype);
+                             : v_scale * load_elem(v_prefix, pre0 + jj * d + c, kv_dtype);
             out_row[c] += w * vc;
         }
     }
     free(s);
     free(vis);
+}
+
+void mcsd_oracle_tree_attention_row(int32_t dtype, int32_t H, int32_t d, int32_t n, int64_t node_stride,
+                                    const void *q, const void *k_tree, const void *v_tree,
+                                    const void *k_prefix, const void *v_prefix,
+                                    const int64_t *seq_base, const int32_t *lens, int64_t head_stride,
+                                    double scale, const uint8_t *M, int64_t mask_stride,
+                                    int32_t b, int32_t h, int32_t i, double *out_row)
+{
+    attention_row(dtype, dtype, 1.0, 1.0, H, d, n, node_stride, q, k_tree, v_tree, k_prefix, v_prefix, seq_base, lens,
+                  head_stride, scale, M, mask_stride, b, h, i, out_row);
+}
+
+/* The same with an fp8 (E4M3) prefix cache: q, k_tree, v_tree are bfloat16. */
+void mcsd_oracle_tree_attention_row_fp8kv(int32_t H, int32_t d, int32_t n, int64_t node_stride, const void *q,
+                                          const void *k_tree, const void *v_tree, const void *k_prefix,
+                                          const void *v_prefix, double k_scale, double v_scale, const int64_t *seq_base,
+                                          const int32_t *lens, int64_t head_stride, double scale, const uint8_t *M,
+                                          int64_t mask_stride, int32_t b, int32_t h, int32_t i, double *out_row)
+{
+    attention_row(1, 2, k_scale, v_scale, H, d, n, node_stride, q, k_tree, v_tree, k_prefix, v_prefix, seq_base, lens,
+                  head_stride, scale, M, mask_stride, b, h, i, out_row);
+}
+
+void mcsd_oracle_tree_attention_fp8kv(int32_t B, int32_t H, int32_t d, int32_t n, int64_t node_stride, const void *q,
+                                      const void *k_tree, const void *v_tree, const void *k_prefix, const void *v_prefix,
+                                      double k_scale, double v_scale, const int64_t *seq_base, const int32_t *lens,
+                                      int64_t head_stride, double scale, const uint8_t *M, int64_t mask_stride,
+                                      double *out)
+{
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int64_t bh = 0; bh < (int64_t)B * H; ++bh) {
+        const int32_t b = (int32_t)(bh / H), h = (int32_t)(bh % H);
+        for (int32_t i = 0; i < n; ++i)
+            attention_row(1, 2, k_scale, v_scale, H, d, n, node_stride, q, k_tree, v_tree, k_prefix, v_prefix, seq_base,
+                          lens, head_stride, scale, M, mask_stride, b, h, i, out + ((bh * n) + i) * d);
+    }
 }
 
 /* All rows: out is binary64 [B][H][n][d].  (b,h) pairs are independent and may run on several threads;

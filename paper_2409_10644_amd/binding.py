@@ -18,6 +18,7 @@ EXPORTS = ["mcsd_strerror", "mcsd_build_mask", "mcsd_slice_mask", "mcsd_free_mas
            "mcsd_tree_attention_workspace", "mcsd_tree_attention",
            "mcsd_tree_attention_rows_workspace", "mcsd_tree_attention_rows",
            "mcsd_tree_attention_gqa_workspace", "mcsd_tree_attention_gqa",
+           "mcsd_tree_attention_fp8kv_workspace", "mcsd_tree_attention_fp8kv",
            "mcsd_verify_tree_workspace", "mcsd_verify_tree", "mcsd_commit_path", "mcsd_early_stop_distribution",
            "mcsd_early_stop_hidden", "mcsd_profile_next", "mcsd_stream_read"]
 DECISION_MAX_K, MLP_MAX_LAYERS, MLP_MAX_WIDTH, MLP_MAX_INPUTS = 16, 3, 512, 8192
@@ -85,6 +86,11 @@ def _load() -> C.CDLL:
     lib.mcsd_tree_attention_gqa.restype = C.c_int
     lib.mcsd_tree_attention_gqa.argtypes = [C.POINTER(MaskView), C.c_int, i32, i32, i32, i32, i32, vp, vp, vp, i64, vp,
                                             vp, vp, vp, i64, i32, C.c_float, vp, vp, C.c_size_t, vp]
+    lib.mcsd_tree_attention_fp8kv_workspace.restype = C.c_size_t
+    lib.mcsd_tree_attention_fp8kv_workspace.argtypes = [i32, i32, i32, i32, i32, i32]
+    lib.mcsd_tree_attention_fp8kv.restype = C.c_int
+    lib.mcsd_tree_attention_fp8kv.argtypes = [C.POINTER(MaskView), i32, i32, i32, i32, vp, vp, vp, i64, vp, vp,
+                                              C.c_float, C.c_float, vp, vp, i64, i32, C.c_float, vp, vp, C.c_size_t, vp]
     lib.mcsd_commit_path.restype = C.c_int
     lib.mcsd_commit_path.argtypes = [C.POINTER(MaskView), C.c_int, i32, i32, i32, i32, C.POINTER(vp), C.POINTER(vp),
                                      i64, C.POINTER(vp), C.POINTER(vp), vp, i64, i32, i32, vp, vp, vp, vp, i32, i32,
@@ -213,6 +219,24 @@ def tree_attention_gqa(view: MaskView, dtype: int, B: int, H_q: int, H_kv: int, 
                                      _ptr(prefix_lens_dev), head_stride, max_prefix, softmax_scale, _ptr(out),
                                      _ptr(workspace), ws_bytes, _stream(stream))
     _check(st, "mcsd_tree_attention_gqa")
+
+
+def tree_attention_fp8kv_workspace(B: int, H_q: int, H_kv: int, n_nodes: int, row_begin: int, max_prefix: int) -> int:
+    return int(lib.mcsd_tree_attention_fp8kv_workspace(B, H_q, H_kv, n_nodes, row_begin, max_prefix))
+
+
+def tree_attention_fp8kv(view: MaskView, B: int, H_q: int, H_kv: int, row_begin: int, q: torch.Tensor,
+                         k_tree: torch.Tensor, v_tree: torch.Tensor, node_stride: int,
+                         k_prefix_fp8: Optional[torch.Tensor], v_prefix_fp8: Optional[torch.Tensor], k_scale: float,
+                         v_scale: float, seq_base_dev: torch.Tensor, prefix_lens_dev: torch.Tensor, head_stride: int,
+                         max_prefix: int, softmax_scale: float, out: torch.Tensor, workspace: Optional[torch.Tensor],
+                         stream=None) -> None:
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    st = lib.mcsd_tree_attention_fp8kv(C.byref(view), B, H_q, H_kv, row_begin, _ptr(q), _ptr(k_tree), _ptr(v_tree),
+                                       node_stride, _ptr(k_prefix_fp8), _ptr(v_prefix_fp8), k_scale, v_scale,
+                                       _ptr(seq_base_dev), _ptr(prefix_lens_dev), head_stride, max_prefix,
+                                       softmax_scale, _ptr(out), _ptr(workspace), ws_bytes, _stream(stream))
+    _check(st, "mcsd_tree_attention_fp8kv")
 
 
 def verify_tree_workspace(view: MaskView, mode: int, B: int, n_new: int) -> int:

@@ -50,6 +50,7 @@ struct AttnParams {
     int32_t max_prefix;
     int64_t node_stride, head_stride;
     float c;          // softmax_scale * log2(e)
+    float k_scale, v_scale;   // fp8 prefix cache: value = stored * scale
     int32_t S;        // key splits of the prefix
     int32_t G;        // workgroups per (b,h): S, plus one for the tree's own keys when the bf16 sweep splits the prefix
     int32_t tps;      // tiles per split (bf16 sweep): split s owns tiles [s*tps, (s+1)*tps) of every sequence
@@ -71,13 +72,15 @@ struct AttnPlan {
 
 __host__ __device__ inline int tile_keys_bf16(int QBP) { return QBP == 1 ? 128 : 64; }   // == SweepCfg::T
 
-AttnPlan make_plan(int dtype, int B, int Hq, int Hkv, int n_rows, int max_prefix)
+AttnPlan make_plan(int dtype, int B, int Hq, int Hkv, int n_rows, int max_prefix, bool f8 = false)
 {
     AttnPlan pl;
     const int grp = Hq / Hkv;
     if (dtype == MCSD_BF16) {
         const int qb = (n_rows + 31) / 32;
         pl.bph = qb <= 1 ? 1 : (qb == 2 ? 2 : 4);
+        // the fp8 ring is sized for 64-key tiles: a single query block of one head runs as two, the second one empty
+        if (f8 && pl.bph == 1 && grp % 2 != 0) pl.bph = 2;
         // grouped-query attention: as many query heads of one kv head as fit the workgroup's four query blocks
         // share its K/V stream (so those bytes leave HBM once for all of them)
         pl.hpw = 1;
@@ -108,7 +111,7 @@ AttnPlan make_plan(int dtype, int B, int Hq, int Hkv, int n_rows, int max_prefix
         const long v = atol(ov);
         if (v >= 1 && v <= 64) S = v;
     }
-    pl.NS = 2;                                              // double buffer, two workgroups per compute unit
+    pl.NS = f8 ? 4 : 2;                                     // LDS stages, two workgroups per compute unit
     pl.S = (int)S;
     // With split keys the tree's own tiles (masked, through registers) would lengthen one split's critical path:
     // they get a workgroup of their own, which costs one more partial result.  Only when all workgroups are
@@ -137,6 +140,14 @@ __device__ inline s16x4_t lds_read_tr16(const unsigned char *p)
 {
     return __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4_t __attribute__((address_space(3))) *)(p));
 }
+// 8-bit variant.  Within 16 lanes, lane i receives byte i%8 of the 8-byte words addressed by lanes 2e + i/8,
+// e = 0..7 (checked on the hardware): lanes 2e and 2e+1 point at the two halves of a 16-byte piece of the row for
+// slot e, and lane i ends up with column i of that piece from all eight rows.
+typedef __attribute__((ext_vector_type(2))) int i32x2_t;
+__device__ inline i32x2_t lds_read_tr8(const unsigned char *p)
+{
+    return __builtin_amdgcn_ds_read_tr8_b64_v2i32((i32x2_t __attribute__((address_space(3))) *)(p));
+}
 
 // 16 bytes per lane from global memory straight into LDS: lane l reads gbase + voff and lands at lds_base + 16*l
 // (gbase and lds_base uniform).  Written as assembly on purpose: the compiler knows nothing about where such a
@@ -160,27 +171,34 @@ __device__ inline void load_to_lds16(const void *gbase, uint32_t voff, void *lds
 // ---------------------------------------------------------------------------------------------------
 // bf16 / MFMA kernel
 // ---------------------------------------------------------------------------------------------------
-template <int D, int QBP, int NS_>
+// F8: the prefix K/V cache holds fp8 (e4m3) elements; a ring stage is then a raw fp8 tile (half the bytes, twice
+// the stages) that the operand reads convert to bf16 on their way into the matrix cores.
+template <int D, int QBP, int NS_, bool F8 = false>
 struct SweepCfg {
     static constexpr int WAVES = 4;
     static constexpr int KG = 4 / QBP;                 // key groups: wavefronts that share a query block and split the keys
     static constexpr int KPW = QBP == 4 ? 2 : 1;       // 32-key blocks per wavefront per tile
     static constexpr int THREADS = WAVES * 64;
     static constexpr int T = 32 * KG * KPW;            // keys per tile (64, 64, 128 for QBP = 4, 2, 1)
-    static constexpr int RB = D * 2;                   // bytes per K/V row
-    static constexpr int CPR = RB / 16;                // 16-byte chunks per row
+    static constexpr int RB = D * 2;                   // bytes per bf16 K/V row (tree tiles, register path)
+    static constexpr int RBP = F8 ? D : D * 2;         // bytes per prefix K/V row (ring stages)
+    static constexpr int CPR = RBP / 16;               // 16-byte chunks per prefix row
     static constexpr int RPI = 64 / CPR;               // rows covered by one direct-to-LDS instruction (1 KiB)
-    static constexpr int TILE_K = T * RB;              // bytes of the K half of a stage; V follows
+    static constexpr int TILE_K = T * RBP;             // bytes of the K half of a ring stage; V follows
     static constexpr int TILE = 2 * TILE_K;
+    static constexpr int BTILE_K = T * RB;             // the same for a bf16 tile written through registers
+    static constexpr int BCPR = RB / 16;
     static constexpr int NI = T / RPI / WAVES;         // direct-to-LDS instructions per wavefront for K (same for V)
     static constexpr int DPT = 2 * NI;                 // ... per tile
     static constexpr int NS = NS_;                     // LDS stages: one being computed, NS - 1 being filled
     static constexpr int KS = D / 16;                  // k-steps of S^T = K Q^T
     static constexpr int CB = D / 32;                  // 32-row blocks of O^T
-    static constexpr int CPT = T * CPR / THREADS;      // 16-byte chunks per thread for K (same for V), register path
+    static constexpr int CPT = T * BCPR / THREADS;     // 16-byte bf16 chunks per thread for K (same for V), register path
     static constexpr int MSLOT = 32 * D * 4 + 256;     // LDS bytes to hand one query block's (O, m, l) to another wavefront
-    static constexpr int LDS_BYTES = NS * TILE > (KG - 1) * QBP * MSLOT ? NS * TILE : (KG - 1) * QBP * MSLOT;
+    static constexpr int RING = NS * TILE > 2 * BTILE_K ? NS * TILE : 2 * BTILE_K;
+    static constexpr int LDS_BYTES = RING > (KG - 1) * QBP * MSLOT ? RING : (KG - 1) * QBP * MSLOT;
     static_assert(NI >= 1 && CPT >= 1 && (NS - 2) * DPT < 64 && LDS_BYTES <= 160 * 1024 - 64, "tile does not map onto the workgroup");
+    static_assert(!F8 || D == 128, "fp8 tiles are laid out for 128-byte rows");
 };
 
 // XOR swizzle of the 16-byte chunk index inside row r.  With it, 16 consecutive rows read at the same logical
@@ -192,6 +210,26 @@ __device__ inline int swz(int r)
     return D == 128 ? (((r & 3) << 2) | ((r >> 2) & 3)) : ((((r >> 1) & 1) << 2) | ((r >> 2) & 3));
 }
 
+// The same for fp8 tiles (128-byte rows, 8 chunks): bijective on row bits 1-3, so 16 consecutive rows read at one
+// chunk with 16-byte loads (K operands) hit 16 different bank groups together with the row's parity, and the rows
+// {0..3, 8..11} + 4g read at two neighbouring chunks by the transpose loads (V operands) do as well.
+__device__ inline int swz8(int r)
+{
+    return ((r >> 2) & 1) | (((r >> 1) & 1) << 1) | (((r >> 3) & 1) << 2);
+}
+
+// 8 fp8 (e4m3, OCP) values in two dwords -> 8 bf16, exact.
+__device__ inline bf16x8_t fp8x8_to_bf16(unsigned lo, unsigned hi)
+{
+    typedef __attribute__((ext_vector_type(4))) unsigned u4;
+    u4 w;
+    w[0] = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(lo, 1.0f, false));
+    w[1] = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(lo, 1.0f, true));
+    w[2] = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(hi, 1.0f, false));
+    w[3] = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(hi, 1.0f, true));
+    return __builtin_bit_cast(bf16x8_t, w);
+}
+
 // Log2-domain slack of the running reference maximum: the accumulators are rescaled only when a block's maximum
 // exceeds the reference by more than this, so exponentiated scores stay below 2^RESCALE_SLACK.  The result is
 // exact: numerator and denominator always share the same reference.
@@ -201,6 +239,8 @@ constexpr float RESCALE_SLACK = 6.f;
 struct LaneAddr {
     int k;   // K operand: row (kg*32 + ln), chunk g ^ swz; XOR ks*32 selects the k-step
     int v;   // V^T operand: row (kg*32 + 4g + j/4), chunk/sub of this lane; XOR ct*16 and an immediate select the rest
+    int k8;  // the same inside an fp8 tile: row (kg*32 + ln), half g of chunk swz8; XOR ks*16 selects the k-step
+    int v8;  // fp8 V^T operand (8-bit transpose load): row of this lane's key slot, chunk (ln/16) ^ swz8, half ln & 1
 };
 
 // State of one 32-query block held by a wavefront.
@@ -215,13 +255,15 @@ struct QBlock {
 // (kept as dwords: pb[r/8] is one B operand).  The empty asm keeps the pair where it is written, between two MFMAs.
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
 typedef __attribute__((ext_vector_type(4))) unsigned u32x4_t;
-__device__ inline void softmax_exp2(const f32x16_t &sacc, int r, float c, float mc, float &psum, u32x4_t *pb)
+// SCALED: the packed values carry the factor vs (the scale of an fp8 V tile); the denominator does not.
+template <bool SCALED = false>
+__device__ inline void softmax_exp2(const f32x16_t &sacc, int r, float c, float mc, float &psum, u32x4_t *pb, float vs = 1.f)
 {
     const float p0 = fast_exp2(fmaf(sacc[r], c, -mc)), p1 = fast_exp2(fmaf(sacc[r + 1], c, -mc));
     psum += p0 + p1;
     bf16x2_t pk;
-    pk[0] = (__bf16)p0;
-    pk[1] = (__bf16)p1;
+    pk[0] = (__bf16)(SCALED ? p0 * vs : p0);
+    pk[1] = (__bf16)(SCALED ? p1 * vs : p1);
     unsigned u = __builtin_bit_cast(unsigned, pk);
     asm volatile("" : "+v"(u));
     pb[r / 8][(r % 8) / 2] = u;
@@ -232,18 +274,29 @@ __device__ inline void softmax_exp2(const f32x16_t &sacc, int r, float c, float 
 //     QK_0, QK_1 | block maxima, rare rescale | exp(0) | PV_0 with exp(1) in its shadow | PV_1
 // Operand reads are issued ahead of their use.  MODE 0: all keys visible; otherwise bit k of bits[u] says whether
 // key k of block u is visible to this lane's query.
-template <int D, int QBP, int NS, int MODE>
+// F8K: the kernel serves an fp8 prefix cache: the reference maximum is kept in log2 units (tiles of different
+// scale share it) and P carries the V scale `vs` of the tile.  F8T: this stage is a raw fp8 tile.
+template <int D, int QBP, int NS, int MODE, bool F8K = false, bool F8T = false>
 __device__ inline void attn_tile(const unsigned char *stage, const LaneAddr la, QBlock<D> &qs, float c, int g,
-                                 const uint32_t *bits)
+                                 const uint32_t *bits, float vs = 1.f)
 {
-    using C = SweepCfg<D, QBP, NS>;
+    using C = SweepCfg<D, QBP, NS, F8K>;
     constexpr int U = C::KPW;
+    constexpr int ROWB = F8T ? C::RBP : C::RB;             // bytes per row of this stage
+    constexpr int VOFF = F8T ? C::TILE_K : C::BTILE_K;     // where its V half starts
     // K rows of the blocks (A operands of S^T = K Q^T); block u sits 32*u rows below the lane's base row
     bf16x8_t kf[U][C::KS];
 #pragma unroll
     for (int u = 0; u < U; ++u)
 #pragma unroll
-        for (int ks = 0; ks < C::KS; ++ks) kf[u][ks] = *(const bf16x8_t *)(stage + (la.k ^ (ks * 32)) + u * 32 * C::RB);
+        for (int ks = 0; ks < C::KS; ++ks) {
+            if constexpr (F8T) {
+                const uint2 raw = *(const uint2 *)(stage + (la.k8 ^ (ks * 16)) + u * 32 * ROWB);
+                kf[u][ks] = fp8x8_to_bf16(raw.x, raw.y);
+            } else {
+                kf[u][ks] = *(const bf16x8_t *)(stage + (la.k ^ (ks * 32)) + u * 32 * ROWB);
+            }
+        }
     __builtin_amdgcn_sched_barrier(0);
     // S^T[key][query] : lane (query = ln, half g) gets keys 8*(r/4) + 4*g + r%4, r = 0..15
     f32x16_t sacc[U];
@@ -256,16 +309,22 @@ __device__ inline void attn_tile(const unsigned char *stage, const LaneAddr la, 
     // V^T fragments via the LDS transpose load, issued ahead of their use: block 0's during the softmax, block 1's
     // before the first PV MFMA.  The reads of one k-step pair (ks2, e4) sit 16*ks2 + 8*e4 rows below the lane's
     // base row; the chunk select is cb*4 ^ e4*2.
-    const unsigned char *vst = stage + C::TILE_K;
+    const unsigned char *vst = stage + VOFF;
     bf16x8_t vf[U][2][C::CB];
     auto read_v = [&](int u) {
 #pragma unroll
         for (int ks2 = 0; ks2 < 2; ++ks2)
 #pragma unroll
             for (int cb = 0; cb < C::CB; ++cb) {
-                const s16x4_t lo = lds_read_tr16(vst + (la.v ^ (((cb * 4) ^ 0) * 16)) + (u * 32 + ks2 * 16) * C::RB);
-                const s16x4_t hi = lds_read_tr16(vst + (la.v ^ (((cb * 4) ^ 2) * 16)) + (u * 32 + ks2 * 16 + 8) * C::RB);
-                vf[u][ks2][cb] = __builtin_bit_cast(bf16x8_t, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+                if constexpr (F8T) {
+                    // one 8-bit transpose load: the 8 key slots of this lane's column (slot e = key 8(e/4) + 4g + e%4)
+                    const i32x2_t t = lds_read_tr8(vst + (la.v8 ^ ((cb * 2) * 16)) + (u * 32 + ks2 * 16) * ROWB);
+                    vf[u][ks2][cb] = fp8x8_to_bf16((unsigned)t[0], (unsigned)t[1]);
+                } else {
+                    const s16x4_t lo = lds_read_tr16(vst + (la.v ^ (((cb * 4) ^ 0) * 16)) + (u * 32 + ks2 * 16) * ROWB);
+                    const s16x4_t hi = lds_read_tr16(vst + (la.v ^ (((cb * 4) ^ 2) * 16)) + (u * 32 + ks2 * 16 + 8) * ROWB);
+                    vf[u][ks2][cb] = __builtin_bit_cast(bf16x8_t, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+                }
             }
     };
     read_v(0);
@@ -285,11 +344,13 @@ __device__ inline void attn_tile(const unsigned char *stage, const LaneAddr la, 
         for (int r = 2; r < 16; r += 2) mx = fmaxf(fmaxf(mx, sacc[u][r]), sacc[u][r + 1]);
     }
     mx = half_swap_max(mx);
+    if (F8K) mx *= c;                                       // log2 units from here on (c > 0)
+    const float cm = F8K ? 1.f : c;                         // what turns a difference of reference maxima into log2 units
     // rescale only when the maximum outgrows the reference by more than the slack (first tile: -inf)
-    const bool grow = (mx - qs.m_ref) * c > RESCALE_SLACK;
+    const bool grow = (mx - qs.m_ref) * cm > RESCALE_SLACK;
     if (__builtin_amdgcn_ballot_w64(grow) != 0) {
         const float m_new = grow ? mx : qs.m_ref;
-        const float alpha = m_new == qs.m_ref ? 1.f : fast_exp2((qs.m_ref - m_new) * c);   // -inf reference: exp2(-inf) = 0
+        const float alpha = m_new == qs.m_ref ? 1.f : fast_exp2((qs.m_ref - m_new) * cm);   // -inf reference: exp2(-inf) = 0
         qs.m_ref = m_new;
         qs.l_run *= alpha;
 #pragma unroll
@@ -297,21 +358,21 @@ __device__ inline void attn_tile(const unsigned char *stage, const LaneAddr la, 
 #pragma unroll
             for (int r = 0; r < 16; ++r) qs.o[cb][r] *= alpha;
     }
-    const float mc = (qs.m_ref == -INFINITY ? 0.f : qs.m_ref) * c;
+    const float mc = (qs.m_ref == -INFINITY ? 0.f : qs.m_ref) * cm;
     u32x4_t pb[U][2];
     float psum = 0.f;
     // With one block per wavefront the exponentials of its second half of keys (registers 8..15, the operand of the
     // second k-step pair) run in the shadow of the first half's PV MFMAs.
 #pragma unroll
-    for (int r = 0; r < (U == 1 ? 8 : 16); r += 2) softmax_exp2(sacc[0], r, c, mc, psum, pb[0]);
+    for (int r = 0; r < (U == 1 ? 8 : 16); r += 2) softmax_exp2<F8K>(sacc[0], r, c, mc, psum, pb[0], vs);
     __builtin_amdgcn_sched_barrier(0);
     // O^T[c][query] += V^T[c][key] * P^T[key][query]
     if (U == 1) {
 #pragma unroll
         for (int cb = 0; cb < C::CB; ++cb) {
             qs.o[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[0][0][cb], __builtin_bit_cast(bf16x8_t, pb[0][0]), qs.o[cb], 0, 0, 0);
-            if (C::CB == 4) softmax_exp2(sacc[0], 8 + 2 * cb, c, mc, psum, pb[0]);
-            else { softmax_exp2(sacc[0], 8 + 4 * cb, c, mc, psum, pb[0]); softmax_exp2(sacc[0], 10 + 4 * cb, c, mc, psum, pb[0]); }
+            if (C::CB == 4) softmax_exp2<F8K>(sacc[0], 8 + 2 * cb, c, mc, psum, pb[0], vs);
+            else { softmax_exp2<F8K>(sacc[0], 8 + 4 * cb, c, mc, psum, pb[0], vs); softmax_exp2<F8K>(sacc[0], 10 + 4 * cb, c, mc, psum, pb[0], vs); }
             __builtin_amdgcn_sched_barrier(0);
         }
 #pragma unroll
@@ -327,8 +388,8 @@ __device__ inline void attn_tile(const unsigned char *stage, const LaneAddr la, 
         for (int i = 0; i < 2 * C::CB; ++i) {
             const int ks2 = i / C::CB, cb = i % C::CB;
             qs.o[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[0][ks2][cb], __builtin_bit_cast(bf16x8_t, pb[0][ks2]), qs.o[cb], 0, 0, 0);
-            if (C::CB == 4) softmax_exp2(sacc[U - 1], 2 * i, c, mc, psum, pb[U - 1]);
-            else { softmax_exp2(sacc[U - 1], 4 * i, c, mc, psum, pb[U - 1]); softmax_exp2(sacc[U - 1], 4 * i + 2, c, mc, psum, pb[U - 1]); }
+            if (C::CB == 4) softmax_exp2<F8K>(sacc[U - 1], 2 * i, c, mc, psum, pb[U - 1], vs);
+            else { softmax_exp2<F8K>(sacc[U - 1], 4 * i, c, mc, psum, pb[U - 1], vs); softmax_exp2<F8K>(sacc[U - 1], 4 * i + 2, c, mc, psum, pb[U - 1], vs); }
             __builtin_amdgcn_sched_barrier(0);
         }
     }
@@ -340,11 +401,11 @@ __device__ inline void attn_tile(const unsigned char *stage, const LaneAddr la, 
     qs.l_run += psum;
 }
 
-template <int D, int QBP, int NS>
-__global__ __launch_bounds__((SweepCfg<D, QBP, NS>::THREADS)) __attribute__((amdgpu_waves_per_eu(2, 2)))
+template <int D, int QBP, int NS, bool F8 = false>
+__global__ __launch_bounds__((SweepCfg<D, QBP, NS, F8>::THREADS)) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void tree_attn_bf16_kernel(const AttnParams p)
 {
-    using C = SweepCfg<D, QBP, NS>;
+    using C = SweepCfg<D, QBP, NS, F8>;
     __shared__ __attribute__((aligned(1024))) unsigned char ring[C::LDS_BYTES];
 
     // Workgroup ids are dealt round-robin to the 8 XCDs: renumber so that the key splits of one (sequence, head),
@@ -404,9 +465,11 @@ void tree_attn_bf16_kernel(const AttnParams p)
     const __bf16 *q = (const __bf16 *)p.q + bh_q * p.node_stride * D;
     const __bf16 *kt = (const __bf16 *)p.kt + bh_kv * p.node_stride * D;
     const __bf16 *vt = (const __bf16 *)p.vt + bh_kv * p.node_stride * D;
-    const int64_t pre0 = p.seq_base[b] + (int64_t)kvh * p.head_stride;
-    const unsigned char *kp = (const unsigned char *)((const __bf16 *)p.kp + pre0);
-    const unsigned char *vp = (const unsigned char *)((const __bf16 *)p.vp + pre0);
+    const int64_t pre0 = p.seq_base[b] + (int64_t)kvh * p.head_stride;     // in elements: 2 bytes each, 1 when fp8
+    const unsigned char *kp = (const unsigned char *)p.kp + pre0 * (F8 ? 1 : 2);
+    const unsigned char *vp = (const unsigned char *)p.vp + pre0 * (F8 ? 1 : 2);
+    // softmax scale of a prefix tile and the factor its V values carry; the tree's own tiles use p.c and 1
+    const float c_pre = F8 ? p.c * p.k_scale : p.c, vs_pre = F8 ? p.v_scale : 1.f;
 
     // query block of this wavefront; mask row of this lane's query (zero for padded rows)
     QBlock<D> qs;
@@ -437,6 +500,13 @@ void tree_attn_bf16_kernel(const AttnParams p)
         const int lchunk = grp * 2 + ((j & 3) >> 1);                   // + 4*cb
         // swz(vrow + 32*u + 16*ks2 + 8*e4) = swz(vrow) ^ (e4 << 1): the e4 part is folded into the compile-time XOR
         la.v = vrow * C::RB + ((lchunk ^ swz<D>(vrow)) * 16) + (j & 1) * 8;
+        la.k8 = la.v8 = 0;
+        if constexpr (F8) {
+            la.k8 = krow * C::RBP + swz8(krow) * 16 + g * 8;
+            const int e = j >> 1;                                        // key slot this lane addresses
+            const int row8 = kg * C::KPW * 32 + 8 * (e >> 2) + 4 * g + (e & 3);
+            la.v8 = row8 * C::RBP + ((grp ^ swz8(row8)) * 16) + (j & 1) * 8;
+        }
     }
     uint32_t all_keys[C::KPW];
 #pragma unroll
@@ -450,7 +520,7 @@ void tree_attn_bf16_kernel(const AttnParams p)
         for (int i = 0; i < C::NI; ++i) {
             const int G = i * C::WAVES + wave;
             const int r = G * C::RPI + lane / C::CPR;
-            goff[i] = (uint32_t)(r * C::RB + (((lane % C::CPR) ^ swz<D>(r)) * 16));
+            goff[i] = (uint32_t)(r * C::RBP + (((lane % C::CPR) ^ (F8 ? swz8(r) : swz<D>(r))) * 16));
         }
         const unsigned char *ksrc = kp + (int64_t)t0 * C::TILE_K;
         const unsigned char *vsrc = vp + (int64_t)t0 * C::TILE_K;
@@ -478,6 +548,7 @@ void tree_attn_bf16_kernel(const AttnParams p)
             for (int i = 0; i < C::DPT; ++i) issue_load(i, stage);
             advance();
         };
+        if constexpr (!F8) {
         auto step = [&](int it, auto stage, auto prefetching) {
             constexpr int ST = decltype(stage)::value;
             constexpr bool PF = decltype(prefetching)::value;    // a later tile is fetched into the stage just freed
@@ -486,9 +557,9 @@ void tree_attn_bf16_kernel(const AttnParams p)
             __builtin_amdgcn_s_barrier();                     // ... and everyone's; the stage of tile it-1 is free again
             // (spreading these loads over the tile's MFMAs instead of issuing them in one burst was measured: no gain)
             if (PF) issue_tile(std::integral_constant<int, (ST + NS - 1) % NS>());
-            attn_tile<D, QBP, NS, 0>(ring + ST * C::TILE, la, qs, p.c, g, all_keys);
+            attn_tile<D, QBP, NS, 0, false, false>(ring + ST * C::TILE, la, qs, p.c, g, all_keys);
         };
-        static_assert(NS == 2, "the step sequence below is written for a double buffer");
+        static_assert(F8 || NS == 2, "the step sequence below is written for a double buffer");
         using S0 = std::integral_constant<int, 0>;
         using S1 = std::integral_constant<int, 1>;
         issue_tile(S0());
@@ -504,6 +575,32 @@ void tree_attn_bf16_kernel(const AttnParams p)
         } else {
             step(it, S0(), std::false_type());
         }
+        } else {
+        // fp8 tiles are half the bytes: a ring of NS stages keeps NS-1 tiles in flight.  Tile t lives in stage
+        // t % NS.  A step waits until at most NS-2 later tiles are outstanding while such tiles are still being
+        // requested, and for everything once the requests have run out (the last NS-1 tiles).
+        auto step = [&](auto stage, bool more) {
+            constexpr int ST = decltype(stage)::value;
+            if (more) MCSD_WAIT_VMCNT((NS - 2) * C::DPT); else MCSD_WAIT_VMCNT(0);
+            __builtin_amdgcn_s_barrier();
+            if (more) issue_tile(std::integral_constant<int, (ST + NS - 1) % NS>());
+            attn_tile<D, QBP, NS, 0, true, true>(ring + ST * C::TILE, la, qs, c_pre, g, all_keys, vs_pre);
+        };
+        static_assert(!F8 || NS == 4, "the step sequence below is unrolled for four stages");
+        // Q and the mask row must have arrived before the first direct-to-LDS load is issued: the steps below wait
+        // with a non-zero count, and the compiler, which does not see those loads, would otherwise place its own
+        // wait for Q at the first MFMA inside the loop, where it would also wait for the tiles in flight.
+        MCSD_WAIT_VMCNT(0);
+        if (0 < n_hot) issue_tile(std::integral_constant<int, 0>());
+        if (1 < n_hot) issue_tile(std::integral_constant<int, 1 % NS>());
+        if (2 < n_hot) issue_tile(std::integral_constant<int, 2 % NS>());
+        for (int it = 0; it < n_hot; it += 4) {
+            step(std::integral_constant<int, 0>(), it + 3 < n_hot);
+            if (it + 1 < n_hot) step(std::integral_constant<int, 1 % NS>(), it + 4 < n_hot);
+            if (it + 2 < n_hot) step(std::integral_constant<int, 2 % NS>(), it + 5 < n_hot);
+            if (it + 3 < n_hot) step(std::integral_constant<int, 3 % NS>(), it + 6 < n_hot);
+        }
+        }
         MCSD_WAIT_VMCNT(0);
     }
     __syncthreads();
@@ -513,29 +610,36 @@ void tree_attn_bf16_kernel(const AttnParams p)
     for (int it = 0; it < n_rest; ++it) {
         const bool tail = it < n_pre - n_hot;
         const int tt = tail ? 0 : it - (n_pre - n_hot);
-        const unsigned char *ksrc = tail ? kp + (int64_t)(t1 - 1) * C::TILE_K : (const unsigned char *)kt + (int64_t)tt * C::TILE_K;
-        const unsigned char *vsrc = tail ? vp + (int64_t)(t1 - 1) * C::TILE_K : (const unsigned char *)vt + (int64_t)tt * C::TILE_K;
+        const unsigned char *ksrc = tail ? kp + (int64_t)(t1 - 1) * C::TILE_K : (const unsigned char *)kt + (int64_t)tt * C::BTILE_K;
+        const unsigned char *vsrc = tail ? vp + (int64_t)(t1 - 1) * C::TILE_K : (const unsigned char *)vt + (int64_t)tt * C::BTILE_K;
         const int valid = tail ? L - (t1 - 1) * C::T : min(C::T, p.n - tt * C::T);
 #pragma unroll
         for (int i0 = 0; i0 < C::CPT; i0 += 4) {           // four chunks of K and V at a time keeps the staging small
             uint4 kreg[4], vreg[4];
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                const int x = (i0 + i) * C::THREADS + tid, row = x / C::CPR, ch = x % C::CPR;
+                const int x = (i0 + i) * C::THREADS + tid, row = x / C::BCPR, ch = x % C::BCPR;
                 kreg[i] = make_uint4(0, 0, 0, 0);
                 vreg[i] = make_uint4(0, 0, 0, 0);
                 if (i0 + i < C::CPT && row < valid) {
-                    kreg[i] = *(const uint4 *)(ksrc + row * C::RB + ch * 16);
-                    vreg[i] = *(const uint4 *)(vsrc + row * C::RB + ch * 16);
+                    if (F8 && tail) {                      // 8 fp8 values become this 16-byte bf16 chunk
+                        const uint2 k8 = *(const uint2 *)(ksrc + row * C::RBP + ch * 8);
+                        const uint2 v8 = *(const uint2 *)(vsrc + row * C::RBP + ch * 8);
+                        kreg[i] = __builtin_bit_cast(uint4, fp8x8_to_bf16(k8.x, k8.y));
+                        vreg[i] = __builtin_bit_cast(uint4, fp8x8_to_bf16(v8.x, v8.y));
+                    } else {
+                        kreg[i] = *(const uint4 *)(ksrc + row * C::RB + ch * 16);
+                        vreg[i] = *(const uint4 *)(vsrc + row * C::RB + ch * 16);
+                    }
                 }
             }
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                const int x = (i0 + i) * C::THREADS + tid, row = x / C::CPR, ch = x % C::CPR;
+                const int x = (i0 + i) * C::THREADS + tid, row = x / C::BCPR, ch = x % C::BCPR;
                 const int off = row * C::RB + ((ch ^ swz<D>(row)) * 16);
                 if (i0 + i < C::CPT) {
                     *(uint4 *)(ring + off) = kreg[i];
-                    *(uint4 *)(ring + C::TILE_K + off) = vreg[i];
+                    *(uint4 *)(ring + C::BTILE_K + off) = vreg[i];
                 }
             }
         }
@@ -552,7 +656,7 @@ void tree_attn_bf16_kernel(const AttnParams p)
                 bits[u] = (uint32_t)(((col >> 6) ? mrow[1] : mrow[0]) >> (col & 63));
             }
         }
-        attn_tile<D, QBP, NS, 1>(ring, la, qs, p.c, g, bits);
+        attn_tile<D, QBP, NS, 1, F8, false>(ring, la, qs, tail ? c_pre : p.c, g, bits, tail ? vs_pre : 1.f);
         __syncthreads();
     }
 
@@ -578,11 +682,12 @@ void tree_attn_bf16_kernel(const AttnParams p)
         __syncthreads();
     }
     // wavefronts of key group 0 now own one query block each; the others are done
+    const float cm = F8 ? 1.f : p.c;                           // reference maxima are in log2 units already with fp8 tiles
     auto merge_from = [&](const float *src_o, float m_k, float l_k) {
         // (O, m, l) of the same query block from elsewhere, fragments in this lane's register layout
         const float m_new = fmaxf(qs.m_ref, m_k);
         const bool any = m_new != -INFINITY;                  // false: neither side has seen a key
-        const float a = any ? fast_exp2((qs.m_ref - m_new) * p.c) : 1.f, bsc = any ? fast_exp2((m_k - m_new) * p.c) : 0.f;
+        const float a = any ? fast_exp2((qs.m_ref - m_new) * cm) : 1.f, bsc = any ? fast_exp2((m_k - m_new) * cm) : 0.f;
         qs.m_ref = m_new;
         l_tot = l_tot * a + l_k * bsc;
 #pragma unroll
@@ -901,11 +1006,11 @@ size_t workspace_bytes_for(const AttnPlan &pl, int dtype, int B, int d, int n)
     return 2 * align256(rows * sizeof(float)) + align256(rows * d * sizeof(float));
 }
 
-template <int D, int QBP, int NS>
+template <int D, int QBP, int NS, bool F8 = false>
 void launch_sweep(const AttnParams &p, const AttnPlan &pl, hipStream_t st)
 {
     const dim3 grid((unsigned)((size_t)pl.G * p.H * p.B));
-    mcsd_launch(MCSD_KERNEL_ATTN_SWEEP, tree_attn_bf16_kernel<D, QBP, NS>, grid, dim3(SweepCfg<D, QBP, NS>::THREADS), st, p);
+    mcsd_launch(MCSD_KERNEL_ATTN_SWEEP, tree_attn_bf16_kernel<D, QBP, NS, F8>, grid, dim3(SweepCfg<D, QBP, NS, F8>::THREADS), st, p);
 }
 
 template <int D, int QBP>
@@ -926,6 +1031,20 @@ hipError_t launch_bf16(const AttnParams &p, const AttnPlan &pl, hipStream_t st)
     if (pl.QBP == 1) launch_merge<D, 1>(p, pl, st);
     else if (pl.QBP == 2) launch_merge<D, 2>(p, pl, st);
     else launch_merge<D, 4>(p, pl, st);
+    return hipGetLastError();
+}
+
+// fp8 prefix cache (d = 128): four-stage ring; reference maxima reach the fold in log2 units
+hipError_t launch_fp8kv(const AttnParams &p, const AttnPlan &pl, hipStream_t st)
+{
+    if (pl.QBP == 2) launch_sweep<128, 2, 4, true>(p, pl, st);
+    else launch_sweep<128, 4, 4, true>(p, pl, st);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || pl.S == 1) return e;
+    AttnParams pm = p;
+    pm.c = 1.f;
+    if (pl.QBP == 2) launch_merge<128, 2>(pm, pl, st);
+    else launch_merge<128, 4>(pm, pl, st);
     return hipGetLastError();
 }
 
@@ -991,13 +1110,12 @@ extern "C" int mcsd_tree_attention_rows(const mcsd_mask_view_t *mask, mcsd_dtype
                                    workspace, workspace_bytes, hip_stream);
 }
 
-extern "C" int mcsd_tree_attention_gqa(const mcsd_mask_view_t *mask, mcsd_dtype_t dtype, int32_t B, int32_t H_q,
-                                       int32_t H_kv, int32_t d, int32_t row_begin, const void *q, const void *k_tree,
-                                       const void *v_tree, int64_t node_stride, const void *k_prefix,
-                                       const void *v_prefix, const int64_t *seq_base_dev,
-                                       const int32_t *prefix_lens_dev, int64_t head_stride, int32_t max_prefix,
-                                       float softmax_scale, void *out, void *workspace, size_t workspace_bytes,
-                                       void *hip_stream)
+namespace {
+int attention_call(const mcsd_mask_view_t *mask, mcsd_dtype_t dtype, bool f8, float k_scale, float v_scale, int32_t B,
+                   int32_t H_q, int32_t H_kv, int32_t d, int32_t row_begin, const void *q, const void *k_tree,
+                   const void *v_tree, int64_t node_stride, const void *k_prefix, const void *v_prefix,
+                   const int64_t *seq_base_dev, const int32_t *prefix_lens_dev, int64_t head_stride, int32_t max_prefix,
+                   float softmax_scale, void *out, void *workspace, size_t workspace_bytes, void *hip_stream)
 {
     const int32_t H = H_q;
     if (H_kv < 1 || H_q < 1 || H_q % H_kv != 0) return MCSD_EINVAL;
@@ -1012,12 +1130,14 @@ extern "C" int mcsd_tree_attention_gqa(const mcsd_mask_view_t *mask, mcsd_dtype_
     if (!(softmax_scale > 0.f) || !isfinite(softmax_scale)) return MCSD_EINVAL;
     if (d != 64 && d != 128) return MCSD_EUNSUPPORTED;
     if (n > MCSD_ATTN_MAX_NODES) return MCSD_EUNSUPPORTED;
+    if (f8 && (d != 128 || dtype != MCSD_BF16)) return MCSD_EUNSUPPORTED;
+    if (f8 && (!(k_scale > 0.f) || !isfinite(k_scale) || !isfinite(v_scale))) return MCSD_EINVAL;
     const uintptr_t align = (uintptr_t)q | (uintptr_t)k_tree | (uintptr_t)v_tree | (uintptr_t)out |
                             (uintptr_t)k_prefix | (uintptr_t)v_prefix;
     if (align & 15) return MCSD_EINVAL;
-    if (((node_stride * d) & 7) || (head_stride & 7)) return MCSD_EINVAL;
+    if (((node_stride * d) & 7) || (head_stride & (f8 ? 15 : 7))) return MCSD_EINVAL;   // 16-byte rows and heads
 
-    const AttnPlan pl = make_plan(dtype, B, H_q, H_kv, n - row_begin, max_prefix);
+    const AttnPlan pl = make_plan(dtype, B, H_q, H_kv, n - row_begin, max_prefix, f8);
     const size_t need = workspace_bytes_for(pl, dtype, B, d, n);
     if (need > 0 && (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 255))) return MCSD_EWORKSPACE;
 
@@ -1029,6 +1149,8 @@ extern "C" int mcsd_tree_attention_gqa(const mcsd_mask_view_t *mask, mcsd_dtype_
     p.Hq = H_q; p.Hkv = H_kv; p.grp = H_q / H_kv; p.hpw = pl.hpw; p.bph = pl.bph; p.chunks = pl.chunks;
     p.node_stride = node_stride; p.head_stride = head_stride;
     p.c = softmax_scale * 1.4426950408889634f;
+    p.k_scale = f8 ? k_scale : 1.f;
+    p.v_scale = f8 ? v_scale : 1.f;
     p.S = pl.S; p.G = pl.G; p.SP = pl.G;
     p.pair_cus = 0;
     if (dtype == MCSD_BF16 && pl.G == 1 && B <= 64) {
@@ -1057,7 +1179,45 @@ extern "C" int mcsd_tree_attention_gqa(const mcsd_mask_view_t *mask, mcsd_dtype_
     }
     hipStream_t st = (hipStream_t)hip_stream;
     hipError_t e;
-    if (dtype == MCSD_BF16) e = d == 128 ? launch_bf16<128>(p, pl, st) : launch_bf16<64>(p, pl, st);
+    if (f8) e = launch_fp8kv(p, pl, st);
+    else if (dtype == MCSD_BF16) e = d == 128 ? launch_bf16<128>(p, pl, st) : launch_bf16<64>(p, pl, st);
     else e = d == 128 ? launch_f32<128>(p, pl, st) : launch_f32<64>(p, pl, st);
     return mcsd_hip_status(e);
+}
+}  // namespace
+
+extern "C" int mcsd_tree_attention_gqa(const mcsd_mask_view_t *mask, mcsd_dtype_t dtype, int32_t B, int32_t H_q,
+                                       int32_t H_kv, int32_t d, int32_t row_begin, const void *q, const void *k_tree,
+                                       const void *v_tree, int64_t node_stride, const void *k_prefix,
+                                       const void *v_prefix, const int64_t *seq_base_dev,
+                                       const int32_t *prefix_lens_dev, int64_t head_stride, int32_t max_prefix,
+                                       float softmax_scale, void *out, void *workspace, size_t workspace_bytes,
+                                       void *hip_stream)
+{
+    return attention_call(mask, dtype, false, 1.f, 1.f, B, H_q, H_kv, d, row_begin, q, k_tree, v_tree, node_stride,
+                          k_prefix, v_prefix, seq_base_dev, prefix_lens_dev, head_stride, max_prefix, softmax_scale, out,
+                          workspace, workspace_bytes, hip_stream);
+}
+
+extern "C" size_t mcsd_tree_attention_fp8kv_workspace(int32_t B, int32_t H_q, int32_t H_kv, int32_t n_nodes,
+                                                      int32_t row_begin, int32_t max_prefix)
+{
+    if (B < 1 || H_q < 1 || H_kv < 1 || H_q % H_kv != 0 || n_nodes < 1 || n_nodes > MCSD_ATTN_MAX_NODES ||
+        max_prefix < 0 || row_begin < 0 || row_begin >= n_nodes)
+        return 0;
+    const AttnPlan a = make_plan(MCSD_BF16, B, H_q, H_kv, n_nodes - row_begin, max_prefix, true);
+    return workspace_bytes_for(a, MCSD_BF16, B, 128, n_nodes);
+}
+
+extern "C" int mcsd_tree_attention_fp8kv(const mcsd_mask_view_t *mask, int32_t B, int32_t H_q, int32_t H_kv,
+                                         int32_t row_begin, const void *q, const void *k_tree, const void *v_tree,
+                                         int64_t node_stride, const void *k_prefix_fp8, const void *v_prefix_fp8,
+                                         float k_scale, float v_scale, const int64_t *seq_base_dev,
+                                         const int32_t *prefix_lens_dev, int64_t head_stride, int32_t max_prefix,
+                                         float softmax_scale, void *out, void *workspace, size_t workspace_bytes,
+                                         void *hip_stream)
+{
+    return attention_call(mask, MCSD_BF16, true, k_scale, v_scale, B, H_q, H_kv, 128, row_begin, q, k_tree, v_tree,
+                          node_stride, k_prefix_fp8, v_prefix_fp8, seq_base_dev, prefix_lens_dev, head_stride,
+                          max_prefix, softmax_scale, out, workspace, workspace_bytes, hip_stream);
 }

@@ -4,7 +4,8 @@ compiled).  Two properties that correctness or speed depend on and that a compil
     not told; so no compiler-generated instruction may use M0;
   - in the steady-state loop of every sweep instantiation the only waits on the vector-memory counter are the
     kernel's own, one per tile, next to its barrier: an additional compiler-placed wait would make the LDS reads of
-    the tile being computed wait for the loads of the next tile."""
+    the tile being computed wait for the loads of the next tile (bf16 prefix: two-tile loop of a double buffer; fp8
+    prefix: four-tile loop of a four-stage ring)."""
 import os
 import re
 import shutil
@@ -62,11 +63,24 @@ def test_steady_state_loops_wait_for_memory_once_per_tile(sweep_asm):
                 if any("global_load_lds" in x for x in loop) and any("v_mfma" in x for x in loop):
                     loops.append(loop)
         assert loops, f"no streaming loop found in {name}"
-        loop = min(loops, key=len)                                   # the innermost one
-        code = [x.split(";")[0] for x in loop]
-        waits = sum("vmcnt" in x for x in code)
-        barriers = sum("s_barrier" in x for x in code)
-        assert barriers == 2 and waits == 2, f"{name}: {waits} vmcnt waits, {barriers} barriers in the two-tile loop"
+        fp8 = "Lb1EEE" in name                                        # template argument F8 = true
+        if not fp8:
+            loop = min(loops, key=len)                                # the innermost one
+            code = [x.split(";")[0] for x in loop]
+            waits = sum("vmcnt" in x for x in code)
+            barriers = sum("s_barrier" in x for x in code)
+            assert barriers == 2 and waits == 2, f"{name}: {waits} vmcnt waits, {barriers} barriers in the two-tile loop"
+        else:
+            # four-stage ring, four tiles per trip; a step waits either for all loads or for all but the two newest
+            # tiles (two alternative instructions), right before its barrier, and nowhere else
+            loop = max(loops, key=len)
+            code = [x.split(";")[0] for x in loop if x.split(";")[0].strip() and not x.strip().startswith(".")]
+            wait_at = [i for i, x in enumerate(code) if "vmcnt" in x]
+            barrier_at = [i for i, x in enumerate(code) if "s_barrier" in x]
+            assert len(barrier_at) == 4 and len(wait_at) == 8, f"{name}: {len(wait_at)} waits, {len(barrier_at)} barriers"
+            for i in wait_at:
+                assert any(0 < b - i <= 12 for b in barrier_at), f"{name}: a wait on vector memory away from the barriers"
+            assert sorted(set(re.search(r"vmcnt\((\d+)\)", code[i]).group(1) for i in wait_at)) == ["0", "8"]
         assert not any("scratch_" in x for x in code), f"{name}: register spills inside the streaming loop"
         checked += 1
-    assert checked == 6          # head_dim 64 / 128 x 1, 2, 4 query blocks
+    assert checked == 8          # head_dim 64 / 128 x 1, 2, 4 query blocks; fp8 prefix: head_dim 128 x 2, 4 query blocks

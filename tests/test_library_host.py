@@ -22,7 +22,7 @@ def binding():
 def test_every_declared_symbol_is_exported(binding):
     header = open(os.path.join(ROOT, "include", "mcsd.h")).read()
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
-    declared = sorted(set(re.findall(r"\b(mcsd_[a-z_]+)\s*\(", header)))
+    declared = sorted(set(re.findall(r"\b(mcsd_[a-z0-9_]+)\s*\(", header)))
     assert declared == sorted(binding.EXPORTS)
     lib = C.CDLL(binding.LIB_PATH)
     for name in declared:

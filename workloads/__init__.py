@@ -108,6 +108,28 @@ def bf16_bits_to_f32(b: np.ndarray) -> np.ndarray:
     return (b.astype(np.uint32) << np.uint32(16)).view(np.float32)
 
 
+def e4m3_bits_to_f32(b: np.ndarray) -> np.ndarray:
+    """Numbers that 8-bit E4M3 codes stand for (OCP format: bias 7, no infinities, S.1111.111 = NaN)."""
+    b = np.asarray(b, dtype=np.uint8).astype(np.int32)
+    e, m = (b >> 3) & 15, b & 7
+    mag = np.where(e == 0, m / 8.0 * 2.0 ** -6, (1.0 + m / 8.0) * np.exp2((e - 7).astype(np.float64)))
+    mag = np.where((e == 15) & (m == 7), np.nan, mag)
+    return np.where(b >> 7 == 1, -mag, mag).astype(np.float32)
+
+
+def f32_to_e4m3_bits(x: np.ndarray) -> np.ndarray:
+    """Round fp32 to 8-bit E4M3 (round-to-nearest-even, values beyond +-448 saturate) and return the codes."""
+    x = np.asarray(x, dtype=np.float32)
+    grid = e4m3_bits_to_f32(np.arange(127, dtype=np.uint8)).astype(np.float64)      # 0 .. 448, ascending
+    mids = (grid[:-1] + grid[1:]) / 2.0
+    a = np.abs(x.astype(np.float64))
+    lo = np.searchsorted(mids, a, side="left")                  # a <= mids[lo]: candidates lo (and lo+1 on a tie)
+    tie = (lo < mids.size) & (a == mids[np.minimum(lo, mids.size - 1)])
+    code = np.where(tie & (lo % 2 == 1), lo + 1, lo).astype(np.uint8)
+    code = np.where(np.isnan(x), np.uint8(0x7F), code)
+    return (code | (np.signbit(x).astype(np.uint8) << 7)).astype(np.uint8)
+
+
 def _normal(rng: np.random.Generator, shape, dtype: str, mult: float = 1.0) -> np.ndarray:
     x = rng.standard_normal(shape, dtype=np.float32)
     if mult != 1.0:
@@ -123,7 +145,7 @@ def prefix_lens(w: Workload, seed: int = 0) -> np.ndarray:
 
 def attention_inputs(w: Workload, seed: int = 0, lens: Optional[Sequence[int]] = None,
                      tensor_mult: float = 1.0, kv_capacity: Optional[int] = None,
-                     variant: int = 0) -> dict:
+                     variant: int = 0, kv_fp8: Optional[Tuple[float, float]] = None) -> dict:
     """q / k_tree / v_tree of shape [B][H][Nmax][d] and a prefix KV cache [B][H][cap][d].
 
     Storage is fp32 arrays (dtype "f32") or uint16 arrays holding bfloat16 bit patterns ("bf16").
@@ -131,6 +153,8 @@ def attention_inputs(w: Workload, seed: int = 0, lens: Optional[Sequence[int]] =
     meaningful, the rest is zero.  `seq_base[b]` is the element offset of sequence b in the cache and
     `head_stride` the element distance between heads.  `variant` selects a different random
     stream of the same recipe (distinct KV buffers for the layers of one step).
+    kv_fp8 = (k_scale, v_scale): the prefix cache is stored as 8-bit E4M3 codes (uint8 arrays) of value / scale,
+    from the same random stream as the bf16 cache (dtype must be "bf16"); the tree tensors stay bf16.
     """
     lens_a = prefix_lens(w, seed) if lens is None else np.asarray(lens, dtype=np.int32)
     assert lens_a.shape == (w.B,)
@@ -138,6 +162,9 @@ def attention_inputs(w: Workload, seed: int = 0, lens: Optional[Sequence[int]] =
     cap = int(kv_capacity) if kv_capacity is not None else max(int(lens_a.max()), 1)
     assert cap >= int(lens_a.max())
     store = np.float32 if w.dtype == "f32" else np.uint16
+    if kv_fp8 is not None:
+        assert w.dtype == "bf16"
+        store = np.uint8
     shape_t = (w.B, w.H, nmax, w.d)
     q = _normal(_rng(seed, w.cfg_id, _T_Q, variant), shape_t, w.dtype, tensor_mult)
     kt = _normal(_rng(seed, w.cfg_id, _T_KT, variant), shape_t, w.dtype, tensor_mult)
@@ -147,13 +174,19 @@ def attention_inputs(w: Workload, seed: int = 0, lens: Optional[Sequence[int]] =
     rk, rv = _rng(seed, w.cfg_id, _T_KP, variant), _rng(seed, w.cfg_id, _T_VP, variant)
     for b in range(w.B):
         L = int(lens_a[b])
-        if L:
+        if L and kv_fp8 is None:
             kp[b, :, :L] = _normal(rk, (w.H, L, w.d), w.dtype, tensor_mult)
             vp[b, :, :L] = _normal(rv, (w.H, L, w.d), w.dtype, tensor_mult)
+        elif L:
+            kp[b, :, :L] = f32_to_e4m3_bits(_normal(rk, (w.H, L, w.d), "f32", tensor_mult) / np.float32(kv_fp8[0]))
+            vp[b, :, :L] = f32_to_e4m3_bits(_normal(rv, (w.H, L, w.d), "f32", tensor_mult) / np.float32(kv_fp8[1]))
     head_stride = cap * w.d
     seq_base = (np.arange(w.B, dtype=np.int64) * (w.H * head_stride)).astype(np.int64)
-    return dict(q=q, k_tree=kt, v_tree=vt, k_prefix=kp, v_prefix=vp, lens=lens_a, seq_base=seq_base,
-                head_stride=head_stride, node_stride=nmax, scale=float(1.0 / np.sqrt(w.d)), dtype=w.dtype)
+    out = dict(q=q, k_tree=kt, v_tree=vt, k_prefix=kp, v_prefix=vp, lens=lens_a, seq_base=seq_base,
+               head_stride=head_stride, node_stride=nmax, scale=float(1.0 / np.sqrt(w.d)), dtype=w.dtype)
+    if kv_fp8 is not None:
+        out.update(k_scale=float(np.float32(kv_fp8[0])), v_scale=float(np.float32(kv_fp8[1])))
+    return out
 
 
 def _softmax_rows_f32(logits: np.ndarray) -> np.ndarray:
