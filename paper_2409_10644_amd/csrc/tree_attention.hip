@@ -548,7 +548,7 @@ void tree_attn_bf16_kernel(const AttnParams p)
             for (int i = 0; i < C::DPT; ++i) issue_load(i, stage);
             advance();
         };
-        if constexpr (!F8) {
+        if constexpr (NS == 2) {
         auto step = [&](int it, auto stage, auto prefetching) {
             constexpr int ST = decltype(stage)::value;
             constexpr bool PF = decltype(prefetching)::value;    // a later tile is fetched into the stage just freed
@@ -559,7 +559,7 @@ void tree_attn_bf16_kernel(const AttnParams p)
             if (PF) issue_tile(std::integral_constant<int, (ST + NS - 1) % NS>());
             attn_tile<D, QBP, NS, 0, false, false>(ring + ST * C::TILE, la, qs, p.c, g, all_keys);
         };
-        static_assert(F8 || NS == 2, "the step sequence below is written for a double buffer");
+        static_assert(!F8, "fp8 tiles use the ring below");
         using S0 = std::integral_constant<int, 0>;
         using S1 = std::integral_constant<int, 1>;
         issue_tile(S0());
@@ -576,17 +576,19 @@ void tree_attn_bf16_kernel(const AttnParams p)
             step(it, S0(), std::false_type());
         }
         } else {
-        // fp8 tiles are half the bytes: a ring of NS stages keeps NS-1 tiles in flight.  Tile t lives in stage
-        // t % NS.  A step waits until at most NS-2 later tiles are outstanding while such tiles are still being
+        // A ring of NS stages keeps NS-1 tiles in flight; used for fp8 tiles, which are half the bytes.  (For bf16
+        // tiles it needs all of a compute unit's LDS; measured on the latency-bound launches that have a compute
+        // unit per workgroup anyway, it was slower than the double buffer: 13.2 against 11.8 us.)  Tile t lives in
+        // stage t % NS.  A step waits until at most NS-2 later tiles are outstanding while such tiles are still being
         // requested, and for everything once the requests have run out (the last NS-1 tiles).
         auto step = [&](auto stage, bool more) {
             constexpr int ST = decltype(stage)::value;
             if (more) MCSD_WAIT_VMCNT((NS - 2) * C::DPT); else MCSD_WAIT_VMCNT(0);
             __builtin_amdgcn_s_barrier();
             if (more) issue_tile(std::integral_constant<int, (ST + NS - 1) % NS>());
-            attn_tile<D, QBP, NS, 0, true, true>(ring + ST * C::TILE, la, qs, c_pre, g, all_keys, vs_pre);
+            attn_tile<D, QBP, NS, 0, F8, F8>(ring + ST * C::TILE, la, qs, c_pre, g, all_keys, vs_pre);
         };
-        static_assert(!F8 || NS == 4, "the step sequence below is unrolled for four stages");
+        static_assert(NS == 4, "the step sequence below is unrolled for four stages");
         // Q and the mask row must have arrived before the first direct-to-LDS load is issued: the steps below wait
         // with a non-zero count, and the compiler, which does not see those loads, would otherwise place its own
         // wait for Q at the first MFMA inside the loop, where it would also wait for the tiles in flight.
@@ -1153,13 +1155,13 @@ int attention_call(const mcsd_mask_view_t *mask, mcsd_dtype_t dtype, bool f8, fl
     p.v_scale = f8 ? v_scale : 1.f;
     p.S = pl.S; p.G = pl.G; p.SP = pl.G;
     p.pair_cus = 0;
+    static int n_cus = 0;                                      // compute units of the current device, asked once
+    if (n_cus == 0) {
+        int dev = 0, v = 0;
+        if (hipGetDevice(&dev) == hipSuccess && hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess)
+            n_cus = v > 0 ? v : -1;
+    }
     if (dtype == MCSD_BF16 && pl.G == 1 && B <= 64) {
-        static int n_cus = 0;                                  // compute units of the current device, asked once
-        if (n_cus == 0) {
-            int dev = 0, v = 0;
-            if (hipGetDevice(&dev) == hipSuccess && hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess)
-                n_cus = v > 0 ? v : -1;
-        }
         if (n_cus > 0 && (long)B * pl.units == 2L * n_cus) p.pair_cus = n_cus;
         if (const char *ov = getenv("MCSD_ATTN_PAIRING")) {  // tuning override: 0 keeps the natural order
             if (atol(ov) == 0) p.pair_cus = 0;
