@@ -28,9 +28,8 @@ N_LAYERS = 32                   # Llama-2-7B
 
 # HBM traffic per launch of the sweep kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (bytes, already
 # scaled by the copy-kernel calibration); filled from the summaries under profiles/.  None = not measured.
-MEASURED_TRAFFIC = {   # profiles/tree_attn_hbm_traffic_pmc.md (sweep kernel: HBM read + written)
-    "cfg2": 21_790_000, "cfg4": 664_670_000, "cfg5": 2_205_450_000,
-}
+MEASURED_TRAFFIC = {"cfg2": 21_770_000, "cfg4": 664_610_000, "cfg5": 2_205_440_000,
+                    "cfg4_fp8kv": 348_140_000, "cfg5_fp8kv": 1_134_400_000}
 
 
 def log(*a):
@@ -516,7 +515,8 @@ def main():
                 extra[name + "_fp8kv"] = {
                     "bound": "hbm", "kernel": "tree_attn_bf16_kernel<fp8 prefix>", "achieved": round(fbytes / (f_avg * 1e-3) / 1e9, 1),
                     "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(fbytes / (f_avg * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
-                    "traffic": None, "algorithmic_bytes_per_launch": int(fbytes), "flops_per_launch": int(fflops),
+                    "traffic": MEASURED_TRAFFIC.get(name + "_fp8kv"), "algorithmic_bytes_per_launch": int(fbytes),
+                    "flops_per_launch": int(fflops),
                     "avg_launch_us": round(f_avg * 1e3, 2), "p10_us": round(f_p10 * 1e3, 2), "p90_us": round(f_p90 * 1e3, 2),
                     "mfma_tflops": round(fflops / (f_avg * 1e-3) / 1e12, 1), "launches_timed": args.extra_reps,
                     "attn_tree_tokens_per_s": round(w8.B * n8 / (f_avg * 1e-3), 1), "verified_vs_oracle": True,
