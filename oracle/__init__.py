@@ -58,6 +58,8 @@ def _load():
                                                            f64, vp, i64, i32, i32, i32, vp]
         L.mcsd_oracle_verify_tree.restype = C.c_int
         L.mcsd_oracle_verify_tree.argtypes = [i32, vp, i32, i32, i32, vp, vp, vp, i64, i64, vp, vp, i32, vp, vp, vp]
+        L.mcsd_oracle_verify_tree_without_replacement.restype = C.c_int
+        L.mcsd_oracle_verify_tree_without_replacement.argtypes = L.mcsd_oracle_verify_tree.argtypes
         L.mcsd_oracle_tree_sum.restype = f64
         L.mcsd_oracle_tree_sum.argtypes = [vp, i64]
         L.mcsd_oracle_tree_sample.restype = i32
@@ -214,8 +216,9 @@ def tree_attention_row_fp8kv(inp: dict, M: np.ndarray, n: int, b: int, h: int, i
 
 
 def verify_tree(mode: int, branching: Sequence[int], tokens: np.ndarray, p: np.ndarray, q: np.ndarray,
-                u_accept: np.ndarray, u_sample: np.ndarray):
-    """Returns (path int32 [B][G] padded with -1, accept_len int32 [B], new_tokens int32 [B][n_new])."""
+                u_accept: np.ndarray, u_sample: np.ndarray, replacement: bool = True):
+    """Returns (path int32 [B][G] padded with -1, accept_len int32 [B], new_tokens int32 [B][n_new]).
+    replacement=False: the siblings of a context were drawn without replacement."""
     b = _branching(branching)
     G = len(b)
     tokens = np.ascontiguousarray(tokens, dtype=np.int32)
@@ -234,9 +237,9 @@ def verify_tree(mode: int, branching: Sequence[int], tokens: np.ndarray, p: np.n
     path = np.zeros((B, G), dtype=np.int32)
     alen = np.zeros(B, dtype=np.int32)
     new = np.zeros((B, n_new), dtype=np.int32)
-    rc = _load().mcsd_oracle_verify_tree(int(mode), _ptr(b), G, B, V, _ptr(tokens), _ptr(p), _ptr(q),
-                                         p.shape[1] * V, q.shape[1] * V, _ptr(ua), _ptr(us), n_new,
-                                         _ptr(path), _ptr(alen), _ptr(new))
+    fn = _load().mcsd_oracle_verify_tree if replacement else _load().mcsd_oracle_verify_tree_without_replacement
+    rc = fn(int(mode), _ptr(b), G, B, V, _ptr(tokens), _ptr(p), _ptr(q), p.shape[1] * V, q.shape[1] * V, _ptr(ua),
+            _ptr(us), n_new, _ptr(path), _ptr(alen), _ptr(new))
     if rc != 0:
         raise ValueError(f"oracle verify_tree failed: {rc}")
     return path, alen, new

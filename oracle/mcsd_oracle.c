@@ -335,7 +335,7 @@ static void children_of(const tree_t *t, int64_t ctx, int32_t ctx_level, int64_t
 static int32_t traverse(const tree_t *t, int64_t start_node, int32_t start_level,
                         int32_t V, int64_t P, const int32_t *tokens,
                         const float *p, const float *q, const float *u_acc,
-                        int32_t *path, double *r, double *term)
+                        int32_t *path, double *r, double *term, int without_replacement, double *qz)
 {
     int64_t cur = start_node;          /* node id of the current context, -1 for the prefix end */
     int32_t cur_level = start_level;   /* level of `cur` (0 for the prefix end) */
@@ -347,16 +347,40 @@ static int32_t traverse(const tree_t *t, int64_t start_node, int32_t start_level
         double S = 1.0;                /* round 0 trusts the target row to be normalised */
         int64_t first; int32_t cnt; int64_t accepted = -1;
         children_of(t, cur, cur_level, &first, &cnt);
-        for (int32_t c = 0; c < cnt; ++c) {
-            const int64_t node = first + c;
-            const int32_t x = tokens[node];
-            const double u = (double)u_acc[node];
-            if (u * ((double)qrow[x] * S) < r[x]) { accepted = node; break; }
-            for (int64_t v = 0; v < V; ++v) {                 /* residual: r <- max(r - S*q, 0) */
-                double d = fma(-S, (double)qrow[v], r[v]);
-                r[v] = d > 0.0 ? d : 0.0;
+        if (!without_replacement) {
+            for (int32_t c = 0; c < cnt; ++c) {
+                const int64_t node = first + c;
+                const int32_t x = tokens[node];
+                const double u = (double)u_acc[node];
+                if (u * ((double)qrow[x] * S) < r[x]) { accepted = node; break; }
+                for (int64_t v = 0; v < V; ++v) {                 /* residual: r <- max(r - S*q, 0) */
+                    double d = fma(-S, (double)qrow[v], r[v]);
+                    r[v] = d > 0.0 ? d : 0.0;
+                }
+                S = tree_sum(r, P);
             }
-            S = tree_sum(r, P);
+        } else {
+            /* Candidates drawn WITHOUT replacement (the siblings of a context are distinct tokens, each drawn from
+             * the draft row with the earlier ones removed): after a rejection the draft row loses the rejected
+             * token as well, q(x) <- 0, q <- norm(q).  Unnormalised: qz is the row with zeros, Sq its sum, kept as
+             * 1 - (mass removed so far) since the row is trusted to be normalised like the target row;
+             *   test   u * (qz(x)/Sq) < r(x)/S      <=>   u * qz(x) * S < r(x) * Sq
+             *   update r <- max(r/S - qz/Sq, 0) * S * Sq = max(r*Sq - S*qz, 0),  then qz(x) <- 0, Sq <- Sq - qz(x). */
+            for (int64_t v = 0; v < V; ++v) qz[v] = (double)qrow[v];
+            double Sq = 1.0;
+            for (int32_t c = 0; c < cnt; ++c) {
+                const int64_t node = first + c;
+                const int32_t x = tokens[node];
+                const double u = (double)u_acc[node];
+                if (u * (qz[x] * S) < r[x] * Sq) { accepted = node; break; }
+                for (int64_t v = 0; v < V; ++v) {
+                    double d = fma(-S, qz[v], r[v] * Sq);
+                    r[v] = d > 0.0 ? d : 0.0;
+                }
+                Sq = Sq - qz[x];
+                qz[x] = 0.0;
+                S = tree_sum(r, P);
+            }
         }
         if (accepted < 0) {
             /* all candidates rejected: new token(s) come from the residual; if the residual vanished
@@ -384,10 +408,9 @@ static int32_t traverse(const tree_t *t, int64_t start_node, int32_t start_level
  * tokens [B][N]; p [b*p_bstride + row*V + v], rows 0..N; q likewise, rows 0..N(G-1);
  * u_acc [B][N] (indexed by node); u_smp [B][n_new]; out_path [B][G] (-1 padded); out_len [B];
  * out_new [B][n_new].  Returns 0, or <0 on invalid arguments. */
-int mcsd_oracle_verify_tree(int32_t mode, const int32_t *branching, int32_t G, int32_t B, int32_t V,
-                            const int32_t *tokens, const float *p, const float *q,
-                            int64_t p_bstride, int64_t q_bstride,
-                            const float *u_acc, const float *u_smp, int32_t n_new,
+static int verify_tree_impl(int32_t mode, int without_replacement, const int32_t *branching, int32_t G, int32_t B,
+                            int32_t V, const int32_t *tokens, const float *p, const float *q, int64_t p_bstride,
+                            int64_t q_bstride, const float *u_acc, const float *u_smp, int32_t n_new,
                             int32_t *out_path, int32_t *out_len, int32_t *out_new)
 {
     tree_t t;
@@ -402,17 +425,18 @@ int mcsd_oracle_verify_tree(int32_t mode, const int32_t *branching, int32_t G, i
         double *best_term = (double *)malloc(sizeof(double) * (size_t)P);
         int32_t *path = (int32_t *)malloc(sizeof(int32_t) * (size_t)(G + 1));
         int32_t *best_path = (int32_t *)malloc(sizeof(int32_t) * (size_t)(G + 1));
-        if (!r || !term || !best_term || !path || !best_path) { rc = -2; goto done; }
+        double *qz = (double *)malloc(sizeof(double) * (size_t)P);
+        if (!r || !term || !best_term || !path || !best_path || !qz) { rc = -2; goto done; }
         const int32_t *tok_b = tokens + (int64_t)b * N;
         const float *p_b = p + (int64_t)b * p_bstride, *q_b = q + (int64_t)b * q_bstride;
         const float *ua_b = u_acc + (int64_t)b * N;
         int32_t best_len = -1;
         if (mode == 0) {
-            best_len = traverse(&t, -1, 0, V, P, tok_b, p_b, q_b, ua_b, best_path, r, best_term);
+            best_len = traverse(&t, -1, 0, V, P, tok_b, p_b, q_b, ua_b, best_path, r, best_term, without_replacement, qz);
         } else {
             for (int32_t i = 0; i < branching[0]; ++i) {
                 path[0] = i;                                   /* accepted by construction */
-                int32_t len = 1 + traverse(&t, i, 1, V, P, tok_b, p_b, q_b, ua_b, path + 1, r, term);
+                int32_t len = 1 + traverse(&t, i, 1, V, P, tok_b, p_b, q_b, ua_b, path + 1, r, term, without_replacement, qz);
                 if (len > best_len) {                          /* strict: lowest id wins ties */
                     best_len = len;
                     memcpy(best_path, path, sizeof(int32_t) * (size_t)len);
@@ -425,9 +449,30 @@ int mcsd_oracle_verify_tree(int32_t mode, const int32_t *branching, int32_t G, i
         for (int32_t k = 0; k < n_new; ++k)
             out_new[(int64_t)b * n_new + k] = tree_sample(best_term, P, V, u_smp[(int64_t)b * n_new + k]);
     done:
-        free(r); free(term); free(best_term); free(path); free(best_path);
+        free(r); free(term); free(best_term); free(path); free(best_path); free(qz);
     }
     return rc;
+}
+
+int mcsd_oracle_verify_tree(int32_t mode, const int32_t *branching, int32_t G, int32_t B, int32_t V,
+                            const int32_t *tokens, const float *p, const float *q,
+                            int64_t p_bstride, int64_t q_bstride,
+                            const float *u_acc, const float *u_smp, int32_t n_new,
+                            int32_t *out_path, int32_t *out_len, int32_t *out_new)
+{
+    return verify_tree_impl(mode, 0, branching, G, B, V, tokens, p, q, p_bstride, q_bstride, u_acc, u_smp, n_new,
+                            out_path, out_len, out_new);
+}
+
+/* The same walk for candidates drawn without replacement (see traverse). */
+int mcsd_oracle_verify_tree_without_replacement(int32_t mode, const int32_t *branching, int32_t G, int32_t B, int32_t V,
+                                                const int32_t *tokens, const float *p, const float *q,
+                                                int64_t p_bstride, int64_t q_bstride, const float *u_acc,
+                                                const float *u_smp, int32_t n_new, int32_t *out_path,
+                                                int32_t *out_len, int32_t *out_new)
+{
+    return verify_tree_impl(mode, 1, branching, G, B, V, tokens, p, q, p_bstride, q_bstride, u_acc, u_smp, n_new,
+                            out_path, out_len, out_new);
 }
 
 /* ------------------------------------------------------------------------------------------------

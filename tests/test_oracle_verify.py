@@ -266,7 +266,7 @@ def test_vanished_residual_falls_back_to_target_row(oracle):
 # ----------------------------------------------------------------------------------------------
 # output law: exact enumeration over token assignments, seeded Monte-Carlo integration over uniforms
 # ----------------------------------------------------------------------------------------------
-def _law_of_first_emitted(oracle, mode, br, p_fn, q_fn, V, M, first_two=False, seed=0):
+def _law_of_first_emitted(oracle, mode, br, p_fn, q_fn, V, M, first_two=False, seed=0, replacement=True):
     """Enumerate every token assignment, weighted by its probability under the generation process, and
     integrate over the uniforms with M seeded random draws per assignment.  Rows are functions of the
     token history, so equal histories have equal distributions.  Returns (law of the first emitted token,
@@ -294,15 +294,26 @@ def _law_of_first_emitted(oracle, mode, br, p_fn, q_fn, V, M, first_two=False, s
         p_rows = np.stack([p_fn(())] + [p_fn(hist[i]) for i in range(N)]).astype(np.float32)
         q_rows = np.stack([q_fn(())] + [q_fn(hist[i]) for i in range(Nin)]).astype(np.float32)
         weight = 1.0
+        gone = {}                                  # without replacement: mass already drawn by earlier siblings
         for i in range(N):
             src = p_fn(()) if (mode == TARGET and parent[i] < 0) else q_fn(hist[i][:-1])
-            weight *= float(np.float32(src[toks[i]]))
+            if replacement:
+                weight *= float(np.float32(src[toks[i]]))
+            else:
+                taken = gone.setdefault(parent[i], [])
+                if toks[i] in taken:
+                    weight = 0.0
+                    break
+                left = 1.0 - sum(float(np.float32(src[t])) for t in taken)
+                weight *= float(np.float32(src[toks[i]])) / left if left > 0 else 0.0
+                taken.append(toks[i])
         if weight == 0.0:
             continue
         ua = rng.random((M, N), dtype=np.float32)
         us = rng.random((M, n_new), dtype=np.float32)
         path, alen, new = oracle.verify_tree(mode, br, np.tile(np.int32(toks), (M, 1)),
-                                             np.tile(p_rows, (M, 1, 1)), np.tile(q_rows, (M, 1, 1)), ua, us)
+                                             np.tile(p_rows, (M, 1, 1)), np.tile(q_rows, (M, 1, 1)), ua, us,
+                                             replacement=replacement)
         tok_arr = np.int32(toks)
         first = np.where(alen > 0, tok_arr[np.maximum(path[:, 0], 0)], new[:, 0])
         np.add.at(law1, first, weight / M)
@@ -463,3 +474,109 @@ def test_one_hot_target_rows_reduce_to_arg_max_matching(oracle):
         assert alen[b] == len(want) and path[b, :len(want)].tolist() == want
         assert new[b, 0] == top[b, 1 + cur]
     assert len(set(alen.tolist())) >= 3
+
+
+# ----------------------------------------------------------------------------------------------
+# candidates drawn without replacement (a variant next to the paper's setting; the rule is the one of
+# multi-candidate speculative sampling: after a rejection the draft row also loses the rejected token)
+# ----------------------------------------------------------------------------------------------
+def _textbook_walk_distinct(br, start, start_lvl, tokens, p, q, ua):
+    """The normalised rule in exact fractions: accept with probability min(1, p(x)/q(x)); after a rejection
+    p <- norm(max(p - q, 0)), q(x) <- 0, q <- norm(q)."""
+    cur, lvl, path = start, start_lvl, []
+    while lvl < len(br):
+        dist, qq = list(p[cur + 1]), list(q[cur + 1])
+        acc = None
+        for c in _children(br, cur, lvl):
+            x = tokens[c]
+            assert qq[x] > 0                            # valid input: a token the current draft row can produce
+            if ua[c] < min(Fraction(1), dist[x] / qq[x]):
+                acc = c
+                break
+            res = [max(a - b, Fraction(0)) for a, b in zip(dist, qq)]
+            tot = sum(res)
+            assert tot > 0
+            dist = [r / tot for r in res]
+            qq[x] = Fraction(0)
+            left = sum(qq)
+            qq = [v / left for v in qq]
+        if acc is None:
+            return path, dist
+        path.append(acc)
+        cur, lvl = acc, lvl + 1
+    return path, list(p[cur + 1])
+
+
+@pytest.mark.parametrize("mode", [DRAFT, TARGET])
+@pytest.mark.parametrize("br", [(2, 2), (3, 2, 1), (2, 1, 3), (4,)])
+def test_without_replacement_exact_agreement_with_rational_textbook_rule(oracle, mode, br):
+    rng = np.random.default_rng(hash((7, mode) + tuple(br)) % (2 ** 32))
+    V, G = 8, len(br)
+    sizes = np.cumprod(br)
+    N, Nin = int(sizes.sum()), int(sizes[:-1].sum())
+    B, n_new = 300, 2
+    p = np.stack([_dyadic_rows(rng, 1 + N, V, 64) for _ in range(B)])
+    # draft rows with full support: 1/32 everywhere plus dyadic extra mass (so distinct siblings always exist)
+    q = np.stack([(_dyadic_rows(rng, 1 + Nin, V, 24) * 24 + 1) / 32 for _ in range(B)]).astype(np.float32)
+    assert np.all(q.sum(axis=-1) == 1.0)
+    tokens = np.empty((B, N), dtype=np.int32)
+    off = np.concatenate([[0], np.cumsum(sizes)])
+    for b in range(B):                                       # distinct tokens inside every sibling group
+        for l, bf in enumerate(br):
+            for grp in range(sizes[l] // bf):
+                tokens[b, off[l] + grp * bf: off[l] + (grp + 1) * bf] = rng.permutation(V)[:bf]
+    ua = (rng.integers(0, 256, size=(B, N)) / 256).astype(np.float32)
+    us = (rng.integers(0, 4096, size=(B, n_new)) / 4096).astype(np.float32)
+    path, alen, new = oracle.verify_tree(mode, br, tokens, p, q, ua, us, replacement=False)
+    lens_seen, differs = set(), 0
+    with_rep = oracle.verify_tree(mode, br, tokens, p, q, ua, us)
+    for b in range(B):
+        pf = [[Fraction(float(x)) for x in row] for row in p[b]]
+        qf = [[Fraction(float(x)) for x in row] for row in q[b]]
+        uaf = [Fraction(float(x)) for x in ua[b]]
+        if mode == DRAFT:
+            want_path, term = _textbook_walk_distinct(br, -1, 0, tokens[b].tolist(), pf, qf, uaf)
+        else:
+            best = None
+            for i in range(br[0]):
+                pth, term_i = _textbook_walk_distinct(br, i, 1, tokens[b].tolist(), pf, qf, uaf)
+                if best is None or 1 + len(pth) > len(best[0]):
+                    best = ([i] + pth, term_i)
+            want_path, term = best
+        want_new = [_linear_cdf_sample(term, Fraction(float(u))) for u in us[b]]
+        assert alen[b] == len(want_path) and path[b, :alen[b]].tolist() == want_path
+        assert new[b].tolist() == want_new
+        lens_seen.add(int(alen[b]))
+        differs += int(alen[b] != with_rep[1][b] or new[b].tolist() != with_rep[2][b].tolist())
+    if not (mode == TARGET and G == 1):
+        assert len(lens_seen) >= 2
+    if max((br[1:] if mode == TARGET else br) + (1,)) > 1:
+        assert differs > 0          # the two rules are not the same rule on these inputs
+
+
+@pytest.mark.parametrize("br", [(2,), (3,), (2, 2)])
+def test_without_replacement_first_token_law_is_the_target_law(oracle, br):
+    """Losslessness of the without-replacement rule: distinct siblings drawn one after the other from the
+    renormalised draft row, verified with the draft row shrinking after every rejection."""
+    V = 3
+    p_fn, q_fn = _rows_by_history(V, 41), _rows_by_history(V, 42)
+    N = int(np.cumprod(br).sum())
+    M = {2: 300000, 3: 150000}.get(N, 6000)
+    law, _, tol = _law_of_first_emitted(oracle, DRAFT, br, p_fn, q_fn, V, M, replacement=False)
+    target = p_fn(()).astype(np.float64)
+    assert tol < 5e-3
+    assert abs(law.sum() - 1.0) < 1e-5
+    assert np.max(np.abs(law - target / target.sum())) < tol
+
+
+def test_without_replacement_is_the_same_rule_for_single_candidates(oracle):
+    """No siblings, nothing to remove: a chain gives identical results under both rules."""
+    rng = np.random.default_rng(3)
+    br, V, B = (1, 1, 1, 1), 50, 200
+    p = rng.random((B, 5, V)).astype(np.float32); p /= p.sum(-1, keepdims=True)
+    q = rng.random((B, 4, V)).astype(np.float32); q /= q.sum(-1, keepdims=True)
+    tokens = rng.integers(0, V, size=(B, 4)).astype(np.int32)
+    ua, us = rng.random((B, 4), dtype=np.float32), rng.random((B, 1), dtype=np.float32)
+    a = oracle.verify_tree(DRAFT, br, tokens, p, q, ua, us)
+    b = oracle.verify_tree(DRAFT, br, tokens, p, q, ua, us, replacement=False)
+    assert all(np.array_equal(x, y) for x, y in zip(a, b))

@@ -203,8 +203,23 @@ def _draw(rng: np.random.Generator, probs_row: np.ndarray, count: int) -> np.nda
     return np.minimum(np.searchsorted(cdf, u, side="right"), probs_row.size - 1).astype(np.int32)
 
 
+def _draw_distinct(rng: np.random.Generator, probs_row: np.ndarray, count: int) -> np.ndarray:
+    """`count` token ids drawn one after the other, each from the row with the earlier ones removed."""
+    w = probs_row.astype(np.float64).copy()
+    out = np.empty(count, dtype=np.int32)
+    for i in range(count):
+        if not (w > 0).any():                    # fewer tokens with mass than candidates: repeat the last one
+            out[i] = out[i - 1] if i else 0
+            continue
+        out[i] = _draw(rng, w, 1)[0]
+        while w[out[i]] == 0.0:                  # the inversion's last-bit landing on an emptied slot
+            out[i] = _draw(rng, w, 1)[0]
+        w[out[i]] = 0.0
+    return out
+
+
 def verify_inputs(w: Workload, seed: int = 0, gamma: Optional[int] = None, mode: Optional[int] = None,
-                  n_new: Optional[int] = None) -> dict:
+                  n_new: Optional[int] = None, replacement: bool = True) -> dict:
     """Target / draft next-token distributions, tree tokens and uniforms for one verification call.
 
     p_target: fp32 [B][1+N][V]   (row 0: the context that ends the prefix; row 1+i: after tree node i)
@@ -213,6 +228,7 @@ def verify_inputs(w: Workload, seed: int = 0, gamma: Optional[int] = None, mode:
                                  target-initialised mode the level-1 tokens are draws from p_target[0]
     u_accept: fp32 [B][N] in [0,1);  u_sample: fp32 [B][n_new] in [0,1)
     Nodes are numbered level by level, children of one parent next to each other.
+    replacement=False: the children of a context are distinct tokens (drawn without replacement).
     """
     g = w.gamma_max if gamma is None else int(gamma)
     md = w.mode if mode is None else int(mode)
@@ -243,7 +259,7 @@ def verify_inputs(w: Workload, seed: int = 0, gamma: Optional[int] = None, mode:
             for par in level_nodes:
                 ctx = 1 + par         # row of the context whose children are drawn
                 row = p[b, 0] if (md == TARGET_INIT and lv == 0) else q[b, ctx]
-                tokens[b, nxt:nxt + bf] = _draw(rt, row, bf)
+                tokens[b, nxt:nxt + bf] = _draw(rt, row, bf) if replacement else _draw_distinct(rt, row, bf)
                 new_nodes.extend(range(nxt, nxt + bf))
                 nxt += bf
             level_nodes = new_nodes
