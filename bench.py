@@ -350,6 +350,31 @@ def main():
         out["verify_roofline"] = {"bound": "hbm", "kernel": "verify_walk_kernel", "achieved": round(vb / (v_avg * 1e-3) / 1e9, 2),
                                   "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(vb / (v_avg * 1e-3) / 1e9 / HBM_PEAK_GBPS, 6),
                                   "algorithmic_bytes_per_launch": int(vb), "avg_launch_us": round(v_avg * 1e3, 2)}
+    # the same verification for candidates drawn without replacement (a scheme next to the paper's), same shapes
+    try:
+        import numpy as np
+        import oracle
+        from workloads import verify_inputs
+        vi2 = verify_inputs(w, seed=0, gamma=st.gamma, mode=st.mode, replacement=False)
+        d2 = [st.H.dev(vi2[k]) for k in ("tokens", "p_target", "q_draft", "u_accept", "u_sample")]
+        o2 = [torch.zeros_like(st.path), torch.zeros_like(st.alen), torch.zeros_like(st.new)]
+
+        def v2call(i):
+            binding.verify_tree_sampling(st.view, st.mode, binding.MCSD_WITHOUT_REPLACEMENT, w.B, w.V, d2[0], d2[1], d2[2],
+                                         vi2["p_target"].shape[1] * w.V, vi2["q_draft"].shape[1] * w.V, d2[3], d2[4],
+                                         st.n_new, o2[0], o2[1], o2[2], st.vws)
+        v2call(0)
+        torch.cuda.synchronize()
+        want2 = oracle.verify_tree(st.mode, w.branching[:st.gamma], vi2["tokens"], vi2["p_target"], vi2["q_draft"],
+                                   vi2["u_accept"], vi2["u_sample"], replacement=False)
+        got2 = (o2[0].cpu().numpy(), o2[1].cpu().numpy(), o2[2].cpu().numpy()[:, :st.n_new])
+        assert all(np.array_equal(a, b) for a, b in zip(got2, want2)), "without-replacement verification differs from the oracle"
+        v2_avg = time_kernel(st, hip, binding.KERNEL_VERIFY_WALK, v2call, args.kernel_reps)[0]
+        out["kernels_us"]["verify_walk_without_replacement"] = round(v2_avg * 1e3, 2)
+        out["verify_without_replacement"] = {"avg_launch_us": round(v2_avg * 1e3, 2), "verified_vs_oracle": True,
+                                             "mean_accept_len": round(float(want2[1].mean()), 3)}
+    except Exception as ex:
+        out["verify_without_replacement"] = {"error": repr(ex)}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(st)
     # the draft side of the loop: attention for the newest level only, a fresh slice of the mask per level

@@ -215,6 +215,22 @@ int mcsd_verify_tree(const mcsd_mask_view_t *mask, mcsd_mode_t mode, int32_t B, 
                      const float *u_sample, int32_t n_new, int32_t *out_path, int32_t *out_accept_len,
                      int32_t *out_new_tokens, void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/* The same walk with the sampling scheme of the candidates stated (Sec. 2.2 leaves it open; mcsd_verify_tree is
+ * MCSD_WITH_REPLACEMENT).  MCSD_WITHOUT_REPLACEMENT: the children of a context are distinct tokens, each drawn from
+ * the draft row with the earlier ones removed; after a rejection the draft row therefore loses the rejected token as
+ * well (q(x) <- 0, q <- norm(q)) before the next child is tested.  In the unnormalised arithmetic above, with q' the
+ * draft row with zeros and Sq = 1 - (draft mass removed so far, subtracted in child order):
+ *   test  u_accept[c] * q'(x) * S < r(x) * Sq,     update  r <- max(r * Sq - S * q', 0), then q'(x) <- 0.
+ * For a chain (one child per context) both schemes are the same rule.  Arguments and errors as mcsd_verify_tree;
+ * MCSD_EINVAL for an unknown scheme. */
+typedef enum { MCSD_WITH_REPLACEMENT = 0, MCSD_WITHOUT_REPLACEMENT = 1 } mcsd_sampling_t;
+
+int mcsd_verify_tree_sampling(const mcsd_mask_view_t *mask, mcsd_mode_t mode, mcsd_sampling_t sampling, int32_t B,
+                              int32_t V, const int32_t *tokens, const float *p_target, const float *q_draft,
+                              int64_t p_batch_stride, int64_t q_batch_stride, const float *u_accept,
+                              const float *u_sample, int32_t n_new, int32_t *out_path, int32_t *out_accept_len,
+                              int32_t *out_new_tokens, void *workspace, size_t workspace_bytes, void *hip_stream);
+
 /* ---------------------------------------------------------------------------------------------------
  * Update after acceptance (Fig. 1 step 6): the accepted path becomes part of the prefix.
  *

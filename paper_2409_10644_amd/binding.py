@@ -13,13 +13,14 @@ LIB_PATH = os.path.join(_HERE, "libmcsd.so")
 MCSD_OK, MCSD_EINVAL, MCSD_ENOMEM, MCSD_EHIP, MCSD_EWORKSPACE, MCSD_EUNSUPPORTED = 0, -1, -2, -3, -4, -5
 MCSD_F32, MCSD_BF16 = 0, 1
 MCSD_DRAFT_INIT, MCSD_TARGET_INIT = 0, 1
+MCSD_WITH_REPLACEMENT, MCSD_WITHOUT_REPLACEMENT = 0, 1
 
 EXPORTS = ["mcsd_strerror", "mcsd_build_mask", "mcsd_slice_mask", "mcsd_free_mask",
            "mcsd_tree_attention_workspace", "mcsd_tree_attention",
            "mcsd_tree_attention_rows_workspace", "mcsd_tree_attention_rows",
            "mcsd_tree_attention_gqa_workspace", "mcsd_tree_attention_gqa",
            "mcsd_tree_attention_fp8kv_workspace", "mcsd_tree_attention_fp8kv",
-           "mcsd_verify_tree_workspace", "mcsd_verify_tree", "mcsd_commit_path", "mcsd_early_stop_distribution",
+           "mcsd_verify_tree_workspace", "mcsd_verify_tree", "mcsd_verify_tree_sampling", "mcsd_commit_path", "mcsd_early_stop_distribution",
            "mcsd_early_stop_hidden", "mcsd_profile_next", "mcsd_stream_read"]
 DECISION_MAX_K, MLP_MAX_LAYERS, MLP_MAX_WIDTH, MLP_MAX_INPUTS = 16, 3, 512, 8192
 
@@ -75,6 +76,9 @@ def _load() -> C.CDLL:
     lib.mcsd_verify_tree.restype = C.c_int
     lib.mcsd_verify_tree.argtypes = [C.POINTER(MaskView), C.c_int, i32, i32, vp, vp, vp, i64, i64, vp, vp, i32,
                                      vp, vp, vp, vp, sz, vp]
+    lib.mcsd_verify_tree_sampling.restype = C.c_int
+    lib.mcsd_verify_tree_sampling.argtypes = [C.POINTER(MaskView), C.c_int, C.c_int, i32, i32, vp, vp, vp, i64, i64, vp,
+                                              vp, i32, vp, vp, vp, vp, sz, vp]
     lib.mcsd_profile_next.restype = C.c_int
     lib.mcsd_tree_attention_rows_workspace.restype = C.c_size_t
     lib.mcsd_tree_attention_rows_workspace.argtypes = [i32, i32, i32, i32, i32, i32]
@@ -252,6 +256,19 @@ def verify_tree(view: MaskView, mode: int, B: int, V: int, tokens: torch.Tensor,
                               q_batch_stride, _ptr(u_accept), _ptr(u_sample), n_new, _ptr(out_path),
                               _ptr(out_accept_len), _ptr(out_new_tokens), _ptr(workspace), ws_bytes, _stream(stream))
     _check(st, "mcsd_verify_tree")
+
+
+def verify_tree_sampling(view: MaskView, mode: int, sampling: int, B: int, V: int, tokens: torch.Tensor,
+                         p_target: torch.Tensor, q_draft: Optional[torch.Tensor], p_batch_stride: int,
+                         q_batch_stride: int, u_accept: torch.Tensor, u_sample: Optional[torch.Tensor], n_new: int,
+                         out_path: torch.Tensor, out_accept_len: torch.Tensor, out_new_tokens: Optional[torch.Tensor],
+                         workspace: Optional[torch.Tensor], stream=None) -> None:
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    st = lib.mcsd_verify_tree_sampling(C.byref(view), mode, sampling, B, V, _ptr(tokens), _ptr(p_target), _ptr(q_draft),
+                                       p_batch_stride, q_batch_stride, _ptr(u_accept), _ptr(u_sample), n_new,
+                                       _ptr(out_path), _ptr(out_accept_len), _ptr(out_new_tokens), _ptr(workspace),
+                                       ws_bytes, _stream(stream))
+    _check(st, "mcsd_verify_tree_sampling")
 
 
 def _ptr_array(tensors: Sequence[torch.Tensor]):

@@ -41,6 +41,8 @@ struct SharedT {
     double heapB[2 * NBMAX];             // heap over the blocks: leaves at [NB, 2NB), root at 1 (built for the descent only)
     double heapA[2 * BLK];               // heap inside one block, rebuilt for each descent
     double s_hist[MCSD_MAX_BRANCH + 1];  // S before each rejection round of the current context
+    double sq_hist[MCSD_MAX_BRANCH + 1]; // candidates without replacement: sum of the shrunken draft row before each round
+    int x_hist[MCSD_MAX_BRANCH + 1];     // ... and the token rejected in that round (its draft mass is zero afterwards)
     float qrow[QROW];                    // register-resident path: the context's draft row, in the lanes' own order
     int lo_idx, hi_idx;
 };
@@ -52,19 +54,29 @@ constexpr int FAST_NB = GROUP * (VT / 64);   // up to this many blocks a context
 // (zeros only enter sums, products and comparisons with 0), so this equals "d > 0 ? d : 0" for every use below.
 __device__ inline double pos_part(double d) { return __builtin_fmax(d, 0.0); }
 
-// Element t of the distribution after `rounds` rejections at a context with rows prow / qrow.
-__device__ inline double residual_at(const float *prow, const float *qrow, const double *s_hist, int rounds,
-                                     int t)
+// One element of the distribution after `rounds` rejections, from its target value r and draft value qd.
+// With replacement: r <- max(r - S q, 0) per round.  NOREP (candidates drawn without replacement): the draft row
+// loses every rejected token, and with Sq the sum of what is left, r <- max(r Sq - S q', 0).
+template <bool NOREP, class Shared>
+__device__ inline double residual_chain(const Shared &sh, double r, double qd, int t, int rounds)
 {
-    double r = (double)prow[t];
-    if (rounds > 0) {
-        const double qv = (double)qrow[t];
-        for (int k = 0; k < rounds; ++k) {
-            const double d = __fma_rn(-s_hist[k], qv, r);
-            r = pos_part(d);
+    for (int k = 0; k < rounds; ++k) {
+        if (NOREP) {
+            if (k > 0 && t == sh.x_hist[k - 1]) qd = 0.0;
+            r = __dmul_rn(r, sh.sq_hist[k]);
         }
+        const double d = __fma_rn(-sh.s_hist[k], qd, r);
+        r = pos_part(d);
     }
     return r;
+}
+
+// Element t of the distribution after `rounds` rejections at a context with rows prow / qrow.
+template <bool NOREP, class Shared>
+__device__ inline double residual_at(const Shared &sh, const float *prow, const float *qrow, int rounds, int t)
+{
+    const double r = (double)prow[t];
+    return rounds > 0 ? residual_chain<NOREP>(sh, r, (double)qrow[t], t, rounds) : r;
 }
 
 // A double from another lane of the row through the data-parallel-primitive path of the vector ALU (no LDS).
@@ -186,7 +198,7 @@ __device__ inline void store_block_sums(Shared &sh, const VerifyParams &P, const
 // Block sums of the distribution (prow, qrow, rounds) recomputed from memory into leaf[buf]; any NB.  No barrier
 // at the end; s_hist[0 .. rounds) must be visible.
 constexpr int SGROUP = 8;                // blocks a wavefront streams at a time
-template <class Shared>
+template <bool NOREP, class Shared>
 __device__ void stream_block_sums(Shared &sh, const VerifyParams &P, const float *prow, const float *qrow,
                                   int rounds, int buf)
 {
@@ -223,15 +235,9 @@ __device__ void stream_block_sums(Shared &sh, const VerifyParams &P, const float
         for (int k = 0; k < SGROUP; ++k) {
             double v[4];
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                double r = (double)pe[k][e];                 // elements beyond V are 0 and stay 0
-                const double qd = (double)qe[k][e];
-                for (int j = 0; j < rounds; ++j) {
-                    const double d = __fma_rn(-sh.s_hist[j], qd, r);
-                    r = pos_part(d);
-                }
-                v[e] = r;
-            }
+            for (int e = 0; e < 4; ++e)                      // elements beyond V are 0 and stay 0
+                v[e] = residual_chain<NOREP>(sh, (double)pe[k][e], (double)qe[k][e],
+                                             (blk0 + k * (VT / 64)) * BLK + lane * 4 + e, rounds);
             sblk[k] = __dadd_rn(__dadd_rn(v[0], v[1]), __dadd_rn(v[2], v[3]));
         }
 #pragma unroll
@@ -281,7 +287,7 @@ __device__ void build_heap(Shared &sh, const VerifyParams &P, int buf)
 }
 
 // Inverse-CDF draw from the distribution whose heapB is current.  All threads call it; all return the token.
-template <class Shared>
+template <bool NOREP, class Shared>
 __device__ int tree_sample(Shared &sh, const VerifyParams &P, const float *prow, const float *qrow, int rounds,
                            float u)
 {
@@ -302,7 +308,7 @@ __device__ int tree_sample(Shared &sh, const VerifyParams &P, const float *prow,
     __syncthreads();     // heapA may still be read by a previous descent
     if (tid < BLK) {
         const int t = blk * BLK + tid;
-        sh.heapA[BLK + tid] = t < P.V ? residual_at(prow, qrow, sh.s_hist, rounds, t) : 0.0;
+        sh.heapA[BLK + tid] = t < P.V ? residual_at<NOREP>(sh, prow, qrow, rounds, t) : 0.0;
     }
     __syncthreads();
     for (int n = BLK >> 1; n >= 1; n >>= 1) {
@@ -329,7 +335,7 @@ __device__ int tree_sample(Shared &sh, const VerifyParams &P, const float *prow,
     int lo = -1, hi = 0x7fffffff;
     for (int e = tid; e < P.V; e += VT) {
         if (e == t) continue;
-        if (residual_at(prow, qrow, sh.s_hist, rounds, e) > 0.0) {
+        if (residual_at<NOREP>(sh, prow, qrow, rounds, e) > 0.0) {
             if (e < t) lo = e > lo ? e : lo;
             else hi = e < hi ? e : hi;
         }
@@ -343,7 +349,8 @@ __device__ int tree_sample(Shared &sh, const VerifyParams &P, const float *prow,
 }
 
 // FAST: a context's rows fit the workgroup's registers (NB <= FAST_NB).
-template <bool FAST>
+// NOREP: the candidates of a context were drawn without replacement (see residual_chain).
+template <bool FAST, bool NOREP>
 __global__ __launch_bounds__(VT) void verify_walk_kernel(const VerifyParams P)
 {
     using Shared = SharedT<FAST ? FAST_NB : MAX_NB, FAST ? FAST_NB * BLK : 1>;
@@ -375,20 +382,23 @@ __global__ __launch_bounds__(VT) void verify_walk_kernel(const VerifyParams P)
         // candidate `lane` of this context (in every wavefront): acceptance uniform, q(x) and the residual at x,
         // which is updated in place after every rejection
         double uc = 0.0, qc = 0.0, rc = 0.0;
+        int xc = -1;
         if (lane < cnt) {
             int x = tokens[first + lane];
             x = x < 0 ? 0 : (x >= P.V ? P.V - 1 : x);   // ids outside 0..V-1 are clamped, never dereferenced
+            xc = x;
             uc = (double)ua[first + lane];
             qc = (double)qrow[x];
             rc = (double)prow[x];
         }
         int rounds = 0, accepted = -1;
-        double S = 1.0;
+        double S = 1.0, Sq = 1.0;                        // both rows are trusted to be normalised in round 0
         // accept test of candidate c: the same value in every lane, read through one lane so that the walk is
         // scalar control flow
         auto accept = [&](int c) {
             const double u = __shfl(uc, c, 64), qx = __shfl(qc, c, 64), rx = __shfl(rc, c, 64);
-            return __builtin_amdgcn_readfirstlane((int)(__dmul_rn(u, __dmul_rn(qx, S)) < rx)) != 0;
+            const double rhs = NOREP ? __dmul_rn(rx, Sq) : rx;
+            return __builtin_amdgcn_readfirstlane((int)(__dmul_rn(u, __dmul_rn(qx, S)) < rhs)) != 0;
         };
         if (accept(0)) {
             accepted = first;
@@ -413,7 +423,12 @@ __global__ __launch_bounds__(VT) void verify_walk_kernel(const VerifyParams P)
             }
             for (int c = 0;;) {
                 // candidate c was rejected: r <- max(r - S q, 0), S <- sum r
-                if (tid == 0) sh.s_hist[rounds] = S;
+                const int xrej = NOREP ? __builtin_amdgcn_readfirstlane(__shfl(xc, c, 64)) : 0;
+                const double qrej = NOREP ? __shfl(qc, c, 64) : 0.0;
+                if (tid == 0) {
+                    sh.s_hist[rounds] = S;
+                    if (NOREP) { sh.sq_hist[rounds] = Sq; sh.x_hist[rounds] = xrej; }
+                }
                 buf ^= 1;
                 if constexpr (FAST) {
                     // four blocks at a time, the next four's q read from LDS while these are updated (the scheduler
@@ -433,18 +448,29 @@ __global__ __launch_bounds__(VT) void verify_walk_kernel(const VerifyParams P)
                             const float4 q4 = qv[(k0 / 4) & 1][k];
                             const float qe[4] = {q4.x, q4.y, q4.z, q4.w};
 #pragma unroll
-                            for (int e = 0; e < 4; ++e) r[k0 + k][e] = pos_part(__fma_rn(-S, (double)qe[e], r[k0 + k][e]));
+                            for (int e = 0; e < 4; ++e)
+                                r[k0 + k][e] = pos_part(__fma_rn(-S, (double)qe[e], NOREP ? __dmul_rn(r[k0 + k][e], Sq) : r[k0 + k][e]));
                         }
                         __builtin_amdgcn_sched_barrier(0);
                     }
+                    if (NOREP) {
+                        // the rejected token leaves the draft row: its owner (block = wave + 8k, 4 entries per lane)
+                        // clears its own LDS copy, after this round's update has used it
+                        const int blk = xrej / BLK, in = xrej % BLK;
+                        if (tid == (blk % (VT / 64)) * 64 + in / 4) ((float *)&qlds[(blk / (VT / 64)) * VT])[in % 4] = 0.f;
+                    }
                     store_block_sums(sh, P, r, buf);
                 } else {
-                    __syncthreads();          // s_hist[rounds] visible
-                    stream_block_sums(sh, P, prow, qrow, rounds + 1, buf);
+                    __syncthreads();          // s_hist[rounds] (sq_hist, x_hist) visible
+                    stream_block_sums<NOREP>(sh, P, prow, qrow, rounds + 1, buf);
                 }
                 {
-                    const double d = __fma_rn(-S, qc, rc);
+                    const double d = __fma_rn(-S, qc, NOREP ? __dmul_rn(rc, Sq) : rc);
                     rc = pos_part(d);
+                }
+                if (NOREP) {
+                    Sq = __dsub_rn(Sq, qrej);
+                    if (xc == xrej) qc = 0.0;             // also a later duplicate of the rejected token
                 }
                 rounds += 1;
                 __syncthreads();              // block sums (and s_hist) visible
@@ -478,13 +504,13 @@ __global__ __launch_bounds__(VT) void verify_walk_kernel(const VerifyParams P)
         if (term_buf < 0) {
             buf ^= 1;
             __syncthreads();
-            stream_block_sums(sh, P, term_p, term_q, 0, buf);
+            stream_block_sums<NOREP>(sh, P, term_p, term_q, 0, buf);
             term_buf = buf;
         }
         __syncthreads();
         build_heap(sh, P, term_buf);
         for (int k = 0; k < P.n_new; ++k) {
-            const int t = tree_sample(sh, P, term_p, term_q, term_rounds, P.us[(int64_t)b * P.n_new + k]);
+            const int t = tree_sample<NOREP>(sh, P, term_p, term_q, term_rounds, P.us[(int64_t)b * P.n_new + k]);
             if (tid == 0) P.cand_new[((int64_t)b * P.R + root) * P.n_new + k] = t;
         }
     }
@@ -522,12 +548,36 @@ extern "C" size_t mcsd_verify_tree_workspace(const mcsd_mask_view_t *mask, mcsd_
            align256(sizeof(int32_t) * B * R * (n_new > 0 ? n_new : 1));
 }
 
+namespace {
+void launch_walk(const VerifyParams &P, bool norep, dim3 grid, hipStream_t st)
+{
+    const bool fast = P.NB <= FAST_NB;
+    auto kernel = fast ? (norep ? verify_walk_kernel<true, true> : verify_walk_kernel<true, false>)
+                       : (norep ? verify_walk_kernel<false, true> : verify_walk_kernel<false, false>);
+    mcsd_launch(MCSD_KERNEL_VERIFY_WALK, kernel, grid, dim3(VT), st, P);
+}
+}  // namespace
+
 extern "C" int mcsd_verify_tree(const mcsd_mask_view_t *mask, mcsd_mode_t mode, int32_t B, int32_t V,
                                 const int32_t *tokens, const float *p_target, const float *q_draft,
                                 int64_t p_batch_stride, int64_t q_batch_stride, const float *u_accept,
                                 const float *u_sample, int32_t n_new, int32_t *out_path, int32_t *out_accept_len,
                                 int32_t *out_new_tokens, void *workspace, size_t workspace_bytes, void *hip_stream)
 {
+    return mcsd_verify_tree_sampling(mask, mode, MCSD_WITH_REPLACEMENT, B, V, tokens, p_target, q_draft, p_batch_stride,
+                                     q_batch_stride, u_accept, u_sample, n_new, out_path, out_accept_len,
+                                     out_new_tokens, workspace, workspace_bytes, hip_stream);
+}
+
+extern "C" int mcsd_verify_tree_sampling(const mcsd_mask_view_t *mask, mcsd_mode_t mode, mcsd_sampling_t sampling,
+                                         int32_t B, int32_t V, const int32_t *tokens, const float *p_target,
+                                         const float *q_draft, int64_t p_batch_stride, int64_t q_batch_stride,
+                                         const float *u_accept, const float *u_sample, int32_t n_new,
+                                         int32_t *out_path, int32_t *out_accept_len, int32_t *out_new_tokens,
+                                         void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    if (sampling != MCSD_WITH_REPLACEMENT && sampling != MCSD_WITHOUT_REPLACEMENT) return MCSD_EINVAL;
+    const bool norep = sampling == MCSD_WITHOUT_REPLACEMENT;
     if (!mask || !tokens || !p_target || !u_accept || !out_path || !out_accept_len) return MCSD_EINVAL;
     if (mode != MCSD_DRAFT_INIT && mode != MCSD_TARGET_INIT) return MCSD_EINVAL;
     if (B < 1 || B > 65535 || V < 1 || n_new < 0 || n_new > 64) return MCSD_EINVAL;
@@ -555,8 +605,7 @@ extern "C" int mcsd_verify_tree(const mcsd_mask_view_t *mask, mcsd_mode_t mode, 
     hipStream_t st = (hipStream_t)hip_stream;
     if (mode == MCSD_DRAFT_INIT) {
         P.cand_path = out_path; P.cand_len = out_accept_len; P.cand_new = out_new_tokens;
-        if (P.NB <= FAST_NB) mcsd_launch(MCSD_KERNEL_VERIFY_WALK, verify_walk_kernel<true>, dim3(1, B), dim3(VT), st, P);
-        else mcsd_launch(MCSD_KERNEL_VERIFY_WALK, verify_walk_kernel<false>, dim3(1, B), dim3(VT), st, P);
+        launch_walk(P, norep, dim3(1, B), st);
         return mcsd_hip_status(hipGetLastError());
     }
     const size_t need = mcsd_verify_tree_workspace(mask, mode, B, n_new);
@@ -568,8 +617,7 @@ extern "C" int mcsd_verify_tree(const mcsd_mask_view_t *mask, mcsd_mode_t mode, 
     P.cand_len = (int32_t *)w;
     w += align256(sizeof(int32_t) * B * R);
     P.cand_new = (int32_t *)w;
-    if (P.NB <= FAST_NB) mcsd_launch(MCSD_KERNEL_VERIFY_WALK, verify_walk_kernel<true>, dim3(P.R, B), dim3(VT), st, P);
-    else mcsd_launch(MCSD_KERNEL_VERIFY_WALK, verify_walk_kernel<false>, dim3(P.R, B), dim3(VT), st, P);
+    launch_walk(P, norep, dim3(P.R, B), st);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return MCSD_EHIP;
     hipLaunchKernelGGL(verify_select_kernel, dim3(B), dim3(64), 0, st, P, out_path, out_accept_len, out_new_tokens);
