@@ -239,7 +239,7 @@ constexpr float RESCALE_SLACK = 6.f;
 struct LaneAddr {
     int k;   // K operand: row (kg*32 + ln), chunk g ^ swz; XOR ks*32 selects the k-step
     int v;   // V^T operand: row (kg*32 + 4g + j/4), chunk/sub of this lane; XOR ct*16 and an immediate select the rest
-    int k8;  // the same inside an fp8 tile: row (kg*32 + ln), half g of chunk swz8; XOR ks*16 selects the k-step
+    int k8;  // the same inside an fp8 tile: row (kg*32 + ln), chunk g ^ swz8; XOR kp*32 selects the pair of k-steps
     int v8;  // fp8 V^T operand (8-bit transpose load): row of this lane's key slot, chunk (ln/16) ^ swz8, half ln & 1
 };
 
@@ -287,16 +287,21 @@ __device__ inline void attn_tile(const unsigned char *stage, const LaneAddr la, 
     // K rows of the blocks (A operands of S^T = K Q^T); block u sits 32*u rows below the lane's base row
     bf16x8_t kf[U][C::KS];
 #pragma unroll
-    for (int u = 0; u < U; ++u)
+    for (int u = 0; u < U; ++u) {
+        if constexpr (F8T) {
+            // one 16-byte read = the lane's share of two k-steps (see the column order in the kernel)
 #pragma unroll
-        for (int ks = 0; ks < C::KS; ++ks) {
-            if constexpr (F8T) {
-                const uint2 raw = *(const uint2 *)(stage + (la.k8 ^ (ks * 16)) + u * 32 * ROWB);
-                kf[u][ks] = fp8x8_to_bf16(raw.x, raw.y);
-            } else {
-                kf[u][ks] = *(const bf16x8_t *)(stage + (la.k ^ (ks * 32)) + u * 32 * ROWB);
+            for (int kp = 0; kp < C::KS / 2; ++kp) {
+                const uint4 raw = *(const uint4 *)(stage + (la.k8 ^ (kp * 32)) + u * 32 * ROWB);
+                kf[u][2 * kp] = fp8x8_to_bf16(raw.x, raw.y);
+                kf[u][2 * kp + 1] = fp8x8_to_bf16(raw.z, raw.w);
             }
+        } else {
+#pragma unroll
+            for (int ks = 0; ks < C::KS; ++ks)
+                kf[u][ks] = *(const bf16x8_t *)(stage + (la.k ^ ((F8K ? 4 * (ks >> 1) + (ks & 1) : 2 * ks) * 16)) + u * 32 * ROWB);
         }
+    }
     __builtin_amdgcn_sched_barrier(0);
     // S^T[key][query] : lane (query = ln, half g) gets keys 8*(r/4) + 4*g + r%4, r = 0..15
     f32x16_t sacc[U];
@@ -477,7 +482,12 @@ void tree_attn_bf16_kernel(const AttnParams p)
 #pragma unroll
     for (int ks = 0; ks < C::KS; ++ks) {
         uint4 v = make_uint4(0, 0, 0, 0);
-        if (qrow < p.n) v = *(const uint4 *)(q + (int64_t)qrow * D + ks * 16 + g * 8);
+        // Columns of k-step ks in lane half g: 16 ks + 8 g .. +7.  With an fp8 prefix cache the halves trade places
+        // with the k-step's parity, 32 (ks/2) + 16 g + 8 (ks%2) .. +7, so that a lane's columns of two consecutive
+        // k-steps are 16 consecutive bytes of an fp8 row (one conflict-free 16-byte LDS read); the contraction is
+        // over all columns either way.
+        const int col = F8 ? (ks >> 1) * 32 + g * 16 + (ks & 1) * 8 : ks * 16 + g * 8;
+        if (qrow < p.n) v = *(const uint4 *)(q + (int64_t)qrow * D + col);
         qs.q[ks] = __builtin_bit_cast(bf16x8_t, v);
     }
     uint64_t mrow[2] = {0, 0};
@@ -494,7 +504,7 @@ void tree_attn_bf16_kernel(const AttnParams p)
     LaneAddr la;
     {
         const int krow = kg * C::KPW * 32 + ln;
-        la.k = krow * C::RB + ((g ^ swz<D>(krow)) * 16);
+        la.k = krow * C::RB + (((F8 ? 2 * g : g) ^ swz<D>(krow)) * 16);     // bf16 chunk of (k-step 0, half g)
         const int j = ln & 15, grp = ln >> 4, jr = j >> 2;
         const int vrow = kg * C::KPW * 32 + 4 * g + jr;               // + 32*u + 16*ks2 + 8*e4 by immediate
         const int lchunk = grp * 2 + ((j & 3) >> 1);                   // + 4*cb
@@ -502,7 +512,7 @@ void tree_attn_bf16_kernel(const AttnParams p)
         la.v = vrow * C::RB + ((lchunk ^ swz<D>(vrow)) * 16) + (j & 1) * 8;
         la.k8 = la.v8 = 0;
         if constexpr (F8) {
-            la.k8 = krow * C::RBP + swz8(krow) * 16 + g * 8;
+            la.k8 = krow * C::RBP + ((g ^ swz8(krow)) * 16);
             const int e = j >> 1;                                        // key slot this lane addresses
             const int row8 = kg * C::KPW * 32 + 8 * (e >> 2) + 4 * g + (e & 3);
             la.v8 = row8 * C::RBP + ((grp ^ swz8(row8)) * 16) + (j & 1) * 8;
