@@ -2,8 +2,9 @@
 // sequence, the probability that the target model accepts it; the tree stops growing when every sequence is
 // predicted below the threshold (caption of Fig. 2).
 //
-//   decision_distribution_kernel  type 2: Concat(Topk(y), Ent(y)) of one draft distribution y per workgroup
-//                                 (one pass over the row from HBM, a second one from cache), then the MLP
+//   decision_distribution_kernel  type 2: Concat(Topk(y), Ent(y)) of one draft distribution y per workgroup (the
+//                                 row is read once into registers, or streamed twice when it is too long), then
+//                                 the MLP
 //   decision_hidden_kernel        type 1: the MLP on the draft model's hidden states, four rows per workgroup
 //   early_stop_kernel             stop[b] = every sequence of tree b below the threshold
 //
@@ -45,20 +46,9 @@ __device__ __forceinline__ double dpp_f64(double v)
     return __hiloint2double(hi, lo);
 }
 
-// Maximum / sum over the 64 lanes, result in every lane.  Partner lanes: l^1 and l^2 by quad permutation; the
-// mirrored lane of the half row (row) stands in for l^4 (l^8) because groups of 4 (8) already agree; l^16 by
-// swizzle; l^32 by the half-wave swap, which returns {own, partner} in an order a commutative operation ignores.
-__device__ __forceinline__ float wave_max(float v)
-{
-    v = fmaxf(v, dpp_f32<0xB1>(v));
-    v = fmaxf(v, dpp_f32<0x4E>(v));
-    v = fmaxf(v, dpp_f32<0x141>(v));
-    v = fmaxf(v, dpp_f32<0x140>(v));
-    v = fmaxf(v, __int_as_float(__builtin_amdgcn_ds_swizzle(__float_as_int(v), 0x401F)));
-    const auto s = __builtin_amdgcn_permlane32_swap((unsigned)__float_as_int(v), (unsigned)__float_as_int(v), false, false);
-    return fmaxf(__int_as_float((int)s[0]), __int_as_float((int)s[1]));
-}
-
+// Sum over the 64 lanes, result in every lane.  Partner lanes: l^1 and l^2 by quad permutation; the mirrored lane of
+// the half row (row) stands in for l^4 (l^8) because groups of 4 (8) already agree; l^16 by swizzle; l^32 by the
+// half-wave swap, which returns {own, partner} in an order a commutative operation ignores.
 __device__ __forceinline__ double wave_sum(double v)
 {
     v += dpp_f64<0xB1>(v);
