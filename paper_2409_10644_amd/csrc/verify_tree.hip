@@ -2,7 +2,7 @@
 // recursive rejection sampling down the candidate tree, longest-path selection for target-initialised
 // trees, and sampling of the new token(s).
 //
-// One workgroup of 512 lanes walks one tree (draft-initialised) or one level-1 subtree (target-initialised).
+// One workgroup of 1024 lanes walks one tree (draft-initialised) or one level-1 subtree (target-initialised).
 // The residual r <- max(r - S*q, 0) is never stored: after j rejections an element is recomputed from p, q
 // and the j previous sums (a chain of j fused multiply-adds), so a round is one coalesced sweep over the
 // two vocabulary rows.  Sums over the vocabulary follow the balanced binary tree over the zero-padded
@@ -18,7 +18,7 @@
 
 namespace {
 
-constexpr int VT = 512;                  // threads per workgroup
+constexpr int VT = 1024;                 // threads per workgroup
 constexpr int BLK = 256;                 // vocabulary elements per wavefront load
 constexpr int MAX_NB = MCSD_MAX_VOCAB / BLK;
 
@@ -47,7 +47,7 @@ struct SharedT {
     int lo_idx, hi_idx;
 };
 
-constexpr int GROUP = 16;                // blocks a wavefront handles at a time
+constexpr int GROUP = 8;                // blocks a wavefront handles at a time
 constexpr int FAST_NB = GROUP * (VT / 64);   // up to this many blocks a context's rows stay in registers
 
 // max(d, 0) as one instruction.  d is never NaN here, and the sign of a zero result never reaches a decision
@@ -149,7 +149,7 @@ __device__ inline void wave_tree_sum_n(double (&v)[N])
     }
 }
 
-// 4 elements of each of the wavefront's GROUP blocks (block wave + 16k): float rows -> registers; beyond V: 0.
+// 4 elements of each of the wavefront's GROUP blocks (block wave + 16 k, 16 wavefronts): float rows -> registers; beyond V: 0.
 // The thread id is hidden from the optimiser so that offsets and bounds tests are recomputed at every use
 // instead of being kept in registers across the whole walk.
 __device__ inline void load_rows(const VerifyParams &P, const float *row, float (&dst)[GROUP][4])
@@ -175,7 +175,7 @@ __device__ inline void load_rows(const VerifyParams &P, const float *row, float 
     }
 }
 
-// Block sums of a register-resident distribution into leaf[buf] (blocks wave + 16k).  No barrier.
+// Block sums of a register-resident distribution into leaf[buf] (blocks wave + 16 k).  No barrier.
 template <class Shared>
 __device__ inline void store_block_sums(Shared &sh, const VerifyParams &P, const double (&r)[GROUP][4], int buf)
 {
@@ -404,7 +404,7 @@ __global__ __launch_bounds__(VT) void verify_walk_kernel(const VerifyParams P)
             accepted = first;
         } else {
             // First rejection at this context: from here on the residual is needed.  Register-resident path: r
-            // holds this lane's 4 elements of blocks wave + 8k and is updated in place; q is parked in LDS at
+            // holds this lane's 4 elements of blocks wave + 16 k and is updated in place; q is parked in LDS at
             // float4 slot k * VT + tid (read back by this lane only).
             double r[GROUP][4];
             float4 *qlds = (float4 *)sh.qrow + tid;
@@ -454,7 +454,7 @@ __global__ __launch_bounds__(VT) void verify_walk_kernel(const VerifyParams P)
                         __builtin_amdgcn_sched_barrier(0);
                     }
                     if (NOREP) {
-                        // the rejected token leaves the draft row: its owner (block = wave + 8k, 4 entries per lane)
+                        // the rejected token leaves the draft row: its owner (block = wave + 16 k, 4 entries per lane)
                         // clears its own LDS copy, after this round's update has used it
                         const int blk = xrej / BLK, in = xrej % BLK;
                         if (tid == (blk % (VT / 64)) * 64 + in / 4) ((float *)&qlds[(blk / (VT / 64)) * VT])[in % 4] = 0.f;
