@@ -135,6 +135,13 @@ class Step:
         return float(want[1].mean())
 
 
+class Ctx:
+    """What time_kernel needs of a Step, for the sections that are not a Step."""
+
+    def __init__(self, binding, torch):
+        self.binding, self.torch = binding, torch
+
+
 def time_kernel(st, hip, kernel_id, launch, reps, warm=0):
     """Average device execution time (ms) of one library kernel over `reps` back-to-back launches, from event
     pairs that the library places around that kernel's launch.  `warm` untimed launches go first in the same
@@ -476,10 +483,7 @@ def main():
                 b_, h_, i_ = int(rng.integers(wq.B)), int(rng.integers(wq.H)), int(rng.integers(n))
                 H.assert_close(got[b_, h_, i_], oracle.tree_attention_row(rep_, M, n, b_, h_, i_), "bf16", "bench gqa")
 
-            class _G:
-                pass
-            gs = _G()
-            gs.binding, gs.torch = binding, torch
+            gs = Ctx(binding, torch)
             g_avg, g_med, g_p10, g_p90 = time_kernel(gs, hip, binding.KERNEL_ATTN_SWEEP, gcall, args.extra_reps, warm=args.extra_reps)
             gbytes = sum(2 * wq.d * (Hkv * (2 * int(L) + 2 * n) + wq.H * 2 * n) for L in lens)
             gflops = sum(wq.H * 4 * n * (int(L) + n) * wq.d for L in lens)
@@ -530,10 +534,7 @@ def main():
                     b_, h_, i_ = int(rng8.integers(w8.B)), int(rng8.integers(w8.H)), int(rng8.integers(n8))
                     H.assert_close(got8[b_, h_, i_], oracle.tree_attention_row_fp8kv(inp8, M8, n8, b_, h_, i_), "bf16", "bench fp8kv")
 
-                class _F:
-                    pass
-                fs = _F()
-                fs.binding, fs.torch = binding, torch
+                fs = Ctx(binding, torch)
                 f_avg, f_med, f_p10, f_p90 = time_kernel(fs, hip, binding.KERNEL_ATTN_SWEEP, fcall, args.extra_reps, warm=args.extra_reps)
                 fbytes = sum(w8.H * w8.d * (2 * int(L) * 1 + 4 * n8 * 2) for L in lens)
                 fflops = sum(w8.H * 4 * n8 * (int(L) + n8) * w8.d for L in lens)
@@ -569,10 +570,7 @@ def main():
             o_len = torch.zeros((wb.B,), dtype=torch.int32, device="cuda")
             o_new = torch.zeros((wb.B, 1), dtype=torch.int32, device="cuda")
 
-            class _V:
-                pass
-            vs = _V()
-            vs.binding, vs.torch = binding, torch
+            vs = Ctx(binding, torch)
             vs.mode, vs.w, vs.gamma, vs.n_new, vs.path, vs.alen = 0, wb, vv.gamma, 1, o_path, o_len
 
             def vcall(i):
@@ -609,10 +607,7 @@ def main():
             prob = torch.zeros((copies * Bd, Wd), dtype=torch.float32, device="cuda")
             stop = torch.zeros((copies * Bd,), dtype=torch.int32, device="cuda")
 
-            class _D:
-                pass
-            ds = _D()
-            ds.binding, ds.torch = binding, torch
+            ds = Ctx(binding, torch)
             nb = min(Bd, 4)
             want = oracle.mlp(ws, bs, oracle.decision_features(q[:nb, 1:].reshape(nb * Wd, V), k)).reshape(nb, Wd)
             for trees, tag in ((1, "1"), (copies * Bd, str(copies * Bd))):
@@ -663,10 +658,7 @@ def main():
         buf.fill_(1)
         sink = torch.zeros(16, dtype=torch.uint8, device="cuda")
 
-        class _S:      # what time_kernel needs of a Step
-            pass
-        ss = _S()
-        ss.binding, ss.torch = binding, torch
+        ss = Ctx(binding, torch)
         per_grid = {}
         for wgs in (256, 512, 2048, 8192):      # the rate depends on how the grid's stride falls on the memory channels
             s_avg = time_kernel(ss, hip, binding.KERNEL_STREAM_READ, lambda i: binding.stream_read(buf, sink, wgs), 10, warm=10)[0]
