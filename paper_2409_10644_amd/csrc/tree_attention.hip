@@ -45,7 +45,7 @@ struct AttnParams {
     int32_t hpw;      // query heads one workgroup of the bf16 sweep serves (they share its K/V stream)
     int32_t bph;      // 32-row query blocks per query head in a workgroup (1, 2 or 4); QBP = bph * hpw
     int32_t chunks;   // grp / hpw: workgroup units per key/value head
-    int32_t pair_cus; // > 0: compute units, and the grid is one workgroup per (b,h), two per compute unit (see the kernel)
+    int32_t pair_cus; // > 0: compute units, and the grid is exactly two workgroups per compute unit, no separate tree workgroup (see the kernel)
     int32_t row0;     // first query row: rows row0 .. n-1 are computed (keys are always all n tree nodes)
     int32_t max_prefix;
     int64_t node_stride, head_stride;
@@ -417,30 +417,36 @@ void tree_attn_bf16_kernel(const AttnParams p)
     // which read the same Q, tree K/V and mask rows and write neighbouring partial results, share one XCD's L2.
     const int total = gridDim.x;
     int wg = blockIdx.x;
-    if (p.G > 1 && (total & 7) == 0) wg = (wg & 7) * (total >> 3) + (wg >> 3);
-    const int s = wg % p.G;
+    if (p.G > 1 && p.pair_cus == 0 && (total & 7) == 0) wg = (wg & 7) * (total >> 3) + (wg >> 3);
+    int s = wg % p.G;
     int bhi = wg / p.G;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // the same in all lanes: keep it in a scalar register
     if (p.pair_cus > 0) {
-        // One workgroup per (sequence, head), exactly two per compute unit.  On this machine workgroups i and
-        // i + #CUs of such a grid land on the same compute unit (measured; nothing but speed depends on it): give
-        // that pair the heads of a long and of a short sequence, so that every compute unit has about the same
-        // number of keys to stream however ragged the batch is.  Sequences are ranked by length here (B <= 64).
-        __shared__ int32_t s_len[64], s_seq_at[64];
-        if (tid < p.B) {
-            const int Lt = p.lens[tid];
-            s_len[tid] = Lt < 0 ? 0 : (Lt > p.max_prefix ? p.max_prefix : Lt);
+        // Exactly two workgroups per compute unit and all of them resident at once.  On this machine workgroups i
+        // and i + #CUs of such a grid land on the same compute unit (measured; nothing but speed depends on it):
+        // give that pair a long and a short piece of work, so that every compute unit has about the same number of
+        // keys to stream however ragged the batch is.  The pieces are the (sequence, key split) classes, p.H equal
+        // items each; they are ranked by their number of tiles here (B * S <= 256).
+        __shared__ int32_t s_work[256], s_cls_at[256];
+        const int n_cls = p.B * p.S;
+        if (tid < n_cls) {
+            const int Lt = p.lens[tid / p.S], sp = tid % p.S;
+            const int Lc = Lt < 0 ? 0 : (Lt > p.max_prefix ? p.max_prefix : Lt);
+            const int tl = (Lc + C::T - 1) / C::T - sp * p.tps;
+            s_work[tid] = (tl < 0 ? 0 : (tl > p.tps ? p.tps : tl)) + (sp == 0 ? (p.n + C::T - 1) / C::T : 0);
         }
         __syncthreads();
-        if (tid < p.B) {
+        if (tid < n_cls) {
             int rank = 0;
-            for (int o = 0; o < p.B; ++o) rank += (s_len[o] > s_len[tid]) || (s_len[o] == s_len[tid] && o < tid);
-            s_seq_at[rank] = tid;
+            for (int o = 0; o < n_cls; ++o) rank += (s_work[o] > s_work[tid]) || (s_work[o] == s_work[tid] && o < tid);
+            s_cls_at[rank] = tid;
         }
         __syncthreads();
         const int r = wg < p.pair_cus ? wg : total + p.pair_cus - 1 - wg;      // rank i with rank total-1-i
-        bhi = s_seq_at[r / p.H] * p.H + r % p.H;
+        const int cls = s_cls_at[r / p.H];
+        s = cls % p.S;
+        bhi = (cls / p.S) * p.H + r % p.H;
     }
     const int h = bhi % p.H, b = bhi / p.H;
 
@@ -1171,8 +1177,8 @@ int attention_call(const mcsd_mask_view_t *mask, mcsd_dtype_t dtype, bool f8, fl
         if (hipGetDevice(&dev) == hipSuccess && hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess)
             n_cus = v > 0 ? v : -1;
     }
-    if (dtype == MCSD_BF16 && pl.G == 1 && B <= 64) {
-        if (n_cus > 0 && (long)B * pl.units == 2L * n_cus) p.pair_cus = n_cus;
+    if (dtype == MCSD_BF16 && pl.G == pl.S && (long)B * pl.S <= 256) {
+        if (n_cus > 0 && (long)B * pl.units * pl.S == 2L * n_cus) p.pair_cus = n_cus;
         if (const char *ov = getenv("MCSD_ATTN_PAIRING")) {  // tuning override: 0 keeps the natural order
             if (atol(ov) == 0) p.pair_cus = 0;
         }
