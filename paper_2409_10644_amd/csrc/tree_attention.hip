@@ -45,7 +45,7 @@ struct AttnParams {
     int32_t hpw;      // query heads one workgroup of the bf16 sweep serves (they share its K/V stream)
     int32_t bph;      // 32-row query blocks per query head in a workgroup (1, 2 or 4); QBP = bph * hpw
     int32_t chunks;   // grp / hpw: workgroup units per key/value head
-    int32_t pair_cus; // > 0: compute units, and the grid is exactly two workgroups per compute unit, no separate tree workgroup (see the kernel)
+    int32_t pair_cus; // > 0: compute units; the grid has more workgroups than that and no separate tree workgroup (see the kernel)
     int32_t row0;     // first query row: rows row0 .. n-1 are computed (keys are always all n tree nodes)
     int32_t max_prefix;
     int64_t node_stride, head_stride;
@@ -423,11 +423,12 @@ void tree_attn_bf16_kernel(const AttnParams p)
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // the same in all lanes: keep it in a scalar register
     if (p.pair_cus > 0) {
-        // Exactly two workgroups per compute unit and all of them resident at once.  On this machine workgroups i
-        // and i + #CUs of such a grid land on the same compute unit (measured; nothing but speed depends on it):
-        // give that pair a long and a short piece of work, so that every compute unit has about the same number of
-        // keys to stream however ragged the batch is.  The pieces are the (sequence, key split) classes, p.H equal
-        // items each; they are ranked by their number of tiles here (B * S <= 256).
+        // More workgroups than compute units.  Up to two per compute unit they are all resident at once, and on this
+        // machine workgroups i and i + #CUs of such a grid land on the same compute unit (measured; nothing but
+        // speed depends on it): that pair gets a long and a short piece of work, so that every compute unit has
+        // about the same number of keys to stream however ragged the batch is.  With more than two per compute unit
+        // the hardware hands out workgroups in id order as slots free up: longest first.  The pieces are the
+        // (sequence, key split) classes, p.H equal items each, ranked by their number of tiles here (B * S <= 256).
         __shared__ int32_t s_work[256], s_cls_at[256];
         const int n_cls = p.B * p.S;
         if (tid < n_cls) {
@@ -443,7 +444,8 @@ void tree_attn_bf16_kernel(const AttnParams p)
             s_cls_at[rank] = tid;
         }
         __syncthreads();
-        const int r = wg < p.pair_cus ? wg : total + p.pair_cus - 1 - wg;      // rank i with rank total-1-i
+        const int r = total > 2 * p.pair_cus ? wg                               // longest first
+                                             : (wg < p.pair_cus ? wg : total + p.pair_cus - 1 - wg);   // rank i with rank total-1-i
         const int cls = s_cls_at[r / p.H];
         s = cls % p.S;
         bhi = (cls / p.S) * p.H + r % p.H;
@@ -1178,7 +1180,7 @@ int attention_call(const mcsd_mask_view_t *mask, mcsd_dtype_t dtype, bool f8, fl
             n_cus = v > 0 ? v : -1;
     }
     if (dtype == MCSD_BF16 && pl.G == pl.S && (long)B * pl.S <= 256) {
-        if (n_cus > 0 && (long)B * pl.units * pl.S == 2L * n_cus) p.pair_cus = n_cus;
+        if (n_cus > 0 && (long)B * pl.units * pl.S > n_cus) p.pair_cus = n_cus;
         if (const char *ov = getenv("MCSD_ATTN_PAIRING")) {  // tuning override: 0 keeps the natural order
             if (atol(ov) == 0) p.pair_cus = 0;
         }

@@ -704,3 +704,22 @@ def test_grouped_query_attention_llama3_like_batch(binding, oracle, H):
     with pytest.raises(binding.McsdError):
         binding.tree_attention_gqa(v, aq.code, B, Hq, 5, d, 0, aq.q, ak.kt, ak.vt, ak.node_stride, ak.kp, ak.vp, ak.base,
                                    ak.lens, ak.head_stride, 700, aq.scale, aq.out, ws)
+
+
+@pytest.mark.parametrize("B,Hh", [(12, 32), (24, 32), (5, 64), (40, 16)])
+def test_ragged_batches_with_more_workgroups_than_compute_units(binding, oracle, H, B, Hh):
+    """Grids between one and two workgroups per compute unit (long/short pairs, some compute units with one
+    workgroup) and beyond two (longest first): the order in which workgroups take (sequence, head) items is
+    computed in the kernel from the lengths; every item must still be computed exactly once."""
+    br = (4, 2, 2, 2)
+    rng = np.random.default_rng(B * 100 + Hh)
+    lens = tuple(int(x) for x in rng.integers(0, 600, size=B))
+    w = scaled(WORKLOADS["cfg4"], B=B, H=Hh, cfg_id=96)
+    inp = attention_inputs(w, seed=3, lens=lens, kv_capacity=640)
+    ad = H.AttnDevice(inp)
+    v = binding.slice_mask(binding.build_mask(br), 4)
+    got = H.run_attention(binding, v, ad, max_prefix=640, fill=float("nan"))
+    assert np.all(np.isfinite(got))                      # every row of every (sequence, head) was written
+    M = oracle.build_mask(br)
+    for (b, h, i) in _sample_rows(rng, B, Hh, v.n_nodes, 96):
+        H.assert_close(got[b, h, i], oracle.tree_attention_row(inp, M, v.n_nodes, b, h, i), "bf16", f"row {(b, h, i)}")

@@ -80,6 +80,11 @@ WORKLOADS: Dict[str, Workload] = {
     "cfg5": Workload(5, "cfg5", B=8, H=32, d=128, dtype="bf16", prefix_min=16384, prefix_max=16384,
                      branching=(8, 2, 2, 1, 1), V=32000, target_sigma=3.0, draft_noise_sigma=2.0,
                      mode=TARGET_INIT),
+    # the ragged batch of cfg4 four times over: more workgroups than the chip holds at once (not one of the five
+    # benchmark configurations; a serving-size batch for the attention sweep)
+    "cfg4_b64": Workload(7, "cfg4_b64", B=64, H=32, d=128, dtype="bf16", prefix_min=512, prefix_max=4096,
+                         branching=(4, 2, 2, 2), V=32000, target_sigma=3.0, draft_noise_sigma=1.5,
+                         mode=DRAFT_INIT),
     # the paper's dynamic setting (Sec. 4.1: depth D = 5, width W = 16): a fork-shaped tree, 16 chains of 5 tokens,
     # temperature 1; one of the "next" workloads, not one of the five benchmark configurations
     "fork": Workload(6, "fork", B=1, H=32, d=128, dtype="bf16", prefix_min=1024, prefix_max=1024,
