@@ -28,8 +28,8 @@ N_LAYERS = 32                   # Llama-2-7B
 
 # HBM traffic per launch of the sweep kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (bytes, already
 # scaled by the copy-kernel calibration); filled from the summaries under profiles/.  None = not measured.
-MEASURED_TRAFFIC = {"cfg2": 21_770_000, "cfg4": 664_610_000, "cfg5": 2_205_440_000,
-                    "cfg4_fp8kv": 348_140_000, "cfg5_fp8kv": 1_134_400_000}
+MEASURED_TRAFFIC = {"cfg2": 21_800_000, "cfg4": 664_690_000, "cfg5": 2_213_330_000, "cfg4_b64": 2_742_410_000,
+                    "cfg4_fp8kv": 348_140_000, "cfg5_fp8kv": 1_142_790_000}
 
 
 def log(*a):
