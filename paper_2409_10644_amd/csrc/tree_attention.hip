@@ -19,6 +19,7 @@
 #include <math.h>
 #include <stdlib.h>
 
+#include <atomic>
 #include <type_traits>
 
 #include "mcsd_internal.h"
@@ -1158,6 +1159,7 @@ int attention_call(const mcsd_mask_view_t *mask, mcsd_dtype_t dtype, bool f8, fl
     if (((node_stride * d) & 7) || (head_stride & (f8 ? 15 : 7))) return MCSD_EINVAL;   // 16-byte rows and heads
 
     const AttnPlan pl = make_plan(dtype, B, H_q, H_kv, n - row_begin, max_prefix, f8);
+    if ((int64_t)pl.G * pl.units * B > 0x7fffffff) return MCSD_EUNSUPPORTED;           // one-dimensional grid
     const size_t need = workspace_bytes_for(pl, dtype, B, d, n);
     if (need > 0 && (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 255))) return MCSD_EWORKSPACE;
 
@@ -1173,11 +1175,16 @@ int attention_call(const mcsd_mask_view_t *mask, mcsd_dtype_t dtype, bool f8, fl
     p.v_scale = f8 ? v_scale : 1.f;
     p.S = pl.S; p.G = pl.G; p.SP = pl.G;
     p.pair_cus = 0;
-    static int n_cus = 0;                                      // compute units of the current device, asked once
-    if (n_cus == 0) {
-        int dev = 0, v = 0;
-        if (hipGetDevice(&dev) == hipSuccess && hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess)
-            n_cus = v > 0 ? v : -1;
+    // compute units of the current device, asked once per device (concurrent first calls store the same value)
+    static std::atomic<int> cus_of_device[64];
+    int n_cus = -1, dev = 0;
+    if (hipGetDevice(&dev) == hipSuccess && dev >= 0 && dev < 64) {
+        n_cus = cus_of_device[dev].load(std::memory_order_relaxed);
+        if (n_cus == 0) {
+            int v = 0;
+            n_cus = hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0 ? v : -1;
+            cus_of_device[dev].store(n_cus, std::memory_order_relaxed);
+        }
     }
     if (dtype == MCSD_BF16 && pl.G == pl.S && (long)B * pl.S <= 256) {
         if (n_cus > 0 && (long)B * pl.units * pl.S > n_cus) p.pair_cus = n_cus;

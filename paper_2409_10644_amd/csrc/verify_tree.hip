@@ -542,7 +542,7 @@ size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 extern "C" size_t mcsd_verify_tree_workspace(const mcsd_mask_view_t *mask, mcsd_mode_t mode, int32_t B, int32_t n_new)
 {
-    if (!mask || mode != MCSD_TARGET_INIT || B < 1 || n_new < 0) return 0;
+    if (!mask || mode != MCSD_TARGET_INIT || B < 1 || n_new < 0 || mask->gamma < 1) return 0;
     const size_t R = (size_t)mask->branching_host[0];
     return align256(sizeof(int32_t) * B * R * mask->gamma) + align256(sizeof(int32_t) * B * R) +
            align256(sizeof(int32_t) * B * R * (n_new > 0 ? n_new : 1));
