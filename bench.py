@@ -280,7 +280,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build measures one GPU only (the path shards by sequence and head without any "
-                 "exchange; see DESIGN.md); run with --gpus 1")
+                 "exchange, so N GPUs are N independent copies of this run); run with --gpus 1")
     import torch
     assert torch.cuda.is_available(), "bench.py needs the MI355X"
     torch.cuda.set_device(0)
