@@ -308,10 +308,15 @@ __device__ inline void attn_tile(const unsigned char *stage, const LaneAddr la, 
     f32x16_t sacc[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
+        // The wavefront's runs of matrix instructions are issued at raised priority: the other wavefront of the SIMD,
+        // busy with its soft-max, then does not delay them (measured: 2-3 % on the long sweeps; the opposite
+        // assignment costs as much).
+        if (u == 0) __builtin_amdgcn_s_setprio(2);
         sacc[u] = (f32x16_t){0};
 #pragma unroll
         for (int ks = 0; ks < C::KS; ++ks) sacc[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[u][ks], qs.q[ks], sacc[u], 0, 0, 0);
     }
+    __builtin_amdgcn_s_setprio(0);
     // V^T fragments via the LDS transpose load, issued ahead of their use: block 0's during the softmax, block 1's
     // before the first PV MFMA.  The reads of one k-step pair (ks2, e4) sit 16*ks2 + 8*e4 rows below the lane's
     // base row; the chunk select is cb*4 ^ e4*2.
@@ -390,6 +395,7 @@ __device__ inline void attn_tile(const unsigned char *stage, const LaneAddr la, 
     if (U == 2) {
         read_v(1);
         __builtin_amdgcn_sched_barrier(0);
+        __builtin_amdgcn_s_setprio(2);
 #pragma unroll
         for (int i = 0; i < 2 * C::CB; ++i) {
             const int ks2 = i / C::CB, cb = i % C::CB;
@@ -404,6 +410,7 @@ __device__ inline void attn_tile(const unsigned char *stage, const LaneAddr la, 
 #pragma unroll
         for (int cb = 0; cb < C::CB; ++cb)
             qs.o[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[U - 1][ks2][cb], __builtin_bit_cast(bf16x8_t, pb[U - 1][ks2]), qs.o[cb], 0, 0, 0);
+    __builtin_amdgcn_s_setprio(0);
     qs.l_run += psum;
 }
 
