@@ -18,6 +18,7 @@ namespace {
 
 constexpr int DT = 512;              // lanes per workgroup
 constexpr int NW = DT / 64;          // wavefronts per workgroup
+typedef float nt_f32x4_t __attribute__((ext_vector_type(4)));
 constexpr int REG_F4 = 16;           // float4 a lane holds when the whole row fits in registers (V <= 32768)
 constexpr int CAND_REG = 1024;       // candidates for the top-k kept in LDS: row in registers ...
 constexpr int CAND_MEM = 8192;       // ... row streamed twice (any V up to MCSD_MAX_VOCAB)
@@ -239,7 +240,11 @@ __global__ __launch_bounds__(DT) void decision_distribution_kernel(MlpDesc mlp, 
 #pragma unroll
         for (int j = 0; j < REG_F4; ++j) {
             const int i = tid * 4 + j * DT * 4;
-            reg[j] = i < V ? *reinterpret_cast<const float4 *>(y + i) : make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
+            reg[j] = make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
+            if (i < V) {                                     // read exactly once: non-temporal, the caches need not keep it
+                const nt_f32x4_t t = __builtin_nontemporal_load(reinterpret_cast<const nt_f32x4_t *>(y + i));
+                reg[j] = make_float4(t.x, t.y, t.z, t.w);
+            }
         }
     }
     // every entry of the row, in the lane's own order (both passes must agree on nothing but the set)
