@@ -28,8 +28,8 @@ N_LAYERS = 32                   # Llama-2-7B
 
 # HBM traffic per launch of the sweep kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (bytes, already
 # scaled by the copy-kernel calibration); filled from the summaries under profiles/.  None = not measured.
-MEASURED_TRAFFIC = {"cfg2": 21_800_000, "cfg4": 664_690_000, "cfg5": 2_213_330_000, "cfg4_b64": 2_742_410_000,
-                    "cfg4_fp8kv": 348_140_000, "cfg5_fp8kv": 1_142_790_000}
+MEASURED_TRAFFIC = {"cfg2": 21_810_000, "cfg4": 664_280_000, "cfg5": 2_213_340_000, "cfg4_b64": 2_742_320_000,
+                    "cfg4_fp8kv": 348_030_000, "cfg5_fp8kv": 1_142_800_000}
 
 
 def log(*a):
@@ -338,7 +338,7 @@ def main():
     ms_per_step = dt / args.steps * 1e3
     value = w.B * st.n / (ms_per_step * 1e-3)
 
-    roof = roofline_of(st, hip, args.kernel_reps)
+    roof = roofline_of(st, hip, args.kernel_reps, warm=args.kernel_reps)
     # the same launch on ONE K/V set over and over: the 16 MiB of a small workload then come from the 256 MB
     # last-level cache, not from HBM.  Reported beside the cold figure (which rotates over n_sets sets), never as it.
     warm_avg = time_kernel(st, hip, binding.KERNEL_ATTN_SWEEP, lambda i: st.attention(0), args.kernel_reps, warm=10)[0]
