@@ -345,6 +345,34 @@ def test_verify_vocabulary_sizes(binding, oracle, H, V, mode):
     _check_verify(binding, oracle, H, w, mode, seed=V, n_new=3)
 
 
+@pytest.mark.parametrize("mode", [DRAFT_INIT, TARGET_INIT])
+def test_verify_largest_vocabulary(binding, oracle, H, mode):
+    """V = MCSD_MAX_VOCAB (262144): 1024 blocks, the streamed-row path at its largest; one entry more is refused."""
+    V = 262144
+    w = scaled(WORKLOADS["cfg1"], B=2, V=V, branching=(3, 2), cfg_id=63, target_sigma=1.5)
+    _check_verify(binding, oracle, H, w, mode, seed=5, n_new=3)
+    vi = verify_inputs(scaled(w, V=8), seed=0, gamma=2, mode=mode, n_new=3)
+    v = binding.slice_mask(binding.build_mask(w.branching), 2)
+    dev = {k: H.dev(vi[k]) for k in ("tokens", "p_target", "q_draft", "u_accept", "u_sample")}
+    out = [torch.zeros(n, dtype=torch.int32, device="cuda") for n in (2 * 2, 2, 2 * 3)]
+    with pytest.raises(binding.McsdError) as e:
+        binding.verify_tree(v, mode, 2, V + 1, dev["tokens"], dev["p_target"], dev["q_draft"], 10 * (V + 1), 10 * (V + 1),
+                            dev["u_accept"], dev["u_sample"], 3, out[0], out[1], out[2],
+                            torch.empty(4096, dtype=torch.uint8, device="cuda"))
+    assert e.value.status == binding.MCSD_EUNSUPPORTED
+
+
+@pytest.mark.parametrize("mode", [DRAFT_INIT, TARGET_INIT])
+def test_verify_deepest_tree(binding, oracle, H, mode):
+    """gamma = MCSD_MAX_LEVELS (32): two chains of 32 tokens; high agreement so that walks go deep."""
+    br = (2,) + (1,) * 31
+    w = scaled(WORKLOADS["cfg1"], B=8, V=300, branching=br, cfg_id=64, target_sigma=1.0, draft_noise_sigma=0.05)
+    alen = _check_verify(binding, oracle, H, w, mode, seed=2, n_new=2)
+    assert alen.max() >= 8, alen                               # some walk really goes deep
+    for g in (1, 17, 31):
+        _check_verify(binding, oracle, H, w, mode, gamma=g, seed=3, n_new=2)
+
+
 def test_verify_many_sequences_and_deep_rejection_chains(binding, oracle, H):
     """Independent draft and target (low acceptance) with wide levels: long chains of residual updates."""
     w = scaled(WORKLOADS["cfg1"], B=64, V=777, branching=(8, 6), cfg_id=61, target_sigma=3.0)
