@@ -9,6 +9,8 @@
  *   - multi-candidate acceptance by recursive rejection sampling, longest-path selection for
  *     target-initialised trees and sampling of the new token(s) (Sec. 2.1, Sec. 3.1, Fig. 1 steps 4-6);
  *   - the update after acceptance: the accepted path's K/V rows join the prefix cache (Fig. 1 step 6).
+ *   - the early-stop decision models that end a draft tree when no level-end node is likely to be accepted
+ *     (Sec. 3.3), and the attention pass for the newest tree level only, grouped-query heads and an fp8 cache.
  *
  * Plain C ABI.  Every pointer is marked HOST or DEVICE.  The library owns only mask handles; every
  * tensor and workspace belongs to the caller.  Device work is enqueued on the caller's HIP stream and
