@@ -242,7 +242,7 @@ void mcsd_oracle_tree_attention(int32_t dtype, int32_t B, int32_t H, int32_t d, 
  * The paper inherits the acceptance rule from speculative sampling (Sec. 2.1) and its multi-candidate
  * extension (Sec. 2.2): a candidate x drawn from the draft distribution q is accepted with probability
  * min(1, p(x)/q(x)); after a rejection the target distribution is replaced by the normalised residual
- * norm(max(p - q, 0)) ("normalized target and draft model's output distribution", Sec. 3.1) and the
+ * norm(max(p - q, 0)) (both models' outputs are normalised distributions, Sec. 3.1) and the
  * next sibling is tried against it; when every sibling is rejected the new token is sampled from the
  * current residual.  Candidates of one context are i.i.d. draws from q (with replacement), so q is not
  * changed by a rejection.
