@@ -100,14 +100,21 @@ AttnPlan make_plan(int dtype, int B, int Hq, int Hkv, int n_rows, int max_prefix
     }
     const long bh = (long)B * pl.units;
     const long tiles_max = (max_prefix + pl.T - 1) / pl.T;
-    // Key splits: enough workgroups for two per compute unit, at least four tiles per split, at most 8 splits
-    // (every split costs a partial result of n rows that is written, written back and folded by the second kernel).
+    // Key splits: enough workgroups for two per compute unit, at least four tiles per split (five with four query
+    // blocks, whose partial result is twice the bytes), at most 8 splits: every split costs a partial result of n
+    // rows that is written, written back and folded by the second kernel.
     long S = (512 + bh - 1) / bh;
-    const long min_tiles = dtype == MCSD_BF16 ? 4 : 1;     // the vector-ALU path is slow per tile: split it all the way
+    // (the vector-ALU path is slow per tile: split it all the way)
+    const long min_tiles = dtype == MCSD_BF16 ? (pl.QBP == 4 ? 5 : 4) : 1;
     if (S > tiles_max / min_tiles) S = tiles_max / min_tiles;
     if (dtype == MCSD_BF16 && S > 8) S = 8;
     if (S < 1) S = 1;
     if (S > 64) S = 64;
+    // One split less when the streaming workgroups alone would have a compute unit each (256) but not together with
+    // the tree's own workgroups: otherwise some compute units get two streaming workgroups and finish last
+    // (measured on B*H = 32, 2048 keys, wide tree: step 0.80 -> 0.74 ms by giving the tree's workgroups the highest
+    // ids instead, 0.69 ms with fewer splits).
+    if (dtype == MCSD_BF16 && S > 2 && bh * S <= 256 && bh * (S + 1) > 256) --S;
     if (const char *ov = getenv("MCSD_ATTN_SPLITS")) {      // tuning override: number of key splits
         const long v = atol(ov);
         if (v >= 1 && v <= 64) S = v;

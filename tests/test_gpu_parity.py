@@ -86,6 +86,19 @@ def test_cfg2_full(binding, oracle, H):
     assert np.array_equal(got, again)
 
 
+@pytest.mark.parametrize("B,Hh,L", [(1, 32, 2048), (2, 16, 2048), (1, 30, 2048), (1, 32, 2000)])
+def test_grids_around_one_workgroup_per_compute_unit(binding, oracle, H, B, Hh, L):
+    """32 (sequence, head) units and 2048 keys: the plan takes 7 key splits + 1 tree workgroup per unit (256
+    workgroups) rather than 8 + 1; unit counts that are and are not multiples of 8; a ragged last tile."""
+    w = scaled(WORKLOADS["cfg2"], B=B, H=Hh, prefix_min=L, prefix_max=L, cfg_id=66)
+    inp = attention_inputs(w, seed=4)
+    ad = H.AttnDevice(inp)
+    v = binding.slice_mask(binding.build_mask(w.branching), w.gamma_max)
+    got = H.run_attention(binding, v, ad, fill=float("nan"))
+    want = oracle.tree_attention(inp, oracle.build_mask(w.branching), v.n_nodes)
+    H.assert_close(got, want, "bf16", f"B{B} H{Hh} L{L}")
+
+
 def test_cfg2_tensors_scaled_variant(binding, oracle, H):
     """Second reading of the recipe: tensors themselves scaled by 1/sqrt(128) (flat softmax)."""
     w = WORKLOADS["cfg2"]
