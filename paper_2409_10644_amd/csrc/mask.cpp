@@ -6,14 +6,17 @@
 
 #include "mcsd_internal.h"
 
-McsdProfileSlot g_mcsd_profile[6] = {};
+McsdProfileSlot g_mcsd_profile[6];      // static storage: both atomics of every slot start as null
 
 extern "C" int mcsd_profile_next(mcsd_kernel_t kernel, void *start_event, void *stop_event)
 {
     if ((int)kernel < 0 || (int)kernel > 5) return MCSD_EINVAL;
     if ((start_event == nullptr) != (stop_event == nullptr)) return MCSD_EINVAL;
-    g_mcsd_profile[(int)kernel].start = (hipEvent_t)start_event;
-    g_mcsd_profile[(int)kernel].stop = (hipEvent_t)stop_event;
+    // disarm first, then publish the stop event before the start event that launches look at
+    McsdProfileSlot &slot = g_mcsd_profile[(int)kernel];
+    slot.start.store(nullptr, std::memory_order_relaxed);
+    slot.stop.store((hipEvent_t)stop_event, std::memory_order_relaxed);
+    slot.start.store((hipEvent_t)start_event, std::memory_order_release);
     return MCSD_OK;
 }
 

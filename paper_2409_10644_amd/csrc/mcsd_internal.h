@@ -29,8 +29,11 @@ struct McsdTreeDesc {
 
 static inline int mcsd_hip_status(hipError_t e) { return e == hipSuccess ? MCSD_OK : MCSD_EHIP; }
 
-// One-shot profiling events per kernel (see mcsd_profile_next); defined in mask.cpp.
-struct McsdProfileSlot { hipEvent_t start, stop; };
+// One-shot profiling events per kernel (see mcsd_profile_next); defined in mask.cpp.  Arming stores `stop` and then
+// `start`; a launch takes `start` with an atomic exchange, so exactly one launch consumes an armed pair even when
+// several host threads launch the same kernel at once.
+#include <atomic>
+struct McsdProfileSlot { std::atomic<hipEvent_t> start, stop; };
 extern McsdProfileSlot g_mcsd_profile[6];
 
 // Launch `kernel` on `st`; if a profiling pair is armed for `which`, bracket the launch with it and disarm.
@@ -38,9 +41,11 @@ template <typename... Args, typename... Actual>
 inline void mcsd_launch(int which, void (*kernel)(Args...), dim3 grid, dim3 block, hipStream_t st, Actual... args)
 {
     McsdProfileSlot &slot = g_mcsd_profile[which];
-    if (slot.start && slot.stop) {
-        hipExtLaunchKernelGGL(kernel, grid, block, 0, st, slot.start, slot.stop, 0, args...);
-        slot.start = slot.stop = nullptr;
+    hipEvent_t start = slot.start.load(std::memory_order_relaxed);
+    if (start) start = slot.start.exchange(nullptr, std::memory_order_acquire);
+    if (start) {
+        hipEvent_t stop = slot.stop.exchange(nullptr, std::memory_order_relaxed);
+        hipExtLaunchKernelGGL(kernel, grid, block, 0, st, start, stop, 0, args...);
     } else {
         hipLaunchKernelGGL(kernel, grid, block, 0, st, args...);
     }

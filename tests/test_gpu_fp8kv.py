@@ -99,13 +99,10 @@ def test_ragged_batch_two_workgroups_per_compute_unit(binding, oracle, H):
     inp = attention_inputs(w, seed=2, lens=lens, kv_fp8=(0.5, 0.5), kv_capacity=704)
     d = Dev(H, inp)
     v = binding.slice_mask(binding.build_mask(br), 4)
+    d.out.fill_(float("nan"))
     got = run(binding, v, d, d, 32, 32)
-    M = oracle.build_mask(br)
-    rows = {(0, 0, 0), (15, 31, v.n_nodes - 1)}
-    while len(rows) < 96:
-        rows.add((int(rng.integers(16)), int(rng.integers(32)), int(rng.integers(v.n_nodes))))
-    for (b, h, i) in sorted(rows):
-        H.assert_close(got[b, h, i], oracle.tree_attention_row_fp8kv(inp, M, v.n_nodes, b, h, i), "bf16", f"row {(b, h, i)}")
+    want = oracle.tree_attention_fp8kv(inp, oracle.build_mask(br), v.n_nodes)
+    H.assert_close(got[:, :, :v.n_nodes], want, "bf16", "fp8kv ragged batch, every element")
 
 
 @pytest.mark.parametrize("Hq,Hkv", [(8, 8), (8, 4), (8, 2), (12, 4), (6, 2)])
