@@ -48,7 +48,7 @@ def attention_algorithmic(w, lens, n):
 class Step:
     """Device-resident inputs of one step and the calls that make it."""
 
-    def __init__(self, name, n_kv_sets, gamma=None, mode=None, seed=0, with_verify=True):
+    def __init__(self, name, n_kv_sets, gamma=None, mode=None, seed=0, with_verify=True, tuning=None):
         import numpy as np
         import torch
         from paper_2409_10644_amd import binding
@@ -71,8 +71,10 @@ class Step:
         self.mask = binding.build_mask(w.branching)                   # once, at gamma_max
         self.view = binding.slice_mask(self.mask, self.gamma)
         self.n = self.view.n_nodes
-        ws_bytes = binding.tree_attention_workspace(w.B, w.H, w.d, self.n, self.cap)
-        self.ws = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device="cuda")
+        self.tuning = tuning                                          # None: the library's own plan
+        ws_bytes = binding.tree_attention_tuned_workspace(tuning, 0, w.B, w.H, w.H, w.d, self.n, 0, self.cap)
+        self.ws_bytes = ws_bytes
+        self.ws = binding.new_workspace(ws_bytes)
         vi = self.vi
         self.p, self.q = H.dev(vi["p_target"]), H.dev(vi["q_draft"])
         self.tokens, self.ua, self.us = H.dev(vi["tokens"]), H.dev(vi["u_accept"]), H.dev(vi["u_sample"])
@@ -86,8 +88,13 @@ class Step:
 
     def attention(self, layer):
         ad, w, b = self.layers[layer % len(self.layers)], self.w, self.binding
-        b.tree_attention(self.view, ad.code, w.B, w.H, w.d, ad.q, ad.kt, ad.vt, ad.node_stride, ad.kp, ad.vp, ad.base,
-                         ad.lens, ad.head_stride, self.cap, ad.scale, ad.out, self.ws)
+        if self.tuning is None:
+            b.tree_attention(self.view, ad.code, w.B, w.H, w.d, ad.q, ad.kt, ad.vt, ad.node_stride, ad.kp, ad.vp, ad.base,
+                             ad.lens, ad.head_stride, self.cap, ad.scale, ad.out, self.ws)
+        else:
+            b.tree_attention_tuned(self.tuning, self.view, ad.code, 0, 1.0, 1.0, w.B, w.H, w.H, w.d, 0, ad.q, ad.kt, ad.vt,
+                                   ad.node_stride, ad.kp, ad.vp, ad.base, ad.lens, ad.head_stride, self.cap, ad.scale,
+                                   ad.out, self.ws)
 
     def verify(self):
         w, b, vi = self.w, self.binding, self.vi
@@ -274,6 +281,11 @@ def main():
     ap.add_argument("--no-fp8kv", action="store_true", help="skip the fp8 prefix-cache variants of cfg4 / cfg5")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--eager", action="store_true", help="launch the step's kernels one by one instead of replaying a HIP graph")
+    ap.add_argument("--key-splits", type=int, default=0,
+                    help="measurement sweeps: key splits of the headline workload's attention (0 = the library's plan)")
+    ap.add_argument("--stages", type=int, default=0, help="measurement sweeps: LDS stages of the bf16 K/V ring (0 = the library's plan)")
+    ap.add_argument("--fold-kernel", action="store_true",
+                    help="measurement sweeps: fold the key splits' partial results in a second kernel")
     ap.add_argument("--traffic-calibration", action="store_true",
                     help="only run a 1 GiB device-to-device copy a few times (the known-size kernel that the "
                          "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run are scaled by) and exit")
@@ -301,7 +313,10 @@ def main():
     w = WORKLOADS[w_name]
     kv_bytes = w.B * w.H * w.prefix_max * w.d * (2 if w.dtype == "bf16" else 4) * 2
     n_sets = N_LAYERS if kv_bytes * N_LAYERS <= (8 << 30) else max(1, min(N_LAYERS, (2 << 30) // kv_bytes))
-    st = Step(w_name, n_sets)
+    tuning = None
+    if args.key_splits or args.fold_kernel or args.stages:
+        tuning = binding.AttentionTuning(key_splits=args.key_splits, fold=1 if args.fold_kernel else 0, stages=args.stages)
+    st = Step(w_name, n_sets, tuning=tuning)
     alpha = st.check_against_oracle()
     log(f"[bench] {w_name}: outputs verified against the oracle (mean accepted length {alpha:.2f})")
 
@@ -344,7 +359,7 @@ def main():
     warm_avg = time_kernel(st, hip, binding.KERNEL_ATTN_SWEEP, lambda i: st.attention(0), args.kernel_reps, warm=10)[0]
     roof["warm_cache_launch_us"] = round(warm_avg * 1e3, 2)
     m_avg = time_kernel(st, hip, binding.KERNEL_ATTN_MERGE, lambda i: st.attention(i), args.kernel_reps)[0] \
-        if st.ws.numel() > 256 else 0.0
+        if st.ws_bytes > 0 and args.fold_kernel else 0.0
     v_avg = time_kernel(st, hip, binding.KERNEL_VERIFY_WALK, lambda i: st.verify(), args.kernel_reps)[0]
     out = {
         "metric": "verified tree-tokens/s, whole verification step (32 tree-attention layers + acceptance)",
@@ -472,7 +487,7 @@ def main():
             vg = binding.slice_mask(binding.build_mask(wq.branching), wq.gamma_max)
             n = vg.n_nodes
             wsb = binding.tree_attention_gqa_workspace(wq.B, wq.H, Hkv, wq.d, n, 0, int(wq.prefix_max))
-            wsg = torch.empty(max(wsb, 256), dtype=torch.uint8, device="cuda")
+            wsg = binding.new_workspace(wsb)
 
             def gcall(i):
                 binding.tree_attention_gqa(vg, 1, wq.B, wq.H, Hkv, wq.d, 0, aq.q, ak.kt, ak.vt, ak.node_stride, ak.kp, ak.vp,
@@ -526,8 +541,7 @@ def main():
                 out8 = torch.zeros_like(q8)
                 v8 = binding.slice_mask(binding.build_mask(w8.branching), w8.gamma_max)
                 n8 = v8.n_nodes
-                ws8 = torch.empty(max(binding.tree_attention_fp8kv_workspace(w8.B, w8.H, w8.H, n8, 0, cap), 256),
-                                  dtype=torch.uint8, device="cuda")
+                ws8 = binding.new_workspace(binding.tree_attention_fp8kv_workspace(w8.B, w8.H, w8.H, n8, 0, cap))
 
                 def fcall(i):
                     binding.tree_attention_fp8kv(v8, w8.B, w8.H, w8.H, 0, q8, kt8, vt8, inp8["node_stride"],

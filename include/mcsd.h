@@ -16,7 +16,9 @@
  * tensor and workspace belongs to the caller.  Device work is enqueued on the caller's HIP stream and
  * the calls return without synchronising (mcsd_build_mask excepted).  Functions return MCSD_OK (0) or a
  * negative status; they never abort, throw or print.  Arguments are validated on the host before any
- * launch; on error nothing has been enqueued and no output has been touched.
+ * launch; on error nothing has been enqueued and no output has been touched.  The calls read no environment
+ * variable and keep no mutable state besides the mask handles and the one-shot arming of mcsd_profile_next, so
+ * calls on distinct streams (with distinct workspaces) may be made from several host threads at once.
  *
  * Tree convention.  A tree is the tuple of per-level branching factors (b_1 .. b_G), e.g. (4,2,2,1) or the
  * target-initialised (2,4,3,1,1) of Sec. 4.1.  Level l has N_l = b_1*...*b_l nodes; nodes are numbered
@@ -108,10 +110,18 @@ void mcsd_free_mask(mcsd_mask_t *mask);
  * Limits: d in {64, 128}; 1 <= n_nodes <= MCSD_ATTN_MAX_NODES; softmax_scale finite and > 0; all tensor
  * base addresses 16-byte aligned; node_stride*d and head_stride and seq_base multiples of 8 elements.
  * workspace: DEVICE, at least mcsd_tree_attention_workspace(...) bytes (0 when the keys are not split: then it may
- * be NULL), 256-byte aligned; holds the partial results of the key splits; contents need not be initialised and
- * are not meaningful afterwards.  Calls that share a workspace must be ordered on one stream.  Inputs are never
- * modified.
+ * be NULL), 256-byte aligned; holds the partial results of the key splits and the arrival counters with which the
+ * workgroup that finishes a (sequence, head) last folds them.  It must have been prepared with mcsd_workspace_init
+ * once (and again after anything else wrote to it); every call leaves it prepared.  A call that finds a workspace
+ * that was never prepared fills the output rows it owns with NaN.  Calls that share a workspace must be ordered on
+ * one stream.  Inputs are never modified.
  * ------------------------------------------------------------------------------------------------- */
+
+/* Prepares `workspace` (DEVICE, 256-byte aligned, workspace_bytes long) for the tree-attention entry points: one small
+ * fill kernel on the stream (no memset node, so the call may be captured into a HIP graph).  Sizes too small to serve
+ * any call that needs a workspace (below 66 KiB) are accepted and left alone. */
+int mcsd_workspace_init(void *workspace, size_t workspace_bytes, void *hip_stream);
+
 size_t mcsd_tree_attention_workspace(int32_t B, int32_t H, int32_t d, int32_t n_nodes, int32_t max_prefix);
 
 int mcsd_tree_attention(const mcsd_mask_view_t *mask, mcsd_dtype_t dtype, int32_t B, int32_t H, int32_t d,
@@ -177,6 +187,34 @@ size_t mcsd_tree_attention_fp8kv_workspace(int32_t B, int32_t H_q, int32_t H_kv,
 int mcsd_tree_attention_fp8kv(const mcsd_mask_view_t *mask, int32_t B, int32_t H_q, int32_t H_kv, int32_t row_begin,
                               const void *q, const void *k_tree, const void *v_tree, int64_t node_stride,
                               const void *k_prefix_fp8, const void *v_prefix_fp8, float k_scale, float v_scale,
+                              const int64_t *seq_base_dev, const int32_t *prefix_lens_dev, int64_t head_stride,
+                              int32_t max_prefix, float softmax_scale, void *out, void *workspace,
+                              size_t workspace_bytes, void *hip_stream);
+
+/* ---------------------------------------------------------------------------------------------------
+ * The same operation (Sec. 2.2) with the launch plan in the caller's hands, for measurement sweeps and tests; one entry
+ * point covers what the four above do (prefix_fp8 != 0: the prefix cache holds E4M3 bytes and k_scale / v_scale
+ * apply, d = 128, dtype MCSD_BF16; otherwise the scales are ignored).  The plan is a function of the shape arguments
+ * and of *tuning only: the library reads no environment variable and keeps no state between the workspace query and
+ * the call, so the same struct must be given to both.  tuning == NULL means all zeros.  Results do not depend on the
+ * plan beyond the order in which partial results are added.  MCSD_EINVAL for values outside the ranges below.
+ * ------------------------------------------------------------------------------------------------- */
+typedef struct {
+    int32_t key_splits;     /* 0: the library chooses; 1..64: workgroups that share the prefix keys of one (sequence, head) */
+    int32_t natural_order;  /* 0: the library chooses; 1: never reorder the workgroups of a ragged batch by length */
+    int32_t fold;           /* 0: the library chooses; 1: always fold the key splits' partial results in a second kernel */
+    int32_t stages;         /* 0: the library chooses; 2 or 4: LDS stages of the bf16 sweep's K/V ring (4 needs a compute
+                               unit per workgroup and trees of more than 32 rows; ignored where it cannot apply) */
+} mcsd_attention_tuning_t;
+
+size_t mcsd_tree_attention_tuned_workspace(const mcsd_attention_tuning_t *tuning, int32_t prefix_fp8, int32_t B,
+                                           int32_t H_q, int32_t H_kv, int32_t d, int32_t n_nodes, int32_t row_begin,
+                                           int32_t max_prefix);
+
+int mcsd_tree_attention_tuned(const mcsd_attention_tuning_t *tuning, const mcsd_mask_view_t *mask, mcsd_dtype_t dtype,
+                              int32_t prefix_fp8, float k_scale, float v_scale, int32_t B, int32_t H_q, int32_t H_kv,
+                              int32_t d, int32_t row_begin, const void *q, const void *k_tree, const void *v_tree,
+                              int64_t node_stride, const void *k_prefix, const void *v_prefix,
                               const int64_t *seq_base_dev, const int32_t *prefix_lens_dev, int64_t head_stride,
                               int32_t max_prefix, float softmax_scale, void *out, void *workspace,
                               size_t workspace_bytes, void *hip_stream);
@@ -253,7 +291,10 @@ int mcsd_verify_tree_sampling(const mcsd_mask_view_t *mask, mcsd_mode_t mode, mc
  * prefix_lens_dev    : DEVICE int32 [B], read and updated in place
  * out_ids_dev        : DEVICE int32 [B][gamma + n_append];  out_n_ids_dev: DEVICE int32 [B]
  * Node ids outside 0..n_nodes-1 and lengths outside 0..gamma are skipped / clamped, never dereferenced.
- * Limits: 1 <= n_layers <= MCSD_COMMIT_MAX_LAYERS per call; d*sizeof(element) a multiple of 16; tensor base
+ * ONE call must cover all layers of the model: the call advances prefix_lens and writes the ids, so a second call
+ * for further layers would append the same path again at the advanced lengths.  A model deeper than
+ * MCSD_COMMIT_MAX_LAYERS layers is MCSD_EUNSUPPORTED rather than served in pieces.
+ * Limits: 1 <= n_layers <= MCSD_COMMIT_MAX_LAYERS; d*sizeof(element) a multiple of 16; tensor base
  * addresses 16-byte aligned; node_stride*d, head_stride and seq_base multiples of 8 elements.
  * Two launches on the stream: the copies, then the lengths and ids (so prefix_lens is updated in place).
  * ------------------------------------------------------------------------------------------------- */
@@ -279,8 +320,10 @@ int mcsd_commit_path(const mcsd_mask_view_t *mask, mcsd_dtype_t dtype, int32_t B
  *                                  (0 ln 0 = 0); k + 1 inputs
  *   mcsd_early_stop_hidden       : type 1, input the draft model's hidden state of the newest token
  * An n-layer MLP is n affine maps with ReLU between them and a logistic sigmoid after the last (Sec. 3.3 gives the
- * layer counts, two for type 2 and three for type 1, and nothing else; weights are the caller's).  Dot products
- * are accumulated in binary64; the entropy uses an fp32 logarithm per entry and a binary64 sum.
+ * layer counts, two for type 2 and three for type 1, and nothing else; weights are the caller's).  The networks
+ * are evaluated in fp32: fused multiply-adds whose partial sums are combined as a tree, within about 1e-6 of an
+ * evaluation in binary64 (a probability closer than that to beta may fall on the other side of it); the entropy
+ * uses an fp32 logarithm per entry and a binary64 sum.
  *
  * mlp             : HOST struct; weight[l] / bias[l] are DEVICE fp32 arrays, weight[l] row-major
  *                   [width[l+1]][width[l]] (one row per output unit), width[0] = inputs, width[n_layers] = 1
@@ -315,7 +358,9 @@ int mcsd_early_stop_hidden(const mcsd_mlp_t *mlp, int32_t B, int32_t W, const fl
  * Measurement aid (not part of the method).  Arms a one-shot pair of HIP events (hipEvent_t, created by the
  * caller with timing enabled) for one of the library's kernels: the next launch of that kernel by the calling
  * process is bracketed by them, so hipEventElapsedTime(start, stop) is that kernel's own execution time on
- * the device.  The arming is consumed by that launch.  Passing NULL events disarms.  Not thread-safe.
+ * the device.  The arming is consumed by exactly one launch, also when several host threads launch that kernel at
+ * once (the slots are atomic); two threads arming the same kernel at the same time is the caller's to avoid.
+ * Passing NULL events disarms.
  * ------------------------------------------------------------------------------------------------- */
 typedef enum { MCSD_KERNEL_ATTN_SWEEP = 0, MCSD_KERNEL_ATTN_MERGE = 1, MCSD_KERNEL_VERIFY_WALK = 2,
                MCSD_KERNEL_COMMIT_COPY = 3, MCSD_KERNEL_STREAM_READ = 4, MCSD_KERNEL_DECISION = 5 } mcsd_kernel_t;

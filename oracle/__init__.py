@@ -19,20 +19,34 @@ _LIB = os.path.join(_HERE, "libmcsd_oracle.so")
 _lib = None
 
 
-def build(force: bool = False) -> str:
-    """Compile the oracle with gcc: -O2, contraction off (explicit fma only), OpenMP over sequences/heads."""
-    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
-        cmd = ["gcc", "-O2", "-std=c11", "-ffp-contract=off", "-fno-fast-math", "-fopenmp", "-fPIC", "-shared",
-               "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm"]
+_LIB_SAN = os.path.join(_HERE, "libmcsd_oracle_san.so")
+
+
+def build(force: bool = False, sanitize: bool = False) -> str:
+    """Compile the oracle with gcc: -O2, contraction off (explicit fma only), OpenMP over sequences/heads.
+    sanitize=True builds a second library, -O1 with AddressSanitizer and UndefinedBehaviorSanitizer (any finding
+    aborts), which a process loads instead when MCSD_ORACLE_SANITIZED=1 is set and the sanitizer runtime is
+    preloaded (see tests/test_sanitized_host_code.py)."""
+    lib = _LIB_SAN if sanitize else _LIB
+    if force or not os.path.exists(lib) or os.path.getmtime(lib) < os.path.getmtime(_SRC):
+        opt = ["-O1", "-g", "-fno-omit-frame-pointer", "-fsanitize=address,undefined", "-fno-sanitize-recover=all"] \
+            if sanitize else ["-O2"]
+        cmd = ["gcc", *opt, "-std=c11", "-ffp-contract=off", "-fno-fast-math", "-fopenmp", "-fPIC", "-shared",
+               "-Wall", "-Wextra", "-o", lib, _SRC, "-lm"]
         subprocess.run(cmd, check=True)
-    return _LIB
+    return lib
+
+
+def sanitizer_runtime() -> str:
+    """Path of gcc's AddressSanitizer runtime, to be preloaded by a process that loads the sanitized library."""
+    return subprocess.run(["gcc", "-print-file-name=libasan.so"], check=True, capture_output=True, text=True).stdout.strip()
 
 
 def _load():
     global _lib
     if _lib is None:
-        build()
-        L = C.CDLL(_LIB)
+        sanitized = os.environ.get("MCSD_ORACLE_SANITIZED") == "1"
+        L = C.CDLL(build(sanitize=sanitized))
         vp, i32, i64, f64 = C.c_void_p, C.c_int32, C.c_int64, C.c_double
         L.mcsd_oracle_level_sizes.restype = i64
         L.mcsd_oracle_level_sizes.argtypes = [vp, i32, vp]

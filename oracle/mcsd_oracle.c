@@ -426,7 +426,11 @@ static int verify_tree_impl(int32_t mode, int without_replacement, const int32_t
         int32_t *path = (int32_t *)malloc(sizeof(int32_t) * (size_t)(G + 1));
         int32_t *best_path = (int32_t *)malloc(sizeof(int32_t) * (size_t)(G + 1));
         double *qz = (double *)malloc(sizeof(double) * (size_t)P);
-        if (!r || !term || !best_term || !path || !best_path || !qz) { rc = -2; goto done; }
+        if (!r || !term || !best_term || !path || !best_path || !qz) {
+#pragma omp atomic write
+            rc = -2;
+            goto done;
+        }
         const int32_t *tok_b = tokens + (int64_t)b * N;
         const float *p_b = p + (int64_t)b * p_bstride, *q_b = q + (int64_t)b * q_bstride;
         const float *ua_b = u_acc + (int64_t)b * N;

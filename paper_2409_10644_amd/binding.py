@@ -21,7 +21,8 @@ EXPORTS = ["mcsd_strerror", "mcsd_build_mask", "mcsd_slice_mask", "mcsd_free_mas
            "mcsd_tree_attention_gqa_workspace", "mcsd_tree_attention_gqa",
            "mcsd_tree_attention_fp8kv_workspace", "mcsd_tree_attention_fp8kv",
            "mcsd_verify_tree_workspace", "mcsd_verify_tree", "mcsd_verify_tree_sampling", "mcsd_commit_path", "mcsd_early_stop_distribution",
-           "mcsd_early_stop_hidden", "mcsd_profile_next", "mcsd_stream_read"]
+           "mcsd_early_stop_hidden", "mcsd_profile_next", "mcsd_stream_read", "mcsd_workspace_init",
+           "mcsd_tree_attention_tuned_workspace", "mcsd_tree_attention_tuned"]
 DECISION_MAX_K, MLP_MAX_LAYERS, MLP_MAX_WIDTH, MLP_MAX_INPUTS = 16, 3, 512, 8192
 
 
@@ -39,6 +40,11 @@ class Mlp(C.Structure):
     """mcsd_mlp_t"""
     _fields_ = [("n_layers", C.c_int32), ("width", C.c_int32 * (MLP_MAX_LAYERS + 1)),
                 ("weight", C.c_void_p * MLP_MAX_LAYERS), ("bias", C.c_void_p * MLP_MAX_LAYERS)]
+
+
+class AttentionTuning(C.Structure):
+    """mcsd_attention_tuning_t"""
+    _fields_ = [("key_splits", C.c_int32), ("natural_order", C.c_int32), ("fold", C.c_int32), ("stages", C.c_int32)]
 
 
 class McsdError(RuntimeError):
@@ -107,6 +113,14 @@ def _load() -> C.CDLL:
     lib.mcsd_early_stop_hidden.argtypes = [C.POINTER(Mlp), i32, i32, vp, i64, i64, C.c_float, vp, vp, vp]
     lib.mcsd_stream_read.restype = C.c_int
     lib.mcsd_stream_read.argtypes = [vp, C.c_size_t, vp, i32, vp]
+    lib.mcsd_workspace_init.restype = C.c_int
+    lib.mcsd_workspace_init.argtypes = [vp, sz, vp]
+    lib.mcsd_tree_attention_tuned_workspace.restype = sz
+    lib.mcsd_tree_attention_tuned_workspace.argtypes = [C.POINTER(AttentionTuning), i32, i32, i32, i32, i32, i32, i32, i32]
+    lib.mcsd_tree_attention_tuned.restype = C.c_int
+    lib.mcsd_tree_attention_tuned.argtypes = [C.POINTER(AttentionTuning), C.POINTER(MaskView), C.c_int, i32, C.c_float,
+                                              C.c_float, i32, i32, i32, i32, i32, vp, vp, vp, i64, vp, vp, vp, vp, i64,
+                                              i32, C.c_float, vp, vp, sz, vp]
     return lib
 
 
@@ -156,6 +170,8 @@ class Mask:
 
 def build_mask(branching: Sequence[int], gamma_max: Optional[int] = None) -> Mask:
     g = len(branching) if gamma_max is None else int(gamma_max)
+    if g > len(branching):
+        raise McsdError(MCSD_EINVAL, "mcsd_build_mask (gamma_max beyond the branching vector)")
     arr = (C.c_int32 * max(len(branching), 1))(*[int(x) for x in branching])
     handle = C.c_void_p()
     _check(lib.mcsd_build_mask(arr, g, C.byref(handle)), "mcsd_build_mask")
@@ -171,6 +187,43 @@ def slice_mask(mask: Mask, gamma: int) -> MaskView:
 
 def free_mask(mask: Mask) -> None:
     mask.close()
+
+
+def workspace_init(workspace: Optional[torch.Tensor], stream=None) -> None:
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib.mcsd_workspace_init(_ptr(workspace), ws_bytes, _stream(stream)), "mcsd_workspace_init")
+
+
+def new_workspace(nbytes: int, stream=None) -> torch.Tensor:
+    """A device buffer of at least nbytes (and at least 256) bytes, prepared with mcsd_workspace_init."""
+    ws = torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device="cuda")
+    workspace_init(ws, stream)
+    return ws
+
+
+def _tuning_ref(tuning: Optional[AttentionTuning]):
+    return None if tuning is None else C.byref(tuning)
+
+
+def tree_attention_tuned_workspace(tuning: Optional[AttentionTuning], prefix_fp8: int, B: int, H_q: int, H_kv: int, d: int,
+                                   n_nodes: int, row_begin: int, max_prefix: int) -> int:
+    return int(lib.mcsd_tree_attention_tuned_workspace(_tuning_ref(tuning), prefix_fp8, B, H_q, H_kv, d, n_nodes,
+                                                       row_begin, max_prefix))
+
+
+def tree_attention_tuned(tuning: Optional[AttentionTuning], view: MaskView, dtype: int, prefix_fp8: int, k_scale: float,
+                         v_scale: float, B: int, H_q: int, H_kv: int, d: int, row_begin: int, q: torch.Tensor,
+                         k_tree: torch.Tensor, v_tree: torch.Tensor, node_stride: int, k_prefix: Optional[torch.Tensor],
+                         v_prefix: Optional[torch.Tensor], seq_base_dev: torch.Tensor, prefix_lens_dev: torch.Tensor,
+                         head_stride: int, max_prefix: int, softmax_scale: float, out: torch.Tensor,
+                         workspace: Optional[torch.Tensor], stream=None) -> None:
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    st = lib.mcsd_tree_attention_tuned(_tuning_ref(tuning), C.byref(view), dtype, prefix_fp8, k_scale, v_scale, B, H_q,
+                                       H_kv, d, row_begin, _ptr(q), _ptr(k_tree), _ptr(v_tree), node_stride,
+                                       _ptr(k_prefix), _ptr(v_prefix), _ptr(seq_base_dev), _ptr(prefix_lens_dev),
+                                       head_stride, max_prefix, softmax_scale, _ptr(out), _ptr(workspace), ws_bytes,
+                                       _stream(stream))
+    _check(st, "mcsd_tree_attention_tuned")
 
 
 def tree_attention_workspace(B: int, H: int, d: int, n_nodes: int, max_prefix: int) -> int:

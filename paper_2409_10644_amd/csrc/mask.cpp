@@ -8,6 +8,60 @@
 
 McsdProfileSlot g_mcsd_profile[6];      // static storage: both atomics of every slot start as null
 
+// ---------------------------------------------------------------------------------------------------
+// Which workgroups share a level-2 cache.  The GPU is made of several accelerator dies, each with its own L2;
+// a launch deals its workgroups to the dies round-robin by workgroup id.  The tree-attention sweep folds the
+// partial results of its key splits through the L2 when the workgroups of one (sequence, head) sit on one die,
+// so the dealing is checked once per device, here, on the hardware: every workgroup of a small launch reports the
+// id of its die.  Result: the number of dies when workgroup i runs on die i % dies for all i, else 0 (the sweep
+// then leaves the fold to its second kernel).
+// ---------------------------------------------------------------------------------------------------
+namespace {
+constexpr int XCC_PROBE_WGS = 256;
+__global__ void xcc_probe_kernel(int32_t *out)
+{
+    unsigned x;
+    asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(x));
+    if (threadIdx.x == 0) out[blockIdx.x] = (int32_t)(x & 15u);
+}
+std::atomic<int> g_xcc_of_device[64];       // 0 = not probed yet, -1 = probed: dealing not as expected, else dies
+}  // namespace
+
+int mcsd_xcc_count(int device)
+{
+    if (device < 0 || device >= 64) return 0;
+    const int v = g_xcc_of_device[device].load(std::memory_order_relaxed);
+    return v > 0 ? v : 0;
+}
+
+// Called by mcsd_build_mask with `device` current (that call synchronises and allocates anyway).
+static void probe_xcc_once(int device)
+{
+    if (device < 0 || device >= 64 || g_xcc_of_device[device].load(std::memory_order_relaxed) != 0) return;
+    int result = -1;
+    int32_t *dev = nullptr;
+    int32_t host[XCC_PROBE_WGS];
+    if (hipMalloc((void **)&dev, sizeof(host)) == hipSuccess) {
+        bool ok = true;
+        int dies = 0;
+        for (int rep = 0; rep < 2 && ok; ++rep) {             // twice: the dealing must not depend on what ran before
+            hipLaunchKernelGGL(xcc_probe_kernel, dim3(XCC_PROBE_WGS), dim3(64), 0, 0, dev);
+            ok = hipGetLastError() == hipSuccess && hipMemcpy(host, dev, sizeof(host), hipMemcpyDeviceToHost) == hipSuccess;
+            if (!ok) break;
+            int mx = 0;
+            for (int i = 0; i < XCC_PROBE_WGS; ++i) mx = host[i] > mx ? host[i] : mx;
+            const int n = mx + 1;
+            ok = (n == 1 || n == 2 || n == 4 || n == 8) && (rep == 0 || n == dies);
+            for (int i = 0; i < XCC_PROBE_WGS && ok; ++i) ok = host[i] == i % n;
+            dies = n;
+        }
+        if (ok) result = dies;
+        (void)hipFree(dev);
+    }
+    (void)hipGetLastError();
+    g_xcc_of_device[device].store(result, std::memory_order_relaxed);
+}
+
 extern "C" int mcsd_profile_next(mcsd_kernel_t kernel, void *start_event, void *stop_event)
 {
     if ((int)kernel < 0 || (int)kernel > 5) return MCSD_EINVAL;
@@ -98,6 +152,7 @@ extern "C" int mcsd_build_mask(const int32_t *branching, int32_t gamma_max, mcsd
         mcsd_free_mask(m);
         return MCSD_ENOMEM;
     }
+    probe_xcc_once(m->device);
     m->bits_dev = (uint64_t *)m->dev_block;
     m->parent_dev = (int32_t *)((char *)m->dev_block + bits_bytes);
     if (hipMemcpy(m->bits_dev, m->bits_host, (size_t)N * W * sizeof(uint64_t), hipMemcpyHostToDevice) != hipSuccess ||

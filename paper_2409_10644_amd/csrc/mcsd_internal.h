@@ -29,6 +29,10 @@ struct McsdTreeDesc {
 
 static inline int mcsd_hip_status(hipError_t e) { return e == hipSuccess ? MCSD_OK : MCSD_EHIP; }
 
+// Accelerator dies (each with its own L2) of `device` when the hardware deals workgroup i of a launch to die
+// i % dies, as established by a probe launch in mcsd_build_mask; 0 when unknown or not so.  Defined in mask.cpp.
+int mcsd_xcc_count(int device);
+
 // One-shot profiling events per kernel (see mcsd_profile_next); defined in mask.cpp.  Arming stores `stop` and then
 // `start`; a launch takes `start` with an atomic exchange, so exactly one launch consumes an armed pair even when
 // several host threads launch the same kernel at once.

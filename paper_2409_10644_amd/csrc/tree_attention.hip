@@ -47,6 +47,10 @@ struct AttnParams {
     int32_t bph;      // 32-row query blocks per query head in a workgroup (1, 2 or 4); QBP = bph * hpw
     int32_t chunks;   // grp / hpw: workgroup units per key/value head
     int32_t pair_cus; // > 0: compute units; the grid has more workgroups than that and no separate tree workgroup (see the kernel)
+    int32_t xcc;      // accelerator dies the hardware deals workgroup ids to round-robin (>= 1)
+    int32_t fold;     // 1: the workgroup of a (sequence, unit) that finishes last folds the partial results itself
+    unsigned long long *ctr;   // fold == 1: arrival counter of unit u at ctr[u * CTR_STRIDE], zero before and after every launch
+    const uint32_t *ws_tag;    // fold == 1: first word of the workspace, WS_TAG once prepared
     int32_t row0;     // first query row: rows row0 .. n-1 are computed (keys are always all n tree nodes)
     int32_t max_prefix;
     int64_t node_stride, head_stride;
@@ -61,6 +65,15 @@ struct AttnParams {
     float *part_l;    // [B*H][SP][n]   sum of exp2((s - m) * c)
 };
 
+// Workspace of a call with split keys: [tag word, 256 bytes] [arrival counters, 64 KiB] [part_m] [part_l] [part_o].
+// mcsd_workspace_init writes the tag and zeroes the counters; every launch leaves them as it found them.
+constexpr uint32_t WS_TAG = 0x4d435344u;
+constexpr size_t WS_HEADER = 256, WS_CTR_BYTES = 64 * 1024;
+// One arrival counter per 128-byte line: atomics on one line are served one after the other (~85 ns each on this
+// machine), so counters of different (sequence, unit) pairs that share a line would queue behind each other.
+constexpr int CTR_STRIDE = 16;                          // in 8-byte counters
+constexpr int FOLD_MAX_PARTIALS = 16;     // the in-kernel fold keeps one weight per partial result in registers
+
 struct AttnPlan {
     int bph, hpw, chunks;  // bf16: query blocks per head, heads per workgroup, units per kv head (see AttnParams)
     int units;             // workgroup units per sequence: kv heads x chunks (bf16), query heads (fp32)
@@ -69,11 +82,33 @@ struct AttnPlan {
     int S;     // key splits of the prefix
     int G;     // workgroups per (b,h): S, or S + 1 when the bf16 sweep gives the tree's own keys a workgroup of their own
     int NS;    // LDS stages of the bf16 sweep
+    int xcc;   // dies the workgroup ids are dealt to (1 when unknown: no renumbering)
+    int pair_cus;  // see AttnParams
+    int fold;  // 1: folded inside the sweep kernel through the L2 its workgroups share
 };
 
 __host__ __device__ inline int tile_keys_bf16(int QBP) { return QBP == 1 ? 128 : 64; }   // == SweepCfg::T
 
-AttnPlan make_plan(int dtype, int B, int Hq, int Hkv, int n_rows, int max_prefix, bool f8 = false)
+// Compute units and accelerator dies of the current device (asked once per device; concurrent first calls store
+// the same values).
+void device_shape(int &n_cus, int &n_xcc)
+{
+    static std::atomic<int> cus_of_device[64];
+    n_cus = -1;
+    n_xcc = 0;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return;
+    n_cus = cus_of_device[dev].load(std::memory_order_relaxed);
+    if (n_cus == 0) {
+        int v = 0;
+        n_cus = hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0 ? v : -1;
+        cus_of_device[dev].store(n_cus, std::memory_order_relaxed);
+    }
+    n_xcc = mcsd_xcc_count(dev);
+}
+
+AttnPlan make_plan(int dtype, int B, int Hq, int Hkv, int n_rows, int max_prefix, bool f8 = false,
+                   const mcsd_attention_tuning_t *tune = nullptr)
 {
     AttnPlan pl;
     const int grp = Hq / Hkv;
@@ -115,17 +150,35 @@ AttnPlan make_plan(int dtype, int B, int Hq, int Hkv, int n_rows, int max_prefix
     // (measured on B*H = 32, 2048 keys, wide tree: step 0.80 -> 0.74 ms by giving the tree's workgroups the highest
     // ids instead, 0.69 ms with fewer splits).
     if (dtype == MCSD_BF16 && S > 2 && bh * S <= 256 && bh * (S + 1) > 256) --S;
-    if (const char *ov = getenv("MCSD_ATTN_SPLITS")) {      // tuning override: number of key splits
-        const long v = atol(ov);
-        if (v >= 1 && v <= 64) S = v;
-    }
-    pl.NS = f8 ? 4 : 2;                                     // LDS stages, two workgroups per compute unit
+    if (tune && tune->key_splits >= 1 && tune->key_splits <= 64) S = tune->key_splits;   // the caller's choice
+    pl.NS = f8 ? 4 : 2;                                     // LDS stages (bf16: see below)
     pl.S = (int)S;
     // With split keys the tree's own tiles (masked, through registers) would lengthen one split's critical path:
     // they get a workgroup of their own, which costs one more partial result.  Only when all workgroups are
     // resident at once (two per compute unit): the hardware dispatcher does not rebalance long workgroups that
     // start behind short ones.
     pl.G = (dtype == MCSD_BF16 && S > 1 && bh * (S + 1) <= 512) ? (int)S + 1 : (int)S;
+    int n_cus, n_xcc;
+    device_shape(n_cus, n_xcc);
+    // Ragged grids larger than the chip are ordered by length inside the kernel (see there)
+    pl.pair_cus = 0;
+    if (dtype == MCSD_BF16 && pl.G == pl.S && (long)B * pl.S <= 256 && n_cus > 0 && bh * pl.S > n_cus &&
+        !(tune && tune->natural_order))
+        pl.pair_cus = n_cus;
+    // bf16 tiles: two stages and two workgroups per compute unit.  Four stages (64-key tiles only: a 128-key tile is
+    // 64 KB) exist for measurement: on launches that have a compute unit per workgroup anyway three tiles in flight
+    // instead of one were expected to help and do not (cfg2: 7.5 against 6.2 us until the partial results are stored;
+    // a bare ring of direct-to-LDS loads needs ~5 us for 128 KB per workgroup on 128 compute units at any depth: a
+    // cold burst of this size is bound by the memory system's ramp-up, not by the bytes a compute unit has in flight).
+    if (tune && !f8 && tune->stages == 4 && dtype == MCSD_BF16 && pl.QBP != 1) pl.NS = 4;
+    pl.xcc = n_xcc > 0 ? n_xcc : 8;        // unknown: the renumbering is then only a guess that may help locality
+    // The fold runs inside the sweep when all workgroups of one (sequence, unit) share a die's L2: the dealing of
+    // workgroup ids to dies is known, and the kernel's numbering keeps a unit's workgroups at one id modulo dies.
+    const long total = bh * pl.G;
+    bool same_die = n_xcc == 1 || (n_xcc > 1 && total % n_xcc == 0 && bh % n_xcc == 0);
+    if (pl.pair_cus > 0) same_die = n_xcc == 1 || (n_xcc > 1 && pl.units % n_xcc == 0 && pl.pair_cus % n_xcc == 0);
+    pl.fold = dtype == MCSD_BF16 && pl.S > 1 && same_die && pl.G <= FOLD_MAX_PARTIALS &&
+              (size_t)bh * CTR_STRIDE * sizeof(unsigned long long) <= WS_CTR_BYTES && !(tune && tune->fold == 1);
     return pl;
 }
 
@@ -432,6 +485,101 @@ __device__ inline void attn_tile(const unsigned char *stage, const LaneAddr la, 
     qs.l_run += psum;
 }
 
+// The fold of the partial results of one query block by one wavefront of the workgroup that arrived last (see the
+// end of the sweep kernel): rows = the wavefront's 32 queries (lane ln, half g), columns = the 32-column blocks
+// kg, kg + KG, ..  ro / rm / rl describe the unit's partial O (fragment order), maxima and denominators and end after
+// the last partial result in use: a load beyond it returns zero without touching memory, so nothing below branches
+// on the number of partial results and all loads of a round are in flight together.
+// A round: NSLOT partial results x two of the lane's float4 positions (j = 2 jp, 2 jp + 1) of a column block.  The
+// rounds of a column block are (jp 0, first group), [(jp 0, second group),] (jp 1, ...): an accumulator lives across
+// the groups of one jp and its result is stored after every round (with two groups the first store of a position is
+// overwritten by the complete one: same lane, same address, program order).  The loads of the next round are issued
+// before this one is added up (two register buffers); a round beyond the last loads from beyond the end, i.e. nothing.
+// Partial results are added in slot order whoever arrived last, so the result is reproducible.
+// Nothing here may spill: a workgroup's scratch memory is cold at this point, every first touch a trip to HBM (a
+// variant that spilled its weights took 9.7 us for five partial results, against 3).
+template <int D, int QBP, int KG, int NSLOT>
+__device__ __attribute__((always_inline)) inline void fold_partials(const __amdgpu_buffer_rsrc_t ro, const __amdgpu_buffer_rsrc_t rm,
+                                     const __amdgpu_buffer_rsrc_t rl, const int n_active, const int kg, const int g,
+                                     const int ln, const float cm, __bf16 *orow, f32x4_t *wlds)
+{
+    constexpr int CB = D / 32;
+    constexpr int NW = NSLOT == 8 ? FOLD_MAX_PARTIALS : NSLOT;      // partial results this variant can hold
+    constexpr int SLOT_BYTES = QBP * 32 * D * 4;
+    float wgt[NW], lw[NW];
+#pragma unroll
+    for (int i = 0; i < NW; ++i) {
+        wgt[i] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rm, (i * QBP * 32 + ln) * 4, 0, 1));
+        lw[i] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rl, (i * QBP * 32 + ln) * 4, 0, 1));
+    }
+    const int ngrp = NSLOT == 8 && n_active > NSLOT ? 2 : 1;
+    const int rounds = ((CB - kg + KG - 1) / KG) * 2 * ngrp;        // even
+    typedef u32x4_t Round[NSLOT][2];
+    auto issue = [&](Round &buf, int r) {
+        const int grp = r % ngrp, jp = (r / ngrp) & 1, cb = kg + (r / (2 * ngrp)) * KG;
+        int off = (((cb * 4 + jp * 2) * 2 + g) * 32 + ln) * 16 + grp * NSLOT * SLOT_BYTES;
+        if (r >= rounds) off = 0x40000000;                          // (uniform select) beyond every workspace
+#pragma unroll
+        for (int i = 0; i < NSLOT; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j) buf[i][j] = __builtin_amdgcn_raw_buffer_load_b128(ro, off + j * 1024 + i * SLOT_BYTES, 0, 1);
+    };
+    Round bufA, bufB;
+    issue(bufA, 0);
+    float M = -INFINITY;
+#pragma unroll
+    for (int i = 0; i < NW; ++i) M = fmaxf(M, i < n_active ? wgt[i] : -INFINITY);
+    float den = 0.f;
+#pragma unroll
+    for (int i = 0; i < NW; ++i) {
+        // 0 for a split that saw no visible key, and beyond the partial results in use
+        wgt[i] = i < n_active ? fast_exp2((wgt[i] - M) * cm) : 0.f;
+        den = fmaf(wgt[i], lw[i], den);
+    }
+    const float inv = 1.f / den;
+    // Two groups: a round picks its group at run time, and registers cannot be indexed at run time, so the weights
+    // go through LDS (the ring is free by now), written and read back by the same lane.
+    if constexpr (NSLOT == 8) {
+#pragma unroll
+        for (int q4 = 0; q4 < NW / 4; ++q4)
+            wlds[q4 * 256] = (f32x4_t){wgt[4 * q4], wgt[4 * q4 + 1], wgt[4 * q4 + 2], wgt[4 * q4 + 3]};
+    }
+    f32x4_t acc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
+    auto add_up = [&](Round &buf, int r) {
+        const int grp = r % ngrp, jp = (r / ngrp) & 1, cb = kg + (r / (2 * ngrp)) * KG;
+        float w[NSLOT];
+        if constexpr (NSLOT == 8) {
+            const f32x4_t wa = wlds[(2 * grp) * 256], wb = wlds[(2 * grp + 1) * 256];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) { w[i] = wa[i]; w[4 + i] = wb[i]; }
+        } else {
+#pragma unroll
+            for (int i = 0; i < NSLOT; ++i) w[i] = wgt[i];
+        }
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            if (grp == 0) acc[j] = (f32x4_t){0.f, 0.f, 0.f, 0.f};   // a new position starts from zero (a select)
+#pragma unroll
+            for (int i = 0; i < NSLOT; ++i) acc[j] += w[i] * __builtin_bit_cast(f32x4_t, buf[i][j]);   // slot order
+            bf16x4_t v;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) v[e] = (__bf16)(acc[j][e] * inv);
+            *(bf16x4_t *)(orow + cb * 32 + 8 * (2 * jp + j) + 4 * g) = v;
+        }
+    };
+#pragma unroll 1
+    for (int r = 0; r < rounds; r += 2) {
+        issue(bufB, r + 1);
+        __builtin_amdgcn_sched_barrier(0);
+        add_up(bufA, r);
+        __builtin_amdgcn_sched_barrier(0);
+        issue(bufA, r + 2);
+        __builtin_amdgcn_sched_barrier(0);
+        add_up(bufB, r + 1);
+        __builtin_amdgcn_sched_barrier(0);
+    }
+}
+
 template <int D, int QBP, int NS, bool F8 = false>
 __global__ __launch_bounds__((SweepCfg<D, QBP, NS, F8>::THREADS)) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void tree_attn_bf16_kernel(const AttnParams p)
@@ -439,11 +587,12 @@ void tree_attn_bf16_kernel(const AttnParams p)
     using C = SweepCfg<D, QBP, NS, F8>;
     __shared__ __attribute__((aligned(1024))) unsigned char ring[C::LDS_BYTES];
 
-    // Workgroup ids are dealt round-robin to the 8 XCDs: renumber so that the key splits of one (sequence, head),
-    // which read the same Q, tree K/V and mask rows and write neighbouring partial results, share one XCD's L2.
+    // Workgroup ids are dealt round-robin to the accelerator dies (p.xcc of them, each with its own L2): renumber so
+    // that the key splits of one (sequence, head), which read the same Q, tree K/V and mask rows, write neighbouring
+    // partial results and fold them through that L2, share one die.
     const int total = gridDim.x;
     int wg = blockIdx.x;
-    if (p.G > 1 && p.pair_cus == 0 && (total & 7) == 0) wg = (wg & 7) * (total >> 3) + (wg >> 3);
+    if (p.G > 1 && p.pair_cus == 0 && p.xcc > 1 && total % p.xcc == 0) wg = (wg % p.xcc) * (total / p.xcc) + wg / p.xcc;
     int s = wg % p.G;
     int bhi = wg / p.G;
     const int tid = threadIdx.x, lane = tid & 63;
@@ -470,8 +619,14 @@ void tree_attn_bf16_kernel(const AttnParams p)
             s_cls_at[rank] = tid;
         }
         __syncthreads();
-        const int r = total > 2 * p.pair_cus ? wg                               // longest first
-                                             : (wg < p.pair_cus ? wg : total + p.pair_cus - 1 - wg);   // rank i with rank total-1-i
+        // rank i with rank total-1-i, in groups of p.xcc ids so that a rank keeps its id modulo the number of dies
+        // (every key split of a (sequence, unit) then runs on the die of unit % dies)
+        int r = wg;                                                              // longest first
+        if (total <= 2 * p.pair_cus && wg >= p.pair_cus) {
+            const int w2 = wg - p.pair_cus, cnt = total - p.pair_cus;
+            r = (cnt % p.xcc == 0) ? p.pair_cus + (cnt / p.xcc - 1 - w2 / p.xcc) * p.xcc + w2 % p.xcc
+                                   : total + p.pair_cus - 1 - wg;
+        }
         const int cls = s_cls_at[r / p.H];
         s = cls % p.S;
         bhi = (cls / p.S) * p.H + r % p.H;
@@ -483,6 +638,7 @@ void tree_attn_bf16_kernel(const AttnParams p)
 
     int L = p.lens[b];
     L = L < 0 ? 0 : (L > p.max_prefix ? p.max_prefix : L);
+    const uint32_t ws_tag = p.fold ? p.ws_tag[0] : WS_TAG;  // (read early: needed only at the very end)
     const int tiles_b = (L + C::T - 1) / C::T;
     const int tps = p.tps;                                  // fixed per call: short sequences use fewer splits
     const bool sep = p.G > p.S;                             // the tree's own keys have a workgroup of their own
@@ -627,16 +783,18 @@ void tree_attn_bf16_kernel(const AttnParams p)
             step(it, S0(), std::false_type());
         }
         } else {
-        // A ring of NS stages keeps NS-1 tiles in flight; used for fp8 tiles, which are half the bytes.  (For bf16
-        // tiles it needs all of a compute unit's LDS; measured on the latency-bound launches that have a compute
-        // unit per workgroup anyway, it was slower than the double buffer: 13.2 against 11.8 us.)  Tile t lives in
-        // stage t % NS.  A step waits until at most NS-2 later tiles are outstanding while such tiles are still being
-        // requested, and for everything once the requests have run out (the last NS-1 tiles).
-        auto step = [&](auto stage, bool more) {
+        // A ring of NS stages keeps NS-1 tiles in flight: fp8 tiles (half the bytes); bf16 tiles only on request (it
+        // needs a compute unit's LDS per workgroup and measured slower, see make_plan).  Tile t lives in stage
+        // t % NS.  A step waits until exactly the tiles requested after its own are still outstanding: NS-2 of them in
+        // the steady state, fewer at the end.
+        auto step = [&](auto stage, int it) {
             constexpr int ST = decltype(stage)::value;
-            if (more) MCSD_WAIT_VMCNT((NS - 2) * C::DPT); else MCSD_WAIT_VMCNT(0);
+            const int later = min(n_hot - it - 1, NS - 2);        // uniform
+            if (later >= 2) MCSD_WAIT_VMCNT(2 * C::DPT);
+            else if (later == 1) MCSD_WAIT_VMCNT(C::DPT);
+            else MCSD_WAIT_VMCNT(0);
             __builtin_amdgcn_s_barrier();
-            if (more) issue_tile(std::integral_constant<int, (ST + NS - 1) % NS>());
+            if (it + NS - 1 < n_hot) issue_tile(std::integral_constant<int, (ST + NS - 1) % NS>());
             attn_tile<D, QBP, NS, 0, F8, F8>(ring + ST * C::TILE, la, qs, c_pre, g, all_keys, vs_pre);
         };
         static_assert(NS == 4, "the step sequence below is unrolled for four stages");
@@ -648,10 +806,10 @@ void tree_attn_bf16_kernel(const AttnParams p)
         if (1 < n_hot) issue_tile(std::integral_constant<int, 1 % NS>());
         if (2 < n_hot) issue_tile(std::integral_constant<int, 2 % NS>());
         for (int it = 0; it < n_hot; it += 4) {
-            step(std::integral_constant<int, 0>(), it + 3 < n_hot);
-            if (it + 1 < n_hot) step(std::integral_constant<int, 1 % NS>(), it + 4 < n_hot);
-            if (it + 2 < n_hot) step(std::integral_constant<int, 2 % NS>(), it + 5 < n_hot);
-            if (it + 3 < n_hot) step(std::integral_constant<int, 3 % NS>(), it + 6 < n_hot);
+            step(std::integral_constant<int, 0>(), it);
+            if (it + 1 < n_hot) step(std::integral_constant<int, 1 % NS>(), it + 1);
+            if (it + 2 < n_hot) step(std::integral_constant<int, 2 % NS>(), it + 2);
+            if (it + 3 < n_hot) step(std::integral_constant<int, 3 % NS>(), it + 3);
         }
         }
         MCSD_WAIT_VMCNT(0);
@@ -797,6 +955,63 @@ void tree_attn_bf16_kernel(const AttnParams p)
             p.part_l[prow] = l_tot;
         }
     }
+    if (!p.fold) return;                                   // a second kernel folds
+
+    // ---- fold inside this kernel: the workgroup of this (sequence, unit) that arrives last does it ----
+    // All workgroups of the unit run on one die (see the numbering above), so their partial results meet in that
+    // die's L2: a store is there once it is acknowledged (the vector L1 writes through), and the loads below go past
+    // the L1.  Nobody waits for anybody: a workgroup counts itself in and leaves unless it is the last.  The
+    // counter also records, per die, how many of the arrivals ran there, so a launch that was not dealt to the
+    // dies as the host established shows up here and poisons the output instead of folding stale data.
+    auto store_nan = [&]() {
+        if (kg != 0 || qrow >= p.n) return;
+        __bf16 *o = (__bf16 *)p.out + (bh_q * p.node_stride + qrow) * D;
+        bf16x4_t v;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = (__bf16)__builtin_nanf("");
+#pragma unroll
+        for (int cb = 0; cb < C::CB; ++cb)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) *(bf16x4_t *)(o + cb * 32 + 8 * j + 4 * g) = v;
+    };
+    if (ws_tag != WS_TAG) {                                // workspace never prepared: its counters mean nothing
+        store_nan();
+        return;
+    }
+    __shared__ unsigned long long s_prev;
+    unsigned die;
+    asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(die));
+    die &= 7u;
+    // This wavefront's partial stores have reached the L2 once the vector-memory counter is back at zero.  (A release
+    // fence of workgroup scope does not wait for it: within a workgroup the shared L1 already orders them.)
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    if (tid == 0)
+        s_prev = __hip_atomic_fetch_add(p.ctr + bh * CTR_STRIDE, 1ull + (1ull << (8 + 7 * die)), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __syncthreads();
+    const unsigned long long prev = s_prev;
+    if ((int)(prev & 0xffu) + 1 != n_active) return;       // someone else arrives later
+    if (tid == 0) __hip_atomic_store(p.ctr + bh * CTR_STRIDE, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // as it was found
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+    if ((int)((prev >> (8 + 7 * die)) & 0x7fu) + 1 != n_active) {   // an arrival from another die
+        store_nan();
+        return;
+    }
+    if (qrow >= p.n) return;
+    // Every wavefront folds its query block's rows for its share of the columns (32-column blocks kg, kg + KG, ..),
+    // all partial results read back in slot order, its own included: the result does not depend on who came last.
+    // Loads go through buffer descriptors that end after the last partial result in use (see fold_partials).
+    const __amdgpu_buffer_rsrc_t ro = __builtin_amdgcn_make_buffer_rsrc(
+        (void *)(p.part_o + (bh * p.SP) * (int64_t)(QBP * 32 * D) + qb * 32 * D), 0, (int)(n_active * QBP * 32 * D * 4), 0x00027000);
+    const __amdgpu_buffer_rsrc_t rm = __builtin_amdgcn_make_buffer_rsrc(
+        (void *)(p.part_m + bh * p.SP * (QBP * 32) + qb * 32), 0, (int)(n_active * QBP * 32 * 4), 0x00027000);
+    const __amdgpu_buffer_rsrc_t rl = __builtin_amdgcn_make_buffer_rsrc(
+        (void *)(p.part_l + bh * p.SP * (QBP * 32) + qb * 32), 0, (int)(n_active * QBP * 32 * 4), 0x00027000);
+    __bf16 *orow = (__bf16 *)p.out + (bh_q * p.node_stride + qrow) * D;
+    // as few slots per round as hold the partial results: a load beyond the end still costs its turn in the L1
+    if (n_active <= 3) fold_partials<D, QBP, C::KG, 3>(ro, rm, rl, n_active, kg, g, ln, cm, orow, (f32x4_t *)ring + tid);
+    else if (n_active <= 5) fold_partials<D, QBP, C::KG, 5>(ro, rm, rl, n_active, kg, g, ln, cm, orow, (f32x4_t *)ring + tid);
+    else fold_partials<D, QBP, C::KG, 8>(ro, rm, rl, n_active, kg, g, ln, cm, orow, (f32x4_t *)ring + tid);
 }
 
 // Folds the partial results of the key splits of the bf16 sweep.  One thread per 4 output columns of one query;
@@ -903,7 +1118,7 @@ __global__ __launch_bounds__(256) void tree_attn_f32_kernel(const AttnParams p)
     const float *kp = (const float *)p.kp + pre0;
     const float *vp = (const float *)p.vp + pre0;
 
-    for (int idx = tid; idx < p.n * D; idx += 256) sQ[idx / D][idx % D] = q[idx];
+    for (int idx = p.row0 * D + tid; idx < p.n * D; idx += 256) sQ[idx / D][idx % D] = q[idx];   // rows below row0 are not read
     if (tid < NMAX) { sM[tid] = -INFINITY; sL[tid] = 0.f; }     // running maximum / denominator of every row
     float acc[NR];
 #pragma unroll
@@ -1045,7 +1260,7 @@ __global__ __launch_bounds__(256) void tree_attn_merge_kernel(const AttnParams p
 
 size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
-// workspace: [part_m] [part_l] [part_o]; nothing when the keys are not split
+// workspace: [tag] [counters] [part_m] [part_l] [part_o]; nothing when the keys are not split
 size_t partial_rows(const AttnPlan &pl, int dtype, int B, int n)
 {
     // per workgroup unit and split; bf16 path: whole 32-row query blocks in register-fragment order; fp32 path: n rows
@@ -1056,7 +1271,14 @@ size_t workspace_bytes_for(const AttnPlan &pl, int dtype, int B, int d, int n)
 {
     if (pl.S == 1) return 0;
     const size_t rows = partial_rows(pl, dtype, B, n);
-    return 2 * align256(rows * sizeof(float)) + align256(rows * d * sizeof(float));
+    return WS_HEADER + WS_CTR_BYTES + 2 * align256(rows * sizeof(float)) + align256(rows * d * sizeof(float));
+}
+
+// Prepares a workspace: tag word, zero counters.  One thread per 16 bytes of the header and counter area.
+__global__ __launch_bounds__(256) void workspace_init_kernel(uint4 *ws)
+{
+    const unsigned i = blockIdx.x * 256 + threadIdx.x;
+    if (i < (WS_HEADER + WS_CTR_BYTES) / 16) ws[i] = make_uint4(i == 0 ? WS_TAG : 0u, 0u, 0u, 0u);
 }
 
 template <int D, int QBP, int NS, bool F8 = false>
@@ -1077,10 +1299,10 @@ template <int D>
 hipError_t launch_bf16(const AttnParams &p, const AttnPlan &pl, hipStream_t st)
 {
     if (pl.QBP == 1) launch_sweep<D, 1, 2>(p, pl, st);
-    else if (pl.QBP == 2) launch_sweep<D, 2, 2>(p, pl, st);
-    else launch_sweep<D, 4, 2>(p, pl, st);
+    else if (pl.QBP == 2) { if (pl.NS == 4) launch_sweep<D, 2, 4>(p, pl, st); else launch_sweep<D, 2, 2>(p, pl, st); }
+    else { if (pl.NS == 4) launch_sweep<D, 4, 4>(p, pl, st); else launch_sweep<D, 4, 2>(p, pl, st); }
     hipError_t e = hipGetLastError();
-    if (e != hipSuccess || pl.S == 1) return e;
+    if (e != hipSuccess || pl.S == 1 || pl.fold) return e;
     if (pl.QBP == 1) launch_merge<D, 1>(p, pl, st);
     else if (pl.QBP == 2) launch_merge<D, 2>(p, pl, st);
     else launch_merge<D, 4>(p, pl, st);
@@ -1093,7 +1315,7 @@ hipError_t launch_fp8kv(const AttnParams &p, const AttnPlan &pl, hipStream_t st)
     if (pl.QBP == 2) launch_sweep<128, 2, 4, true>(p, pl, st);
     else launch_sweep<128, 4, 4, true>(p, pl, st);
     hipError_t e = hipGetLastError();
-    if (e != hipSuccess || pl.S == 1) return e;
+    if (e != hipSuccess || pl.S == 1 || pl.fold) return e;
     AttnParams pm = p;
     pm.c = 1.f;
     if (pl.QBP == 2) launch_merge<128, 2>(pm, pl, st);
@@ -1112,59 +1334,23 @@ hipError_t launch_f32(const AttnParams &p, const AttnPlan &pl, hipStream_t st)
     return hipGetLastError();
 }
 
-}  // namespace
-
-extern "C" size_t mcsd_tree_attention_gqa_workspace(int32_t B, int32_t H_q, int32_t H_kv, int32_t d, int32_t n_nodes,
-                                                    int32_t row_begin, int32_t max_prefix)
+size_t workspace_query(const mcsd_attention_tuning_t *tune, bool f8, int32_t B, int32_t H_q, int32_t H_kv, int32_t d,
+                       int32_t n_nodes, int32_t row_begin, int32_t max_prefix)
 {
     if (B < 1 || H_q < 1 || H_kv < 1 || H_q % H_kv != 0 || (d != 64 && d != 128) || n_nodes < 1 ||
-        n_nodes > MCSD_ATTN_MAX_NODES || max_prefix < 0 || row_begin < 0 || row_begin >= n_nodes)
+        n_nodes > MCSD_ATTN_MAX_NODES || max_prefix < 0 || row_begin < 0 || row_begin >= n_nodes || (f8 && d != 128))
         return 0;
+    const AttnPlan a = make_plan(MCSD_BF16, B, H_q, H_kv, n_nodes - row_begin, max_prefix, f8, tune);
+    const size_t wa = workspace_bytes_for(a, MCSD_BF16, B, d, n_nodes);
+    if (f8) return wa;
     // the larger of the two dtypes' needs, so one buffer serves both
-    const AttnPlan a = make_plan(MCSD_BF16, B, H_q, H_kv, n_nodes - row_begin, max_prefix);
-    const AttnPlan f = make_plan(MCSD_F32, B, H_q, H_kv, n_nodes - row_begin, max_prefix);
-    const size_t wa = workspace_bytes_for(a, MCSD_BF16, B, d, n_nodes), wf = workspace_bytes_for(f, MCSD_F32, B, d, n_nodes);
+    const AttnPlan f = make_plan(MCSD_F32, B, H_q, H_kv, n_nodes - row_begin, max_prefix, false, tune);
+    const size_t wf = workspace_bytes_for(f, MCSD_F32, B, d, n_nodes);
     return wa > wf ? wa : wf;
 }
 
-extern "C" size_t mcsd_tree_attention_rows_workspace(int32_t B, int32_t H, int32_t d, int32_t n_nodes,
-                                                     int32_t row_begin, int32_t max_prefix)
-{
-    return mcsd_tree_attention_gqa_workspace(B, H, H, d, n_nodes, row_begin, max_prefix);
-}
-
-extern "C" size_t mcsd_tree_attention_workspace(int32_t B, int32_t H, int32_t d, int32_t n_nodes, int32_t max_prefix)
-{
-    return mcsd_tree_attention_gqa_workspace(B, H, H, d, n_nodes, 0, max_prefix);
-}
-
-extern "C" int mcsd_tree_attention(const mcsd_mask_view_t *mask, mcsd_dtype_t dtype, int32_t B, int32_t H, int32_t d,
-                                   const void *q, const void *k_tree, const void *v_tree, int64_t node_stride,
-                                   const void *k_prefix, const void *v_prefix, const int64_t *seq_base_dev,
-                                   const int32_t *prefix_lens_dev, int64_t head_stride, int32_t max_prefix,
-                                   float softmax_scale, void *out, void *workspace, size_t workspace_bytes,
-                                   void *hip_stream)
-{
-    return mcsd_tree_attention_rows(mask, dtype, B, H, d, 0, q, k_tree, v_tree, node_stride, k_prefix, v_prefix,
-                                    seq_base_dev, prefix_lens_dev, head_stride, max_prefix, softmax_scale, out,
-                                    workspace, workspace_bytes, hip_stream);
-}
-
-extern "C" int mcsd_tree_attention_rows(const mcsd_mask_view_t *mask, mcsd_dtype_t dtype, int32_t B, int32_t H,
-                                        int32_t d, int32_t row_begin, const void *q, const void *k_tree,
-                                        const void *v_tree, int64_t node_stride, const void *k_prefix,
-                                        const void *v_prefix, const int64_t *seq_base_dev,
-                                        const int32_t *prefix_lens_dev, int64_t head_stride, int32_t max_prefix,
-                                        float softmax_scale, void *out, void *workspace, size_t workspace_bytes,
-                                        void *hip_stream)
-{
-    return mcsd_tree_attention_gqa(mask, dtype, B, H, H, d, row_begin, q, k_tree, v_tree, node_stride, k_prefix,
-                                   v_prefix, seq_base_dev, prefix_lens_dev, head_stride, max_prefix, softmax_scale, out,
-                                   workspace, workspace_bytes, hip_stream);
-}
-
-namespace {
-int attention_call(const mcsd_mask_view_t *mask, mcsd_dtype_t dtype, bool f8, float k_scale, float v_scale, int32_t B,
+int attention_call(const mcsd_attention_tuning_t *tune, const mcsd_mask_view_t *mask, mcsd_dtype_t dtype, bool f8,
+                   float k_scale, float v_scale, int32_t B,
                    int32_t H_q, int32_t H_kv, int32_t d, int32_t row_begin, const void *q, const void *k_tree,
                    const void *v_tree, int64_t node_stride, const void *k_prefix, const void *v_prefix,
                    const int64_t *seq_base_dev, const int32_t *prefix_lens_dev, int64_t head_stride, int32_t max_prefix,
@@ -1177,6 +1363,9 @@ int attention_call(const mcsd_mask_view_t *mask, mcsd_dtype_t dtype, bool f8, fl
     if (dtype != MCSD_F32 && dtype != MCSD_BF16) return MCSD_EINVAL;
     if (B < 1 || H < 1 || B > 65535 || H > 65535 || max_prefix < 0) return MCSD_EINVAL;
     if (max_prefix > 0 && (!k_prefix || !v_prefix)) return MCSD_EINVAL;
+    if (tune && (tune->key_splits < 0 || tune->key_splits > 64 || tune->fold < 0 || tune->fold > 1 ||
+                 (tune->stages != 0 && tune->stages != 2 && tune->stages != 4)))
+        return MCSD_EINVAL;
     const int32_t n = mask->n_nodes;
     if (n < 1 || node_stride < n || head_stride < 0) return MCSD_EINVAL;
     if (row_begin < 0 || row_begin >= n) return MCSD_EINVAL;
@@ -1190,7 +1379,7 @@ int attention_call(const mcsd_mask_view_t *mask, mcsd_dtype_t dtype, bool f8, fl
     if (align & 15) return MCSD_EINVAL;
     if (((node_stride * d) & 7) || (head_stride & (f8 ? 15 : 7))) return MCSD_EINVAL;   // 16-byte rows and heads
 
-    const AttnPlan pl = make_plan(dtype, B, H_q, H_kv, n - row_begin, max_prefix, f8);
+    const AttnPlan pl = make_plan(dtype, B, H_q, H_kv, n - row_begin, max_prefix, f8, tune);
     if ((int64_t)pl.G * pl.units * B > 0x7fffffff) return MCSD_EUNSUPPORTED;           // one-dimensional grid
     const size_t need = workspace_bytes_for(pl, dtype, B, d, n);
     if (need > 0 && (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 255))) return MCSD_EWORKSPACE;
@@ -1206,30 +1395,20 @@ int attention_call(const mcsd_mask_view_t *mask, mcsd_dtype_t dtype, bool f8, fl
     p.k_scale = f8 ? k_scale : 1.f;
     p.v_scale = f8 ? v_scale : 1.f;
     p.S = pl.S; p.G = pl.G; p.SP = pl.G;
-    p.pair_cus = 0;
-    // compute units of the current device, asked once per device (concurrent first calls store the same value)
-    static std::atomic<int> cus_of_device[64];
-    int n_cus = -1, dev = 0;
-    if (hipGetDevice(&dev) == hipSuccess && dev >= 0 && dev < 64) {
-        n_cus = cus_of_device[dev].load(std::memory_order_relaxed);
-        if (n_cus == 0) {
-            int v = 0;
-            n_cus = hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0 ? v : -1;
-            cus_of_device[dev].store(n_cus, std::memory_order_relaxed);
-        }
-    }
-    if (dtype == MCSD_BF16 && pl.G == pl.S && (long)B * pl.S <= 256) {
-        if (n_cus > 0 && (long)B * pl.units * pl.S > n_cus) p.pair_cus = n_cus;
-        if (const char *ov = getenv("MCSD_ATTN_PAIRING")) {  // tuning override: 0 keeps the natural order
-            if (atol(ov) == 0) p.pair_cus = 0;
-        }
-    }
+    p.pair_cus = pl.pair_cus;
+    p.xcc = pl.xcc;
+    p.fold = pl.fold;
     p.tps = (int32_t)((((int64_t)max_prefix + pl.T - 1) / pl.T + pl.S - 1) / pl.S);
     if (p.tps < 1) p.tps = 1;
     char *w = (char *)workspace;
     p.part_o = p.part_m = p.part_l = nullptr;
+    p.ctr = nullptr;
+    p.ws_tag = nullptr;
     if (pl.S > 1) {
         const size_t rows = partial_rows(pl, dtype, B, n);
+        p.ws_tag = (const uint32_t *)w;
+        p.ctr = (unsigned long long *)(w + WS_HEADER);
+        w += WS_HEADER + WS_CTR_BYTES;
         p.part_m = (float *)w;
         w += align256(rows * sizeof(float));
         p.part_l = (float *)w;
@@ -1243,7 +1422,74 @@ int attention_call(const mcsd_mask_view_t *mask, mcsd_dtype_t dtype, bool f8, fl
     else e = d == 128 ? launch_f32<128>(p, pl, st) : launch_f32<64>(p, pl, st);
     return mcsd_hip_status(e);
 }
+
 }  // namespace
+
+extern "C" int mcsd_workspace_init(void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    if (!workspace && workspace_bytes > 0) return MCSD_EINVAL;
+    if ((uintptr_t)workspace & 255) return MCSD_EINVAL;
+    if (workspace_bytes < WS_HEADER + WS_CTR_BYTES) return MCSD_OK;    // too small to serve a call that needs one
+    const unsigned n16 = (unsigned)((WS_HEADER + WS_CTR_BYTES) / 16);
+    hipLaunchKernelGGL(workspace_init_kernel, dim3((n16 + 255) / 256), dim3(256), 0, (hipStream_t)hip_stream, (uint4 *)workspace);
+    return mcsd_hip_status(hipGetLastError());
+}
+
+extern "C" size_t mcsd_tree_attention_gqa_workspace(int32_t B, int32_t H_q, int32_t H_kv, int32_t d, int32_t n_nodes,
+                                                    int32_t row_begin, int32_t max_prefix)
+{
+    return workspace_query(nullptr, false, B, H_q, H_kv, d, n_nodes, row_begin, max_prefix);
+}
+
+extern "C" size_t mcsd_tree_attention_rows_workspace(int32_t B, int32_t H, int32_t d, int32_t n_nodes,
+                                                     int32_t row_begin, int32_t max_prefix)
+{
+    return workspace_query(nullptr, false, B, H, H, d, n_nodes, row_begin, max_prefix);
+}
+
+extern "C" size_t mcsd_tree_attention_workspace(int32_t B, int32_t H, int32_t d, int32_t n_nodes, int32_t max_prefix)
+{
+    return workspace_query(nullptr, false, B, H, H, d, n_nodes, 0, max_prefix);
+}
+
+extern "C" size_t mcsd_tree_attention_fp8kv_workspace(int32_t B, int32_t H_q, int32_t H_kv, int32_t n_nodes,
+                                                      int32_t row_begin, int32_t max_prefix)
+{
+    return workspace_query(nullptr, true, B, H_q, H_kv, 128, n_nodes, row_begin, max_prefix);
+}
+
+extern "C" size_t mcsd_tree_attention_tuned_workspace(const mcsd_attention_tuning_t *tuning, int32_t prefix_fp8, int32_t B,
+                                                      int32_t H_q, int32_t H_kv, int32_t d, int32_t n_nodes,
+                                                      int32_t row_begin, int32_t max_prefix)
+{
+    if (tuning && (tuning->key_splits < 0 || tuning->key_splits > 64)) return 0;
+    return workspace_query(tuning, prefix_fp8 != 0, B, H_q, H_kv, d, n_nodes, row_begin, max_prefix);
+}
+
+extern "C" int mcsd_tree_attention(const mcsd_mask_view_t *mask, mcsd_dtype_t dtype, int32_t B, int32_t H, int32_t d,
+                                   const void *q, const void *k_tree, const void *v_tree, int64_t node_stride,
+                                   const void *k_prefix, const void *v_prefix, const int64_t *seq_base_dev,
+                                   const int32_t *prefix_lens_dev, int64_t head_stride, int32_t max_prefix,
+                                   float softmax_scale, void *out, void *workspace, size_t workspace_bytes,
+                                   void *hip_stream)
+{
+    return attention_call(nullptr, mask, dtype, false, 1.f, 1.f, B, H, H, d, 0, q, k_tree, v_tree, node_stride, k_prefix,
+                          v_prefix, seq_base_dev, prefix_lens_dev, head_stride, max_prefix, softmax_scale, out, workspace,
+                          workspace_bytes, hip_stream);
+}
+
+extern "C" int mcsd_tree_attention_rows(const mcsd_mask_view_t *mask, mcsd_dtype_t dtype, int32_t B, int32_t H,
+                                        int32_t d, int32_t row_begin, const void *q, const void *k_tree,
+                                        const void *v_tree, int64_t node_stride, const void *k_prefix,
+                                        const void *v_prefix, const int64_t *seq_base_dev,
+                                        const int32_t *prefix_lens_dev, int64_t head_stride, int32_t max_prefix,
+                                        float softmax_scale, void *out, void *workspace, size_t workspace_bytes,
+                                        void *hip_stream)
+{
+    return attention_call(nullptr, mask, dtype, false, 1.f, 1.f, B, H, H, d, row_begin, q, k_tree, v_tree, node_stride,
+                          k_prefix, v_prefix, seq_base_dev, prefix_lens_dev, head_stride, max_prefix, softmax_scale, out,
+                          workspace, workspace_bytes, hip_stream);
+}
 
 extern "C" int mcsd_tree_attention_gqa(const mcsd_mask_view_t *mask, mcsd_dtype_t dtype, int32_t B, int32_t H_q,
                                        int32_t H_kv, int32_t d, int32_t row_begin, const void *q, const void *k_tree,
@@ -1253,19 +1499,9 @@ extern "C" int mcsd_tree_attention_gqa(const mcsd_mask_view_t *mask, mcsd_dtype_
                                        float softmax_scale, void *out, void *workspace, size_t workspace_bytes,
                                        void *hip_stream)
 {
-    return attention_call(mask, dtype, false, 1.f, 1.f, B, H_q, H_kv, d, row_begin, q, k_tree, v_tree, node_stride,
-                          k_prefix, v_prefix, seq_base_dev, prefix_lens_dev, head_stride, max_prefix, softmax_scale, out,
-                          workspace, workspace_bytes, hip_stream);
-}
-
-extern "C" size_t mcsd_tree_attention_fp8kv_workspace(int32_t B, int32_t H_q, int32_t H_kv, int32_t n_nodes,
-                                                      int32_t row_begin, int32_t max_prefix)
-{
-    if (B < 1 || H_q < 1 || H_kv < 1 || H_q % H_kv != 0 || n_nodes < 1 || n_nodes > MCSD_ATTN_MAX_NODES ||
-        max_prefix < 0 || row_begin < 0 || row_begin >= n_nodes)
-        return 0;
-    const AttnPlan a = make_plan(MCSD_BF16, B, H_q, H_kv, n_nodes - row_begin, max_prefix, true);
-    return workspace_bytes_for(a, MCSD_BF16, B, 128, n_nodes);
+    return attention_call(nullptr, mask, dtype, false, 1.f, 1.f, B, H_q, H_kv, d, row_begin, q, k_tree, v_tree,
+                          node_stride, k_prefix, v_prefix, seq_base_dev, prefix_lens_dev, head_stride, max_prefix,
+                          softmax_scale, out, workspace, workspace_bytes, hip_stream);
 }
 
 extern "C" int mcsd_tree_attention_fp8kv(const mcsd_mask_view_t *mask, int32_t B, int32_t H_q, int32_t H_kv,
@@ -1276,7 +1512,21 @@ extern "C" int mcsd_tree_attention_fp8kv(const mcsd_mask_view_t *mask, int32_t B
                                          float softmax_scale, void *out, void *workspace, size_t workspace_bytes,
                                          void *hip_stream)
 {
-    return attention_call(mask, MCSD_BF16, true, k_scale, v_scale, B, H_q, H_kv, 128, row_begin, q, k_tree, v_tree,
-                          node_stride, k_prefix_fp8, v_prefix_fp8, seq_base_dev, prefix_lens_dev, head_stride,
+    return attention_call(nullptr, mask, MCSD_BF16, true, k_scale, v_scale, B, H_q, H_kv, 128, row_begin, q, k_tree,
+                          v_tree, node_stride, k_prefix_fp8, v_prefix_fp8, seq_base_dev, prefix_lens_dev, head_stride,
                           max_prefix, softmax_scale, out, workspace, workspace_bytes, hip_stream);
+}
+
+extern "C" int mcsd_tree_attention_tuned(const mcsd_attention_tuning_t *tuning, const mcsd_mask_view_t *mask,
+                                         mcsd_dtype_t dtype, int32_t prefix_fp8, float k_scale, float v_scale, int32_t B,
+                                         int32_t H_q, int32_t H_kv, int32_t d, int32_t row_begin, const void *q,
+                                         const void *k_tree, const void *v_tree, int64_t node_stride,
+                                         const void *k_prefix, const void *v_prefix, const int64_t *seq_base_dev,
+                                         const int32_t *prefix_lens_dev, int64_t head_stride, int32_t max_prefix,
+                                         float softmax_scale, void *out, void *workspace, size_t workspace_bytes,
+                                         void *hip_stream)
+{
+    return attention_call(tuning, mask, dtype, prefix_fp8 != 0, k_scale, v_scale, B, H_q, H_kv, d, row_begin, q, k_tree,
+                          v_tree, node_stride, k_prefix, v_prefix, seq_base_dev, prefix_lens_dev, head_stride, max_prefix,
+                          softmax_scale, out, workspace, workspace_bytes, hip_stream);
 }

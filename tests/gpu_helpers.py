@@ -40,7 +40,7 @@ def run_attention(binding, view, ad: AttnDevice, max_prefix: int | None = None, 
     n = view.n_nodes
     mp = ad.max_prefix if max_prefix is None else max_prefix
     ws_bytes = binding.tree_attention_workspace(ad.B, ad.H, ad.d, n, mp)
-    ws = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device="cuda")
+    ws = binding.new_workspace(ws_bytes)
     if fill is not None:
         ad.out.fill_(fill)
     binding.tree_attention(view, ad.code, ad.B, ad.H, ad.d, ad.q, ad.kt, ad.vt, ad.node_stride, ad.kp, ad.vp,

@@ -159,7 +159,7 @@ def test_hidden_state_model(binding, oracle, widths, B, W):
     torch.cuda.synchronize()
     prob, stop = prob.cpu().numpy(), stop.cpu().numpy()
     want = oracle.mlp(ws, bs, x.reshape(B * W, -1).astype(np.float64)).reshape(B, W)
-    assert np.abs(prob - want).max() <= 1e-6            # binary64 accumulation on both sides: only the fp32 store differs
+    assert np.abs(prob - want).max() <= 1e-6            # fp32 multiply-adds with tree-combined partial sums against the binary64 oracle
     assert stop.tolist() == [int(np.all(prob[b] < np.float32(BETA))) for b in range(B)]
     clear = np.abs(want - BETA).min(axis=1) > P_ATOL
     assert np.array_equal(stop[clear], oracle.early_stop(want, BETA)[clear])

@@ -1,8 +1,6 @@
 """GPU parity of mcsd_tree_attention_fp8kv (bf16 queries and tree keys/values over an fp8 E4M3 prefix cache) against
 the CPU oracle on the same seeded inputs, to the bf16 path's tolerance (2e-2 relative + 1e-2 absolute): the kernel
 converts fp8 to bf16 exactly, so its arithmetic is that of the bf16 sweep."""
-import os
-
 import numpy as np
 import pytest
 import torch
@@ -40,22 +38,28 @@ class Dev:
         self.out = torch.full(self.q.shape, 31.0, dtype=torch.bfloat16, device="cuda")
 
 
-def run(binding, view, qd, kd, Hq, Hkv, row_begin=0, max_prefix=None):
+def run(binding, view, qd, kd, Hq, Hkv, row_begin=0, max_prefix=None, tuning=None):
     mp = kd.max_prefix if max_prefix is None else max_prefix
-    ws = torch.empty(max(binding.tree_attention_fp8kv_workspace(qd.B, Hq, Hkv, view.n_nodes, row_begin, mp), 256),
-                     dtype=torch.uint8, device="cuda")
-    binding.tree_attention_fp8kv(view, qd.B, Hq, Hkv, row_begin, qd.q, kd.kt, kd.vt, kd.node_stride, kd.kp, kd.vp,
-                                 kd.ks, kd.vs, kd.base, kd.lens, kd.head_stride, mp, qd.scale, qd.out, ws)
+    if tuning is None:
+        ws = binding.new_workspace(binding.tree_attention_fp8kv_workspace(qd.B, Hq, Hkv, view.n_nodes, row_begin, mp))
+        binding.tree_attention_fp8kv(view, qd.B, Hq, Hkv, row_begin, qd.q, kd.kt, kd.vt, kd.node_stride, kd.kp, kd.vp,
+                                     kd.ks, kd.vs, kd.base, kd.lens, kd.head_stride, mp, qd.scale, qd.out, ws)
+    else:
+        ws = binding.new_workspace(binding.tree_attention_tuned_workspace(tuning, 1, qd.B, Hq, Hkv, 128, view.n_nodes,
+                                                                          row_begin, mp))
+        binding.tree_attention_tuned(tuning, view, 1, 1, kd.ks, kd.vs, qd.B, Hq, Hkv, 128, row_begin, qd.q, kd.kt, kd.vt,
+                                     kd.node_stride, kd.kp, kd.vp, kd.base, kd.lens, kd.head_stride, mp, qd.scale,
+                                     qd.out, ws)
     torch.cuda.synchronize()
     return qd.out.float().cpu().numpy().astype(np.float64)
 
 
-def case(binding, oracle, H, br, B, Hh, lens, scales=(0.5, 0.25), seed=0, cfg_id=80, cap=None, row_begin=0):
+def case(binding, oracle, H, br, B, Hh, lens, scales=(0.5, 0.25), seed=0, cfg_id=80, cap=None, row_begin=0, tuning=None):
     w = scaled(WORKLOADS["cfg2"], B=B, H=Hh, branching=br, cfg_id=cfg_id)
     inp = attention_inputs(w, seed=seed, lens=lens, kv_fp8=scales, kv_capacity=cap)
     d = Dev(H, inp)
     v = binding.slice_mask(binding.build_mask(br), len(br))
-    got = run(binding, v, d, d, Hh, Hh, row_begin)
+    got = run(binding, v, d, d, Hh, Hh, row_begin, tuning=tuning)
     want = oracle.tree_attention_fp8kv(inp, oracle.build_mask(br), v.n_nodes)
     H.assert_close(got[:, :, row_begin:v.n_nodes], want[:, :, row_begin:], "bf16", f"fp8kv tree {br} lens {lens}")
     assert np.all(got[:, :, :row_begin] == 31.0)            # rows before row_begin are never written
@@ -82,12 +86,9 @@ def test_prefix_lengths_around_tile_and_split_boundaries(binding, oracle, H, br,
 @pytest.mark.parametrize("tiles", [1, 2, 3, 4, 5, 6, 7, 8, 9, 13])
 def test_every_length_of_the_four_stage_ring(binding, oracle, H, br, tiles):
     """One workgroup walks all the tiles of a head (no key splits): every remainder of the unrolled step sequence."""
-    os.environ["MCSD_ATTN_SPLITS"] = "1"
-    try:
-        case(binding, oracle, H, br, 1, 2, (64 * tiles,), cfg_id=82)
-        case(binding, oracle, H, br, 2, 1, (64 * tiles + 17, 64 * tiles), cfg_id=83)
-    finally:
-        del os.environ["MCSD_ATTN_SPLITS"]
+    one = binding.AttentionTuning(key_splits=1)
+    case(binding, oracle, H, br, 1, 2, (64 * tiles,), cfg_id=82, tuning=one)
+    case(binding, oracle, H, br, 2, 1, (64 * tiles + 17, 64 * tiles), cfg_id=83, tuning=one)
 
 
 def test_ragged_batch_two_workgroups_per_compute_unit(binding, oracle, H):
@@ -148,8 +149,7 @@ def test_bad_arguments_are_status_codes(binding, H):
     inp = attention_inputs(w, seed=0, lens=(2000,), kv_fp8=(0.5, 0.5))
     d = Dev(H, inp)
     v = binding.slice_mask(binding.build_mask(br), 4)
-    ws = torch.empty(max(binding.tree_attention_fp8kv_workspace(1, 2, 2, v.n_nodes, 0, 2000), 256), dtype=torch.uint8,
-                     device="cuda")
+    ws = binding.new_workspace(binding.tree_attention_fp8kv_workspace(1, 2, 2, v.n_nodes, 0, 2000))
 
     def call(ks=0.5, vs=0.5, head_stride=d.head_stride, workspace=ws, Hkv=2):
         binding.tree_attention_fp8kv(v, 1, 2, Hkv, 0, d.q, d.kt, d.vt, d.node_stride, d.kp, d.vp, ks, vs, d.base, d.lens,

@@ -36,8 +36,7 @@ def test_added_entry_points_replayed_from_a_hip_graph(binding, oracle, H):
     lens = H.dev(np.ascontiguousarray(inp["lens"], dtype=np.int32))
     base = H.dev(np.ascontiguousarray(inp["seq_base"], dtype=np.int64))
     out = torch.zeros_like(q)
-    ws = torch.empty(max(binding.tree_attention_fp8kv_workspace(w.B, w.H, w.H, n, 0, 700), 256), dtype=torch.uint8,
-                     device="cuda")
+    ws = binding.new_workspace(binding.tree_attention_fp8kv_workspace(w.B, w.H, w.H, n, 0, 700))
     vi = verify_inputs(w, seed=6, mode=DRAFT_INIT, replacement=False)
     p, qd = H.dev(vi["p_target"]), H.dev(vi["q_draft"])
     tokens, ua, us = H.dev(vi["tokens"]), H.dev(vi["u_accept"]), H.dev(vi["u_sample"])

@@ -307,6 +307,80 @@ def test_workspace_too_small_is_an_error_not_a_fault(binding, H):
     assert e.value.status == binding.MCSD_EWORKSPACE
 
 
+def _tuned_attention(binding, view, ad, tuning, ws=None, max_prefix=None):
+    mp = ad.max_prefix if max_prefix is None else max_prefix
+    if ws is None:
+        ws = binding.new_workspace(binding.tree_attention_tuned_workspace(tuning, 0, ad.B, ad.H, ad.H, ad.d, view.n_nodes, 0, mp))
+    binding.tree_attention_tuned(tuning, view, ad.code, 0, 1.0, 1.0, ad.B, ad.H, ad.H, ad.d, 0, ad.q, ad.kt, ad.vt,
+                                 ad.node_stride, ad.kp, ad.vp, ad.base, ad.lens, ad.head_stride, mp, ad.scale, ad.out, ws)
+    torch.cuda.synchronize()
+    return ad.out[:, :, :view.n_nodes].float().cpu().numpy().astype(np.float64)
+
+
+@pytest.mark.parametrize("fold", [0, 1])
+@pytest.mark.parametrize("splits", [1, 2, 3, 4, 5, 6, 8, 9, 15, 16])
+def test_every_split_count_folds_to_the_same_attention(binding, oracle, H, splits, fold):
+    """cfg2 with the number of key splits in the caller's hands, folded by the workgroup that finishes last
+    (fold = 0 leaves the choice to the library: that path, up to 16 partial results) and by the second kernel
+    (fold = 1); the workspace is reused for a second call, which must give the same bits."""
+    w = WORKLOADS["cfg2"]
+    inp = attention_inputs(w, seed=2)
+    ad = H.AttnDevice(inp)
+    v = binding.slice_mask(binding.build_mask(w.branching), w.gamma_max)
+    tuning = binding.AttentionTuning(key_splits=splits, fold=fold)
+    ws = binding.new_workspace(binding.tree_attention_tuned_workspace(tuning, 0, ad.B, ad.H, ad.H, ad.d, v.n_nodes, 0, ad.max_prefix))
+    ad.out.fill_(float("nan"))
+    got = _tuned_attention(binding, v, ad, tuning, ws)
+    H.assert_close(got, oracle.tree_attention(inp, oracle.build_mask(w.branching), v.n_nodes), "bf16", f"{splits} splits")
+    ad.out.fill_(float("nan"))
+    again = _tuned_attention(binding, v, ad, tuning, ws)
+    assert np.array_equal(got, again), "the second call on the same workspace differs"
+
+
+@pytest.mark.parametrize("B,Hh,lens", [(1, 8, (1000,)), (3, 8, (0, 70, 700)), (2, 12, (513, 64)), (1, 3, (900,)), (5, 7, (300,) * 5)])
+def test_folds_for_head_counts_that_do_and_do_not_divide_over_the_dies(binding, oracle, H, B, Hh, lens):
+    """The in-kernel fold needs all workgroups of a (sequence, head) on one die; with head counts that do not divide
+    over the dies the library must take the second kernel instead.  Either way every element matches."""
+    br = (4, 2, 2, 1)
+    w = scaled(WORKLOADS["cfg2"], B=B, H=Hh, cfg_id=67)
+    inp = attention_inputs(w, seed=5, lens=lens)
+    ad = H.AttnDevice(inp)
+    v = binding.slice_mask(binding.build_mask(br), 4)
+    got = H.run_attention(binding, v, ad, fill=float("nan"))
+    H.assert_close(got, oracle.tree_attention(inp, oracle.build_mask(br), v.n_nodes), "bf16", f"B{B} H{Hh}")
+
+
+def test_a_workspace_that_was_never_prepared_poisons_the_output(binding, H):
+    """The arrival counters of the fold live in the workspace; one that mcsd_workspace_init never saw must not give
+    plausible numbers: the rows come back NaN."""
+    w = WORKLOADS["cfg2"]
+    ad = H.AttnDevice(attention_inputs(w, seed=0))
+    v = binding.slice_mask(binding.build_mask(w.branching), w.gamma_max)
+    need = binding.tree_attention_workspace(ad.B, ad.H, ad.d, v.n_nodes, ad.max_prefix)
+    ws = torch.full((need,), 0xA5, dtype=torch.uint8, device="cuda")
+    ad.out.fill_(1.0)
+    binding.tree_attention(v, ad.code, ad.B, ad.H, ad.d, ad.q, ad.kt, ad.vt, ad.node_stride, ad.kp, ad.vp, ad.base,
+                           ad.lens, ad.head_stride, ad.max_prefix, ad.scale, ad.out, ws)
+    torch.cuda.synchronize()
+    assert bool(torch.isnan(ad.out[:, :, :v.n_nodes].float()).all())
+    binding.workspace_init(ws)                              # prepared: the same buffer now serves
+    binding.tree_attention(v, ad.code, ad.B, ad.H, ad.d, ad.q, ad.kt, ad.vt, ad.node_stride, ad.kp, ad.vp, ad.base,
+                           ad.lens, ad.head_stride, ad.max_prefix, ad.scale, ad.out, ws)
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(ad.out[:, :, :v.n_nodes].float()).all())
+
+
+def test_tuning_out_of_range_is_rejected(binding, H):
+    w = WORKLOADS["cfg2"]
+    ad = H.AttnDevice(attention_inputs(w, seed=0))
+    v = binding.slice_mask(binding.build_mask(w.branching), w.gamma_max)
+    ws = binding.new_workspace(1 << 24)
+    for bad in (binding.AttentionTuning(key_splits=65), binding.AttentionTuning(key_splits=-1), binding.AttentionTuning(fold=2)):
+        with pytest.raises(binding.McsdError) as e:
+            _tuned_attention(binding, v, ad, bad, ws)
+        assert e.value.status == binding.MCSD_EINVAL
+
+
 # ------------------------------------------------------------------------------------------------
 # verification: bit-exact paths, lengths and tokens
 # ------------------------------------------------------------------------------------------------
@@ -482,8 +556,7 @@ def test_step_replayed_from_a_hip_graph_matches_eager_launches(binding, oracle, 
     inp = attention_inputs(w, seed=2)
     ad = H.AttnDevice(inp)
     v = binding.slice_mask(binding.build_mask(w.branching), w.gamma_max)
-    ws = torch.empty(max(binding.tree_attention_workspace(ad.B, ad.H, ad.d, v.n_nodes, ad.max_prefix), 256),
-                     dtype=torch.uint8, device="cuda")
+    ws = binding.new_workspace(binding.tree_attention_workspace(ad.B, ad.H, ad.d, v.n_nodes, ad.max_prefix))
     vi = verify_inputs(w, seed=2, gamma=w.gamma_max, mode=DRAFT_INIT)
     p, q = H.dev(vi["p_target"]), H.dev(vi["q_draft"])
     tokens, ua, us = H.dev(vi["tokens"]), H.dev(vi["u_accept"]), H.dev(vi["u_sample"])
@@ -624,7 +697,7 @@ def test_commit_path_rejects_bad_arguments(binding, H):
 def _attend_rows(binding, H, v, ad, row_begin, max_prefix, fill):
     ws_bytes = binding.tree_attention_rows_workspace(ad.B, ad.H, ad.d, v.n_nodes, row_begin, max_prefix)
     assert ws_bytes <= binding.tree_attention_workspace(ad.B, ad.H, ad.d, v.n_nodes, max_prefix)
-    ws = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device="cuda")
+    ws = binding.new_workspace(ws_bytes)
     ad.out.fill_(fill)
     binding.tree_attention_rows(v, ad.code, ad.B, ad.H, ad.d, row_begin, ad.q, ad.kt, ad.vt, ad.node_stride, ad.kp,
                                 ad.vp, ad.base, ad.lens, ad.head_stride, max_prefix, ad.scale, ad.out, ws)
@@ -685,7 +758,7 @@ def _gqa_case(binding, oracle, H, br, B, Hq, Hkv, d, dtype, lens, max_prefix=Non
     v = binding.slice_mask(m, len(br))
     mp = ak.max_prefix if max_prefix is None else max_prefix
     ws_bytes = binding.tree_attention_gqa_workspace(B, Hq, Hkv, d, v.n_nodes, row_begin, mp)
-    ws = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device="cuda")
+    ws = binding.new_workspace(ws_bytes)
     aq.out.fill_(31.0)
     binding.tree_attention_gqa(v, aq.code, B, Hq, Hkv, d, row_begin, aq.q, ak.kt, ak.vt, ak.node_stride, ak.kp, ak.vp,
                                ak.base, ak.lens, ak.head_stride, mp, aq.scale, aq.out, ws)
@@ -727,8 +800,7 @@ def test_grouped_query_attention_llama3_like_batch(binding, oracle, H):
                head_stride=cap * d, seq_base=(np.arange(B, dtype=np.int64) * (Hq * cap * d)))
     aq, ak = H.AttnDevice(qi), H.AttnDevice(ki)
     v = binding.slice_mask(binding.build_mask(br), 4)
-    ws = torch.empty(max(binding.tree_attention_gqa_workspace(B, Hq, Hkv, d, v.n_nodes, 0, 700), 256), dtype=torch.uint8,
-                     device="cuda")
+    ws = binding.new_workspace(binding.tree_attention_gqa_workspace(B, Hq, Hkv, d, v.n_nodes, 0, 700))
     binding.tree_attention_gqa(v, aq.code, B, Hq, Hkv, d, 0, aq.q, ak.kt, ak.vt, ak.node_stride, ak.kp, ak.vp, ak.base,
                                ak.lens, ak.head_stride, 700, aq.scale, aq.out, ws)
     torch.cuda.synchronize()
