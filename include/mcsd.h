@@ -192,6 +192,25 @@ int mcsd_tree_attention_fp8kv(const mcsd_mask_view_t *mask, int32_t B, int32_t H
                               size_t workspace_bytes, void *hip_stream);
 
 /* ---------------------------------------------------------------------------------------------------
+ * mcsd_tree_attention for callers that cannot allocate device memory or carry a workspace around: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, results and errors as
+ * mcsd_tree_attention minus the workspace: the partial results and arrival counters of the key splits live in a
+ * device array of MCSD_STATIC_SCRATCH_BYTES inside the library (one copy per GPU, held until the process ends; its
+ * address is looked up on the first call on a device, which also enqueues one small fill kernel on the stream).
+ * The call allocates and frees nothing.  Shapes that need more than the array holds are MCSD_EUNSUPPORTED and nothing
+ * is enqueued (the five headline configurations need 0 to 34.2 MB; larger batches of long prefixes under wide trees
+ * need more and must bring a workspace).  All calls on one GPU share the array: calls that overlap in time on one GPU,
+ * on whatever streams, race on it and must be ordered by the caller.
+ * ------------------------------------------------------------------------------------------------- */
+enum { MCSD_STATIC_SCRATCH_BYTES = 40 * 1024 * 1024 };
+
+int mcsd_tree_attention_static(const mcsd_mask_view_t *mask, mcsd_dtype_t dtype, int32_t B, int32_t H, int32_t d,
+                               const void *q, const void *k_tree, const void *v_tree, int64_t node_stride,
+                               const void *k_prefix, const void *v_prefix, const int64_t *seq_base_dev,
+                               const int32_t *prefix_lens_dev, int64_t head_stride, int32_t max_prefix,
+                               float softmax_scale, void *out, void *hip_stream);
+
+/* ---------------------------------------------------------------------------------------------------
  * The same operation (Sec. 2.2) with the launch plan in the caller's hands, for measurement sweeps and tests; one entry
  * point covers what the four above do (prefix_fp8 != 0: the prefix cache holds E4M3 bytes and k_scale / v_scale
  * apply, d = 128, dtype MCSD_BF16; otherwise the scales are ignored).  The plan is a function of the shape arguments

@@ -22,7 +22,8 @@ EXPORTS = ["mcsd_strerror", "mcsd_build_mask", "mcsd_slice_mask", "mcsd_free_mas
            "mcsd_tree_attention_fp8kv_workspace", "mcsd_tree_attention_fp8kv",
            "mcsd_verify_tree_workspace", "mcsd_verify_tree", "mcsd_verify_tree_sampling", "mcsd_commit_path", "mcsd_early_stop_distribution",
            "mcsd_early_stop_hidden", "mcsd_profile_next", "mcsd_stream_read", "mcsd_workspace_init",
-           "mcsd_tree_attention_tuned_workspace", "mcsd_tree_attention_tuned"]
+           "mcsd_tree_attention_tuned_workspace", "mcsd_tree_attention_tuned", "mcsd_tree_attention_static"]
+STATIC_SCRATCH_BYTES = 40 * 1024 * 1024
 DECISION_MAX_K, MLP_MAX_LAYERS, MLP_MAX_WIDTH, MLP_MAX_INPUTS = 16, 3, 512, 8192
 
 
@@ -113,6 +114,9 @@ def _load() -> C.CDLL:
     lib.mcsd_early_stop_hidden.argtypes = [C.POINTER(Mlp), i32, i32, vp, i64, i64, C.c_float, vp, vp, vp]
     lib.mcsd_stream_read.restype = C.c_int
     lib.mcsd_stream_read.argtypes = [vp, C.c_size_t, vp, i32, vp]
+    lib.mcsd_tree_attention_static.restype = C.c_int
+    lib.mcsd_tree_attention_static.argtypes = [C.POINTER(MaskView), C.c_int, i32, i32, i32, vp, vp, vp, i64, vp, vp, vp,
+                                               vp, i64, i32, C.c_float, vp, vp]
     lib.mcsd_workspace_init.restype = C.c_int
     lib.mcsd_workspace_init.argtypes = [vp, sz, vp]
     lib.mcsd_tree_attention_tuned_workspace.restype = sz
@@ -241,6 +245,16 @@ def tree_attention(view: MaskView, dtype: int, B: int, H: int, d: int, q: torch.
                                  head_stride, max_prefix, softmax_scale, _ptr(out), _ptr(workspace), ws_bytes,
                                  _stream(stream))
     _check(st, "mcsd_tree_attention")
+
+
+def tree_attention_static(view: MaskView, dtype: int, B: int, H: int, d: int, q: torch.Tensor, k_tree: torch.Tensor,
+                          v_tree: torch.Tensor, node_stride: int, k_prefix: Optional[torch.Tensor],
+                          v_prefix: Optional[torch.Tensor], seq_base_dev: torch.Tensor, prefix_lens_dev: torch.Tensor,
+                          head_stride: int, max_prefix: int, softmax_scale: float, out: torch.Tensor, stream=None) -> None:
+    st = lib.mcsd_tree_attention_static(C.byref(view), dtype, B, H, d, _ptr(q), _ptr(k_tree), _ptr(v_tree), node_stride,
+                                        _ptr(k_prefix), _ptr(v_prefix), _ptr(seq_base_dev), _ptr(prefix_lens_dev),
+                                        head_stride, max_prefix, softmax_scale, _ptr(out), _stream(stream))
+    _check(st, "mcsd_tree_attention_static")
 
 
 def tree_attention_rows_workspace(B: int, H: int, d: int, n_nodes: int, row_begin: int, max_prefix: int) -> int:

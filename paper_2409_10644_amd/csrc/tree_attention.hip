@@ -1425,6 +1425,65 @@ int attention_call(const mcsd_attention_tuning_t *tune, const mcsd_mask_view_t *
 
 }  // namespace
 
+// ---------------------------------------------------------------------------------------------------
+// Entry point that allocates nothing: the workspace is a file-scope device array.  Each GPU the library runs on
+// holds its own copy at its own address; the array's name is a host-side stand-in only, so the device address is
+// asked for once per device with hipGetSymbolAddress and that pointer, never the name, is what the kernels get.
+// ---------------------------------------------------------------------------------------------------
+static __device__ __align__(256) unsigned char scratch[MCSD_STATIC_SCRATCH_BYTES];
+
+namespace {
+std::atomic<void *> g_scratch_of_device[64];        // device address of `scratch`, null until the first call there
+std::atomic<int> g_scratch_prepared[64];            // 1 once the tag word has been written on that device
+
+// Device address of this device's copy of `scratch`; the first call on a device also enqueues the fill kernel that
+// writes the workspace tag (the counters start as zeros like all of the array, and every launch leaves them zero).
+int static_scratch(hipStream_t st, void **out)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return MCSD_EHIP;
+    void *ptr = g_scratch_of_device[dev].load(std::memory_order_acquire);
+    if (!ptr) {
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) {
+            (void)hipGetLastError();
+            return MCSD_EHIP;
+        }
+        g_scratch_of_device[dev].store(ptr, std::memory_order_release);
+    }
+    if (g_scratch_prepared[dev].load(std::memory_order_acquire) == 0) {
+        const unsigned n16 = (unsigned)((WS_HEADER + WS_CTR_BYTES) / 16);
+        hipLaunchKernelGGL(workspace_init_kernel, dim3((n16 + 255) / 256), dim3(256), 0, st, (uint4 *)ptr);
+        if (hipGetLastError() != hipSuccess) return MCSD_EHIP;
+        g_scratch_prepared[dev].store(1, std::memory_order_release);
+    }
+    *out = ptr;
+    return MCSD_OK;
+}
+}  // namespace
+
+extern "C" int mcsd_tree_attention_static(const mcsd_mask_view_t *mask, mcsd_dtype_t dtype, int32_t B, int32_t H,
+                                          int32_t d, const void *q, const void *k_tree, const void *v_tree,
+                                          int64_t node_stride, const void *k_prefix, const void *v_prefix,
+                                          const int64_t *seq_base_dev, const int32_t *prefix_lens_dev,
+                                          int64_t head_stride, int32_t max_prefix, float softmax_scale, void *out,
+                                          void *hip_stream)
+{
+    if (!mask || B < 1 || H < 1 || max_prefix < 0 || (d != 64 && d != 128) || mask->n_nodes < 1 ||
+        mask->n_nodes > MCSD_ATTN_MAX_NODES || (dtype != MCSD_F32 && dtype != MCSD_BF16))
+        return attention_call(nullptr, mask, dtype, false, 1.f, 1.f, B, H, H, d, 0, q, k_tree, v_tree, node_stride, k_prefix,
+                              v_prefix, seq_base_dev, prefix_lens_dev, head_stride, max_prefix, softmax_scale, out, nullptr,
+                              0, hip_stream);          // (reports the argument error; nothing is launched)
+    // the shape's need against the array's size, before anything is enqueued
+    const AttnPlan pl = make_plan(dtype, B, H, H, mask->n_nodes, max_prefix);
+    if (workspace_bytes_for(pl, dtype, B, d, mask->n_nodes) > (size_t)MCSD_STATIC_SCRATCH_BYTES) return MCSD_EUNSUPPORTED;
+    void *ws = nullptr;
+    const int rc = static_scratch((hipStream_t)hip_stream, &ws);
+    if (rc != MCSD_OK) return rc;
+    return attention_call(nullptr, mask, dtype, false, 1.f, 1.f, B, H, H, d, 0, q, k_tree, v_tree, node_stride, k_prefix,
+                          v_prefix, seq_base_dev, prefix_lens_dev, head_stride, max_prefix, softmax_scale, out, ws,
+                          (size_t)MCSD_STATIC_SCRATCH_BYTES, hip_stream);
+}
+
 extern "C" int mcsd_workspace_init(void *workspace, size_t workspace_bytes, void *hip_stream)
 {
     if (!workspace && workspace_bytes > 0) return MCSD_EINVAL;
