@@ -5,55 +5,103 @@ One STEP is one pass of the whole hot path over one batch of seeded synthetic in
     mcsd_slice_mask(gamma)  ->  one mcsd_tree_attention call per transformer layer (32 for Llama-2-7B, every
     layer with its own KV cache and q/k/v)  ->  one mcsd_verify_tree call.
 All inputs are resident in HBM before the timed region.  The headline value is verified tree-tokens/s =
-B * N(gamma) / step time.  The line also carries the roofline of the dominant kernel (the tree-attention
-key sweep), measured with HIP events that bracket that kernel's launches, and the CPU oracle timed on the
-host cores as a reported baseline.
+B * N(gamma) / step time on cfg2 (the configuration the metric is quoted on).  The line also carries the roofline of
+the dominant kernel (the tree-attention key sweep), measured with HIP events that bracket that kernel's launches, the
+CPU oracle timed on the host cores as a reported baseline, and one section per other configuration.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2] [--extra cfg4,cfg5]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2] [--extra cfg1,cfg3,cfg4,cfg5,cfg4_b64]
 """
 from __future__ import annotations
 
 import argparse
 import json
 import os
+import re
 import sys
 import time
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
+sys.path.insert(0, os.path.join(ROOT, "tests"))
 
 HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16, published
 N_LAYERS = 32                   # Llama-2-7B
-
-# HBM traffic per launch of the sweep kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (bytes, already
-# scaled by the copy-kernel calibration); filled from the summaries under profiles/.  None = not measured.
-MEASURED_TRAFFIC = {"cfg2": 21_810_000, "cfg4": 664_280_000, "cfg5": 2_213_340_000, "cfg4_b64": 2_742_320_000,
-                    "cfg4_fp8kv": 348_030_000, "cfg5_fp8kv": 1_142_800_000}
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "tree_attn_hbm_traffic_pmc.md")
 
 
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def attention_algorithmic(w, lens, n):
+def measured_traffic():
+    """HBM bytes per launch of the sweep kernel from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs summarised in
+    profiles/: rows `| workload | kernel instantiation | workgroups | fetched bytes | written bytes |`, keyed by
+    (instantiation, grid).  A launch whose key is not in the file has no measured traffic (null in the output)."""
+    table = {}
+    try:
+        with open(TRAFFIC_FILE) as f:
+            for line in f:
+                m = re.match(r"^\|[^|]*\|\s*`?(tree_attn_\w+<[^>|]*>)`?\s*\|\s*(\d+)\s*\|\s*([\d ]+)\|\s*([\d ]+)\|", line)
+                if m:
+                    table[(m.group(1).replace(" ", ""), int(m.group(2)))] = \
+                        int(m.group(3).replace(" ", "")) + int(m.group(4).replace(" ", ""))
+    except OSError:
+        pass
+    return table
+
+
+def attention_algorithmic(w, lens, n, kv_bytes_per_elem=None):
     """Algorithmic bytes and flops of one mcsd_tree_attention call: prefix K and V read once, tree q/k/v read and
     the output written once, plus the mask slice; 4*N*(L+N)*d flops per (sequence, head)."""
     e = 2 if w.dtype == "bf16" else 4
-    by = sum(w.H * e * w.d * (2 * int(L) + 4 * n) for L in lens) + n * ((w.n_nodes() + 63) // 64) * 8
+    ekv = e if kv_bytes_per_elem is None else kv_bytes_per_elem
+    by = sum(w.H * w.d * (2 * int(L) * ekv + 4 * n * e) for L in lens) + n * ((w.n_nodes() + 63) // 64) * 8
     fl = sum(w.H * 4 * n * (int(L) + n) * w.d for L in lens)
     return by, fl
+
+
+def walk_bytes(w, gamma, mode, n_new, paths, lens):
+    """Vocabulary bytes the acceptance walks have to read, from their own results.  paths / lens: one entry per walk
+    (draft-initialised: one per sequence from the context that ends the prefix; target-initialised: one per level-1
+    node, whose first entry is that node, accepted untested).  A context with at least one rejection needs its target
+    and draft row (2 * V * 4 bytes, read once); a walk that accepts at every level needs the target row after its last
+    node for the new tokens (V * 4 bytes; after a rejection the new tokens come from the residual the walk already
+    holds); every tested candidate needs p(x), q(x), its token id and its uniform (16 bytes)."""
+    br = list(w.branching[:gamma])
+    off = [0]
+    for l, b in enumerate(br):
+        off.append(off[-1] + (b if l == 0 else (off[-1] - off[-2]) * b))
+    total = 0
+    for path, ln in zip(paths, lens):
+        cur, level = -1, 0
+        if mode == 1:
+            cur, level = int(path[0]), 1
+        while level < gamma:
+            cnt = br[level]
+            first = 0 if cur < 0 else off[level] + (cur - off[level - 1]) * cnt
+            if level < ln:
+                rejected = int(path[level]) - first
+                total += 16 * (rejected + 1) + (2 * w.V * 4 if rejected else 0)
+                cur = int(path[level])
+                level += 1
+            else:
+                total += 16 * cnt + 2 * w.V * 4          # every child rejected: the walk ends here
+                break
+        else:
+            total += w.V * 4 if n_new else 0             # all levels accepted
+    return total
 
 
 class Step:
     """Device-resident inputs of one step and the calls that make it."""
 
-    def __init__(self, name, n_kv_sets, gamma=None, mode=None, seed=0, with_verify=True, tuning=None):
+    def __init__(self, name, n_kv_sets, gamma=None, mode=None, seed=0, verify_seed=None, tuning=None):
         import numpy as np
         import torch
         from paper_2409_10644_amd import binding
-        from workloads import WORKLOADS, attention_inputs, prefix_lens, scaled, verify_inputs
-        sys.path.insert(0, os.path.join(ROOT, "tests"))
+        from workloads import WORKLOADS, attention_inputs, prefix_lens
         import gpu_helpers as H
 
         self.binding, self.H, self.torch, self.np = binding, H, torch, np
@@ -65,26 +113,39 @@ class Step:
         t0 = time.time()
         self.layers_host = [attention_inputs(w, seed=seed, kv_capacity=self.cap, variant=l) for l in range(n_kv_sets)]
         self.layers = [H.AttnDevice(inp) for inp in self.layers_host]
-        self.with_verify = with_verify
-        self.vi = verify_inputs(w if with_verify else scaled(w, B=1), seed=seed, gamma=self.gamma, mode=self.mode)
         log(f"[bench] {name}: {n_kv_sets} KV set(s) generated and uploaded in {time.time() - t0:.1f}s")
         self.mask = binding.build_mask(w.branching)                   # once, at gamma_max
-        self.view = binding.slice_mask(self.mask, self.gamma)
-        self.n = self.view.n_nodes
         self.tuning = tuning                                          # None: the library's own plan
-        ws_bytes = binding.tree_attention_tuned_workspace(tuning, 0, w.B, w.H, w.H, w.d, self.n, 0, self.cap)
-        self.ws_bytes = ws_bytes
-        self.ws = binding.new_workspace(ws_bytes)
-        vi = self.vi
+        self.set_gamma(self.gamma)
+        self.set_verify_inputs(seed if verify_seed is None else verify_seed)
+
+    def set_gamma(self, gamma):
+        b, w = self.binding, self.w
+        self.gamma = gamma
+        self.view = b.slice_mask(self.mask, gamma)
+        self.n = self.view.n_nodes
+        self.ws_bytes = b.tree_attention_tuned_workspace(self.tuning, 0, w.B, w.H, w.H, w.d, self.n, 0, self.cap)
+        self.ws = b.new_workspace(self.ws_bytes)
+        self.plan = b.tree_attention_plan(self.tuning, 1 if w.dtype == "bf16" else 0, 0, w.B, w.H, w.H, w.d, self.n, 0, self.cap)
+        self.alg_bytes, self.alg_flops = attention_algorithmic(w, self.lens, self.n)
+
+    def set_verify_inputs(self, seed, vi=None):
+        from workloads import verify_inputs
+        torch, H, w, b = self.torch, self.H, self.w, self.binding
+        self.vi = vi = verify_inputs(w, seed=seed, gamma=self.gamma, mode=self.mode) if vi is None else vi
         self.p, self.q = H.dev(vi["p_target"]), H.dev(vi["q_draft"])
         self.tokens, self.ua, self.us = H.dev(vi["tokens"]), H.dev(vi["u_accept"]), H.dev(vi["u_sample"])
         self.n_new = vi["n_new"]
         self.path = torch.zeros((w.B, self.gamma), dtype=torch.int32, device="cuda")
         self.alen = torch.zeros((w.B,), dtype=torch.int32, device="cuda")
         self.new = torch.zeros((w.B, max(self.n_new, 1)), dtype=torch.int32, device="cuda")
-        vws = binding.verify_tree_workspace(self.view, self.mode, w.B, self.n_new)
-        self.vws = torch.empty(max(vws, 256), dtype=torch.uint8, device="cuda") if vws else None
-        self.alg_bytes, self.alg_flops = attention_algorithmic(w, self.lens, self.n)
+        vws = b.verify_tree_workspace(self.view, self.mode, w.B, self.n_new)
+        self.vws = torch.zeros(max(vws, 256), dtype=torch.uint8, device="cuda") if vws else None
+
+    def kernel_name(self):
+        if not self.plan.mfma_path:
+            return f"tree_attn_f32_kernel<{self.w.d}>"
+        return f"tree_attn_bf16_kernel<{self.w.d}, {self.plan.query_blocks}, {self.plan.stages}, false>"
 
     def attention(self, layer):
         ad, w, b = self.layers[layer % len(self.layers)], self.w, self.binding
@@ -118,32 +179,43 @@ class Step:
             self.attention(l)
         self.verify()
 
-    def check_against_oracle(self, rows=24):
-        """'Verified': the outputs of this very configuration match the oracle (sampled attention rows of layer
-        0, full verification result)."""
+    def walks(self):
+        """(paths, lengths) of all walks of the last verify call, as numpy (see walk_bytes)."""
+        np_, w = self.np, self.w
+        if self.mode == 0:
+            return self.path.cpu().numpy(), self.alen.cpu().numpy()
+        R, g = int(w.branching[0]), self.gamma               # the workspace keeps every level-1 subtree's walk
+        raw = self.vws.cpu().numpy()
+        a256 = lambda x: (x + 255) & ~255
+        paths = raw[:4 * w.B * R * g].view(np_.int32).reshape(w.B * R, g)
+        o = a256(4 * w.B * R * g)
+        lens = raw[o:o + 4 * w.B * R].view(np_.int32).reshape(w.B * R)
+        return paths, lens
+
+    def check_against_oracle(self):
+        """'Verified': the outputs of this very configuration match the oracle: EVERY element of layer 0's attention
+        output (the buffer starts as NaN) and the full verification result.  Returns (mean accepted length, seconds
+        the oracle took for the attention layer)."""
         import oracle
         np_, torch = self.np, self.torch
         w = self.w
+        self.layers[0].out.fill_(float("nan"))
         self.attention(0)
-        if self.with_verify:
-            self.verify()
+        self.verify()
         torch.cuda.synchronize()
         M = oracle.build_mask(w.branching)
         got = self.layers[0].out[:, :, :self.n].float().cpu().numpy().astype(np_.float64)
-        rng = np_.random.default_rng(1)
-        for _ in range(rows):
-            b, h, i = int(rng.integers(w.B)), int(rng.integers(w.H)), int(rng.integers(self.n))
-            want = oracle.tree_attention_row(self.layers_host[0], M, self.n, b, h, i)
-            self.H.assert_close(got[b, h, i], want, w.dtype, f"bench {w.name} row {(b, h, i)}")
-        if not self.with_verify:
-            return float("nan")
+        t0 = time.time()
+        want = oracle.tree_attention(self.layers_host[0], M, self.n)
+        t_attn = time.time() - t0
+        self.H.assert_close(got, want, w.dtype, f"bench {w.name} gamma={self.gamma}, every element")
         vi = self.vi
-        want = oracle.verify_tree(self.mode, w.branching[:self.gamma], vi["tokens"], vi["p_target"], vi["q_draft"],
-                                  vi["u_accept"], vi["u_sample"])
+        want_v = oracle.verify_tree(self.mode, w.branching[:self.gamma], vi["tokens"], vi["p_target"], vi["q_draft"],
+                                    vi["u_accept"], vi["u_sample"])
         got_v = (self.path.cpu().numpy(), self.alen.cpu().numpy(), self.new.cpu().numpy()[:, :self.n_new])
-        for a, b_ in zip(got_v, want):
+        for a, b_ in zip(got_v, want_v):
             assert np_.array_equal(a, b_), "verification differs from the oracle"
-        return float(want[1].mean())
+        return float(want_v[1].mean()), t_attn
 
 
 class Ctx:
@@ -173,93 +245,156 @@ def time_kernel(st, hip, kernel_id, launch, reps, warm=0):
     return sum(ms) / len(ms), ms[len(ms) // 2], ms[len(ms) // 10], ms[(len(ms) * 9) // 10]
 
 
-def roofline_of(st, hip, reps, warm=0):
+def roofline_of(st, hip, reps, traffic, warm=0):
     b = st.binding
     avg, med, p10, p90 = time_kernel(st, hip, b.KERNEL_ATTN_SWEEP, lambda i: st.attention(i), reps, warm)
     ach = st.alg_bytes / (avg * 1e-3) / 1e9
-    traffic = MEASURED_TRAFFIC.get(st.w.name)
-    return {"bound": "hbm", "kernel": "tree_attn_bf16_kernel" if st.w.dtype == "bf16" else "tree_attn_f32_kernel",
+    kname = st.kernel_name()
+    return {"bound": "hbm", "kernel": kname, "workgroups": int(st.plan.workgroups), "key_splits": int(st.plan.key_splits),
+            "fold_in_kernel": bool(st.plan.fold_in_kernel),
             "achieved": round(ach, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBPS, 4),
-            "traffic": traffic, "algorithmic_bytes_per_launch": int(st.alg_bytes),
+            "traffic": traffic.get((kname.replace(" ", ""), int(st.plan.workgroups))),
+            "algorithmic_bytes_per_launch": int(st.alg_bytes),
             "flops_per_launch": int(st.alg_flops), "avg_launch_us": round(avg * 1e3, 2),
             "median_launch_us": round(med * 1e3, 2), "p10_us": round(p10 * 1e3, 2), "p90_us": round(p90 * 1e3, 2),
             "mfma_tflops": round(st.alg_flops / (avg * 1e-3) / 1e12, 1), "launches_timed": reps}
 
 
-def verify_algorithmic_bytes(st):
-    """Vocabulary rows the acceptance walk has to read, from its own result (draft-initialised mode: one walk per
-    sequence): a context with at least one rejection needs its target and draft row (2 * V * 4 bytes, read once);
-    a terminal context without rejections needs its target row for the new token (V * 4 bytes); every tested
-    candidate needs p(x), q(x), its token id and its uniform (16 bytes).  None in target-initialised mode, where
-    the walks of the losing level-1 subtrees are not part of the result."""
-    if st.mode != 0:
-        return None
-    w = st.w
-    path = st.path.cpu().numpy()
-    alen = st.alen.cpu().numpy()
-    br = list(w.branching[:st.gamma])
-    off = [0]
-    for l, b in enumerate(br):
-        off.append(off[-1] + (b if l == 0 else (off[-1] - off[-2]) * b))
-    total = 0
-    for bi in range(w.B):
-        cur = -1
-        for level in range(st.gamma):
-            cnt = br[level]
-            first = 0 if cur < 0 else off[level] + (cur - off[level - 1]) * cnt
-            if level < alen[bi]:
-                rejected = int(path[bi, level]) - first
-                total += 16 * (rejected + 1) + (2 * w.V * 4 if rejected else 0)
-                cur = int(path[bi, level])
-            else:
-                total += 16 * cnt + 2 * w.V * 4          # every child rejected: terminal context
-                break
-        else:
-            total += w.V * 4 if st.n_new else 0          # all levels accepted: bonus token from one target row
-    return total
+def verify_section(st, hip, reps):
+    """The verification call of a Step as it stands: kernel time, the vocabulary bytes its walks need, acceptance."""
+    b, torch = st.binding, st.torch
+    v_avg = time_kernel(st, hip, b.KERNEL_VERIFY_WALK, lambda i: st.verify(), reps, warm=8)[0]
+    torch.cuda.synchronize()
+    paths, lens = st.walks()
+    vb = walk_bytes(st.w, st.gamma, st.mode, st.n_new, paths, lens)
+    alen = st.alen.cpu().numpy().astype(float)
+    tested = st.gamma - (1 if st.mode else 0)
+    return {"bound": "hbm", "kernel": "verify_walk_fast_kernel" if st.w.V <= 32768 else "verify_walk_kernel",
+            "mode": "target-init" if st.mode else "draft-init", "walks": int(len(lens)),
+            "achieved": round(vb / (v_avg * 1e-3) / 1e9, 2), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+            "frac": round(vb / (v_avg * 1e-3) / 1e9 / HBM_PEAK_GBPS, 5), "algorithmic_bytes_per_launch": int(vb),
+            "avg_launch_us": round(v_avg * 1e3, 2),
+            "verify_tree_tokens_per_s": round(st.w.B * st.n / (v_avg * 1e-3), 1),
+            "mean_accept_len": round(float(alen.mean()), 3),
+            "alpha": round(float((alen.mean() - (1 if st.mode else 0)) / tested), 3) if tested > 0 else None}
 
 
-def cpu_baseline(st, budget_s=20.0):
-    """The oracle as it stands on the host cores: attention of as many layers as fit the time budget (scaled to
-    32 layers) plus one verification; tree-tokens/s of a whole step."""
+def pick_verify_seed(w, gamma, mode, n_seeds=16):
+    """The acceptance walk of one sequence depends on its draw; the timed step uses the seed (of 0..n_seeds-1) whose
+    accepted length is closest to the mean over those seeds (lowest seed on ties), decided by the oracle.  Returns
+    (seed, per-seed inputs, per-seed accepted lengths)."""
+    import numpy as np
     import oracle
-    w = st.w
-    M = oracle.build_mask(w.branching)
-    inp = st.layers_host[0]
-    B, Hh = w.B, w.H
-    # bounded sample: whole layers if one fits in the budget, else a subset of (b,h) rows of one layer
-    t0 = time.time()
-    probe_rows = 8
-    for k in range(probe_rows):
-        oracle.tree_attention_row(inp, M, st.n, k % B, k % Hh, k % st.n)
-    t_row = (time.time() - t0) / probe_rows
-    threads = oracle.threads()
-    est_layer = t_row * B * Hh * st.n / max(1, min(threads, B * Hh))
-    vi = st.vi
+    from workloads import verify_inputs
+    vis, lens = [], []
+    for s in range(n_seeds):
+        vi = verify_inputs(w, seed=s, gamma=gamma, mode=mode)
+        want = oracle.verify_tree(mode, w.branching[:gamma], vi["tokens"], vi["p_target"], vi["q_draft"], vi["u_accept"],
+                                  vi["u_sample"])
+        vis.append(vi)
+        lens.append(float(want[1].mean()))
+    mean = float(np.mean(lens))
+    seed = min(range(n_seeds), key=lambda s: (abs(lens[s] - mean), s))
+    return seed, vis, lens
+
+
+def timed_steps(st, torch, steps, warmup, eager, ramp_ms=25.0):
+    """Captures the step into a HIP graph (unless eager), runs untimed steps until the chip has left its idle clocks
+    (at least `warmup` steps and at least ramp_ms of back-to-back work), then times `steps` steps."""
+    run_step, launch, graph = st.step, "eager", None
+    if not eager:
+        try:
+            side = torch.cuda.Stream()
+            side.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.stream(side):
+                st.step()
+            torch.cuda.current_stream().wait_stream(side)
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph):
+                st.step()
+            run_step, launch = graph.replay, "hip-graph"
+        except Exception as ex:
+            log(f"[bench] graph capture failed ({ex!r}); timing eager launches")
+    torch.cuda.synchronize()
+    n_ramp, t0 = 0, time.perf_counter()
+    while n_ramp < warmup or (time.perf_counter() - t0) * 1e3 < ramp_ms:
+        run_step()
+        n_ramp += 1
+        if n_ramp % 8 == 0:
+            torch.cuda.synchronize()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        run_step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    if launch == "hip-graph":                     # the replayed step must leave what the eager step leaves
+        last = st.layers[(N_LAYERS - 1) % len(st.layers)].out
+        got_v = (st.path.clone(), st.alen.clone(), st.new.clone(), last.clone())
+        st.step()
+        torch.cuda.synchronize()
+        assert all(torch.equal(a, b) for a, b in zip(got_v, (st.path, st.alen, st.new, last))), \
+            "graph replay differs from eager launches"
+    return dt / steps * 1e3, launch, n_ramp, graph
+
+
+def cpu_baseline(st, t_attn_layer):
+    """The oracle as it stands on the host cores: one attention layer in full (the run that checked the GPU's output)
+    and one verification, scaled to a step of 32 layers; tree-tokens/s of a whole step."""
+    import oracle
+    w, vi = st.w, st.vi
     t0 = time.time()
     oracle.verify_tree(st.mode, w.branching[:st.gamma], vi["tokens"], vi["p_target"], vi["q_draft"], vi["u_accept"],
                        vi["u_sample"])
     t_verify = time.time() - t0
-    if est_layer <= budget_s:
-        n_layers = max(1, min(N_LAYERS, int(budget_s / max(est_layer, 1e-3))))
-        t0 = time.time()
-        for l in range(n_layers):
-            oracle.tree_attention(st.layers_host[l % len(st.layers_host)], M, st.n)
-        t_layer = (time.time() - t0) / n_layers
-        sample = f"{n_layers} of {N_LAYERS} attention layers in full + 1 verification, attention time scaled to {N_LAYERS} layers"
-    else:
-        rows = max(threads, int(budget_s / t_row) // threads * threads)
-        import concurrent.futures as cf
-        picks = [(r % B, (r // B) % Hh, (r * 7) % st.n) for r in range(rows)]
-        t0 = time.time()
-        with cf.ThreadPoolExecutor(threads) as ex:       # ctypes releases the GIL: rows run on all cores
-            list(ex.map(lambda a: oracle.tree_attention_row(inp, M, st.n, *a), picks))
-        t_layer = (time.time() - t0) / rows * (B * Hh * st.n)
-        sample = (f"{rows} of {B * Hh * st.n} output rows of one attention layer + 1 verification, scaled to "
-                  f"{N_LAYERS} full layers")
-    t_step = N_LAYERS * t_layer + t_verify
-    return {"value": round(w.B * st.n / t_step, 3), "unit": "tree-tokens/s", "cores": threads, "kind": "oracle",
-            "sample": sample, "attention_layer_s": round(t_layer, 4), "verify_s": round(t_verify, 4)}
+    t_step = N_LAYERS * t_attn_layer + t_verify
+    return {"value": round(w.B * st.n / t_step, 3), "unit": "tree-tokens/s", "cores": oracle.threads(), "kind": "oracle",
+            "sample": f"1 of {N_LAYERS} attention layers in full ({w.B * w.H * st.n} output rows) + 1 verification, "
+                      f"attention time scaled to {N_LAYERS} layers",
+            "attention_layer_s": round(t_attn_layer, 4), "verify_s": round(t_verify, 4)}
+
+
+def config_section(name, hip, args, traffic, gammas=(None,), n_sets=1, with_step=False):
+    """Attention roofline, verification and (optionally) the whole step of one of the other configurations, each
+    checked against the oracle first.  One entry per gamma."""
+    import torch
+    out = {}
+    es = Step(name, n_sets)
+    for g in gammas:
+        tag = name if g is None or g == es.w.gamma_max else f"{name}_gamma{g}"
+        if g is not None:
+            es.set_gamma(g)
+            es.set_verify_inputs(0)
+        alpha, t_attn = es.check_against_oracle()
+        for i in range(3):
+            es.attention(i)
+        reps = args.extra_reps if es.alg_bytes > 1e8 else args.kernel_reps
+        r = roofline_of(es, hip, reps, traffic, warm=reps)
+        torch.cuda.synchronize()
+        t0e = time.perf_counter()
+        for i in range(reps):
+            es.attention(i)
+        torch.cuda.synchronize()
+        call_us = (time.perf_counter() - t0e) / reps * 1e6
+        r["attention_call_us"] = round(call_us, 1)
+        r["attn_tree_tokens_per_s"] = round(es.w.B * es.n / (call_us * 1e-6), 1)
+        r["workload"] = (f"{name}: B{es.w.B} H{es.w.H} d{es.w.d} {es.w.dtype} N={es.n} gamma={es.gamma} "
+                         f"prefix {es.w.prefix_min}-{es.w.prefix_max}")
+        r["verified_vs_oracle"] = "every element of one layer's output + the verification result"
+        r["verify"] = verify_section(es, hip, args.kernel_reps)
+        r["step_tree_tokens_per_s_projected"] = round(
+            es.w.B * es.n / (N_LAYERS * call_us * 1e-6 + r["verify"]["avg_launch_us"] * 1e-6), 1)
+        if not args.no_cpu_baseline:
+            r["cpu_baseline"] = cpu_baseline(es, t_attn)
+        if with_step:
+            ms, launch, n_ramp, graph = timed_steps(es, torch, args.steps, args.warmup, args.eager)
+            r["step"] = {"ms_per_step": round(ms, 4), "tree_tokens_per_s": round(es.w.B * es.n / (ms * 1e-3), 1),
+                         "launch": launch, "kv_sets": n_sets, "steps": args.steps}
+            del graph
+        out[tag] = r
+    del es
+    torch.cuda.empty_cache()
+    return out
 
 
 def main():
@@ -268,10 +403,12 @@ def main():
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="cfg2")
-    ap.add_argument("--extra", default="cfg4,cfg5,cfg4_b64", help="other workloads whose attention roofline is reported too")
+    ap.add_argument("--extra", default="cfg1,cfg3,cfg4,cfg5,cfg4_b64",
+                    help="other configurations reported beside the headline one (attention roofline, verification, "
+                         "oracle baseline; cfg1 and cfg3 also as whole steps; cfg5 at gamma 5 and 4)")
     ap.add_argument("--kernel-reps", type=int, default=64)
     ap.add_argument("--extra-reps", type=int, default=200,
-                    help="timed launches (after as many untimed ones) of each extra workload's attention")
+                    help="timed launches (after as many untimed ones) of each large configuration's attention")
     ap.add_argument("--gqa-kv-heads", type=int, default=8,
                     help="key/value heads of the grouped-query variant of cfg4 (0 skips that section)")
     ap.add_argument("--verify-batch", type=int, default=128,
@@ -281,6 +418,8 @@ def main():
     ap.add_argument("--no-fp8kv", action="store_true", help="skip the fp8 prefix-cache variants of cfg4 / cfg5")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--eager", action="store_true", help="launch the step's kernels one by one instead of replaying a HIP graph")
+    ap.add_argument("--replay-only", type=int, default=0,
+                    help="for profilers: capture the headline step, replay it this many times and exit")
     ap.add_argument("--key-splits", type=int, default=0,
                     help="measurement sweeps: key splits of the headline workload's attention (0 = the library's plan)")
     ap.add_argument("--stages", type=int, default=0, help="measurement sweeps: LDS stages of the bf16 K/V ring (0 = the library's plan)")
@@ -305,62 +444,58 @@ def main():
         print(json.dumps({"calibration": "3 device-to-device copies", "bytes_read_each": src.numel() * 4,
                           "bytes_written_each": src.numel() * 4}))
         return
+    import numpy as np
     from paper_2409_10644_amd import binding
+    import gpu_helpers as H
+    import oracle
+    from workloads import WORKLOADS
     hip = binding.HipRuntime()
+    traffic = measured_traffic()
 
     w_name = args.workload
-    from workloads import WORKLOADS
     w = WORKLOADS[w_name]
     kv_bytes = w.B * w.H * w.prefix_max * w.d * (2 if w.dtype == "bf16" else 4) * 2
     n_sets = N_LAYERS if kv_bytes * N_LAYERS <= (8 << 30) else max(1, min(N_LAYERS, (2 << 30) // kv_bytes))
     tuning = None
     if args.key_splits or args.fold_kernel or args.stages:
         tuning = binding.AttentionTuning(key_splits=args.key_splits, fold=1 if args.fold_kernel else 0, stages=args.stages)
-    st = Step(w_name, n_sets, tuning=tuning)
-    alpha = st.check_against_oracle()
-    log(f"[bench] {w_name}: outputs verified against the oracle (mean accepted length {alpha:.2f})")
+    # the verification draw of the timed step: a typical one (see pick_verify_seed), not whatever seed 0 gives
+    v_seed, seed_inputs, seed_lens = pick_verify_seed(w, w.gamma_max, w.mode)
+    st = Step(w_name, n_sets, tuning=tuning, verify_seed=v_seed)
+    alpha, t_attn_cpu = st.check_against_oracle()
+    log(f"[bench] {w_name}: outputs verified against the oracle; verification seed {v_seed} (accepted length "
+        f"{alpha:.2f}, mean over seeds {np.mean(seed_lens):.2f})")
+    if args.replay_only:
+        ms, launch, n_ramp, graph = timed_steps(st, torch, args.replay_only, args.warmup, False)
+        print(json.dumps({"replayed": args.replay_only, "ms_per_step": round(ms, 4), "launch": launch}))
+        return
 
-    # The 65 launches of a step are captured once into a HIP graph and replayed (the library's calls neither
-    # allocate nor synchronise, so they can be captured); --eager launches them one by one instead.
-    run_step, launch = st.step, "eager"
-    if not args.eager:
-        try:
-            side = torch.cuda.Stream()
-            side.wait_stream(torch.cuda.current_stream())
-            with torch.cuda.stream(side):
-                st.step()
-            torch.cuda.current_stream().wait_stream(side)
-            graph = torch.cuda.CUDAGraph()
-            with torch.cuda.graph(graph):
-                st.step()
-            run_step, launch = graph.replay, "hip-graph"
-        except Exception as ex:
-            log(f"[bench] graph capture failed ({ex!r}); timing eager launches")
-    for _ in range(args.warmup):
-        run_step()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        run_step()
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    if launch == "hip-graph":                     # the replayed step must leave what the eager step leaves
-        got_v = (st.path.clone(), st.alen.clone(), st.new.clone(), st.layers[N_LAYERS % len(st.layers) - 1].out.clone())
-        st.step()
-        torch.cuda.synchronize()
-        now_v = (st.path, st.alen, st.new, st.layers[N_LAYERS % len(st.layers) - 1].out)
-        assert all(torch.equal(a, b) for a, b in zip(got_v, now_v)), "graph replay differs from eager launches"
-    ms_per_step = dt / args.steps * 1e3
+    ms_per_step, launch, n_ramp, graph = timed_steps(st, torch, args.steps, args.warmup, args.eager)
     value = w.B * st.n / (ms_per_step * 1e-3)
 
-    roof = roofline_of(st, hip, args.kernel_reps, warm=args.kernel_reps)
+    roof = roofline_of(st, hip, args.kernel_reps, traffic, warm=args.kernel_reps)
     # the same launch on ONE K/V set over and over: the 16 MiB of a small workload then come from the 256 MB
     # last-level cache, not from HBM.  Reported beside the cold figure (which rotates over n_sets sets), never as it.
     warm_avg = time_kernel(st, hip, binding.KERNEL_ATTN_SWEEP, lambda i: st.attention(0), args.kernel_reps, warm=10)[0]
     roof["warm_cache_launch_us"] = round(warm_avg * 1e3, 2)
-    m_avg = time_kernel(st, hip, binding.KERNEL_ATTN_MERGE, lambda i: st.attention(i), args.kernel_reps)[0] \
-        if st.ws_bytes > 0 and args.fold_kernel else 0.0
-    v_avg = time_kernel(st, hip, binding.KERNEL_VERIFY_WALK, lambda i: st.verify(), args.kernel_reps)[0]
+    has_fold_kernel = st.plan.key_splits > 1 and not st.plan.fold_in_kernel
+    m_avg = time_kernel(st, hip, binding.KERNEL_ATTN_MERGE, lambda i: st.attention(i), args.kernel_reps)[0] if has_fold_kernel else 0.0
+    vsec = verify_section(st, hip, args.kernel_reps)
+    # the walk over all the seeds the timed one was picked from: mean time per call and per visited context
+    per_seed = []
+    for s, vi in enumerate(seed_inputs):
+        st.set_verify_inputs(s, vi)
+        t = time_kernel(st, hip, binding.KERNEL_VERIFY_WALK, lambda i: st.verify(), 16, warm=4)[0]
+        torch.cuda.synchronize()
+        al = st.alen.cpu().numpy()
+        per_seed.append((t * 1e3, int(np.minimum(al + 1, st.gamma).sum()), float(al.mean())))
+    st.set_verify_inputs(v_seed, seed_inputs[v_seed])
+    vsec["over_seeds"] = {"seeds": len(per_seed), "mean_launch_us": round(float(np.mean([x[0] for x in per_seed])), 2),
+                          "min_launch_us": round(min(x[0] for x in per_seed), 2), "max_launch_us": round(max(x[0] for x in per_seed), 2),
+                          "mean_us_per_visited_context": round(float(np.sum([x[0] for x in per_seed]) / np.sum([x[1] for x in per_seed])), 2),
+                          "mean_accept_len": round(float(np.mean([x[2] for x in per_seed])), 3),
+                          "alpha": round(float(np.mean([x[2] for x in per_seed])) / st.gamma, 3),
+                          "accept_len_by_seed": [round(x[2], 2) for x in per_seed]}
     out = {
         "metric": "verified tree-tokens/s, whole verification step (32 tree-attention layers + acceptance)",
         "value": round(value, 1), "unit": "tree-tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -369,24 +504,19 @@ def main():
         "config": {"workload": f"{w_name}: B{w.B} H{w.H} d{w.d} {w.dtype} prefix {w.prefix_min}"
                                f"{'' if w.prefix_min == w.prefix_max else '-' + str(w.prefix_max)} tree {w.branching} "
                                f"N={st.n} gamma={st.gamma} V={w.V} mode={'target' if st.mode else 'draft'}-init",
-                   "layers_per_step": N_LAYERS, "kv_sets": n_sets, "launch": launch, "verified_vs_oracle": True,
+                   "layers_per_step": N_LAYERS, "kv_sets": n_sets, "launch": launch,
+                   "untimed_steps_before": n_ramp, "verified_vs_oracle": True, "verify_seed": v_seed,
                    "mean_accept_len": round(alpha, 3)},
         "roofline": roof,
         "kernels_us": {"attn_sweep": roof["avg_launch_us"], "attn_merge": round(m_avg * 1e3, 2),
-                       "verify_walk": round(v_avg * 1e3, 2)},
+                       "verify_walk": vsec["avg_launch_us"]},
+        "verify_roofline": vsec,
     }
-    vb = verify_algorithmic_bytes(st)
-    if vb is not None:          # the vocabulary pass: one workgroup per sequence, latency-bound at this batch size
-        out["verify_roofline"] = {"bound": "hbm", "kernel": "verify_walk_kernel", "achieved": round(vb / (v_avg * 1e-3) / 1e9, 2),
-                                  "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(vb / (v_avg * 1e-3) / 1e9 / HBM_PEAK_GBPS, 6),
-                                  "algorithmic_bytes_per_launch": int(vb), "avg_launch_us": round(v_avg * 1e3, 2)}
     # the same verification for candidates drawn without replacement (a scheme next to the paper's), same shapes
     try:
-        import numpy as np
-        import oracle
         from workloads import verify_inputs
-        vi2 = verify_inputs(w, seed=0, gamma=st.gamma, mode=st.mode, replacement=False)
-        d2 = [st.H.dev(vi2[k]) for k in ("tokens", "p_target", "q_draft", "u_accept", "u_sample")]
+        vi2 = verify_inputs(w, seed=v_seed, gamma=st.gamma, mode=st.mode, replacement=False)
+        d2 = [H.dev(vi2[k]) for k in ("tokens", "p_target", "q_draft", "u_accept", "u_sample")]
         o2 = [torch.zeros_like(st.path), torch.zeros_like(st.alen), torch.zeros_like(st.new)]
 
         def v2call(i):
@@ -406,13 +536,12 @@ def main():
     except Exception as ex:
         out["verify_without_replacement"] = {"error": repr(ex)}
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(st)
+        out["cpu_baseline"] = cpu_baseline(st, t_attn_cpu)
     # the draft side of the loop: attention for the newest level only, a fresh slice of the mask per level
     lvl = {}
     for g in range(1, st.gamma + 1):
         vg = binding.slice_mask(st.mask, g)
         rb = int(vg.level_off_host[g - 1])
-        ad = st.layers[0]
 
         def level_call(i, vg=vg, rb=rb):
             a = st.layers[i % len(st.layers)]
@@ -427,56 +556,51 @@ def main():
         torch.cuda.synchronize()
         lvl[f"gamma{g}_rows{vg.n_nodes - rb}"] = round((time.perf_counter() - t0l) / 64 * 1e6, 1)
     out["level_attention_call_us"] = lvl
-    # the row after the step: accepted path appended to every layer's cache (last: it overwrites cache rows)
+    # The row after the step: the accepted path appended to every layer's cache (last: it overwrites cache rows).
+    # Timed with the walk's own result and with a full path forced into the outputs (every level accepted: gamma rows
+    # of every head of every layer move), so that the copy kernel is never timed on an empty path only.
     ids = torch.zeros((w.B, st.gamma + 1), dtype=torch.int32, device="cuda")
     n_ids = torch.zeros((w.B,), dtype=torch.int32, device="cuda")
     lens_c = st.layers[0].lens.clone()
+    st.verify()
+    torch.cuda.synchronize()
+    commit = {"layers_per_call": len(st.layers)}
+    own = (st.path.clone(), st.alen.clone())
+    sizes = oracle.level_sizes(w.branching[:st.gamma])
+    chain = torch.tensor(sizes.cumsum() - sizes, dtype=torch.int32, device="cuda")   # first node of every level: a root-to-leaf path
+    for tag, (pth, aln) in (("walk_result", own), ("full_path", (chain.repeat(w.B, 1), torch.full_like(st.alen, st.gamma)))):
+        st.path.copy_(pth)
+        st.alen.copy_(aln)
 
-    def commit_once(i):
-        lens_c.copy_(st.layers[0].lens)
-        st.commit(lens_c, ids, n_ids)
-    c_avg = time_kernel(st, hip, binding.KERNEL_COMMIT_COPY, commit_once, 20, warm=5)[0]
-    torch.cuda.synchronize()
-    t0c = time.perf_counter()
-    for i in range(20):
-        st.commit(lens_c, ids, n_ids)
-    torch.cuda.synchronize()
-    out["commit_path"] = {"layers_per_call": len(st.layers), "copy_kernel_us": round(c_avg * 1e3, 2),
-                          "call_us": round((time.perf_counter() - t0c) / 20 * 1e6, 1),
-                          "mean_accept_len": round(float(st.alen.float().mean().item()), 3)}
-    del st
+        def commit_once(i):
+            lens_c.copy_(st.layers[0].lens)
+            st.commit(lens_c, ids, n_ids)
+        c_avg = time_kernel(st, hip, binding.KERNEL_COMMIT_COPY, commit_once, 20, warm=5)[0]
+        torch.cuda.synchronize()
+        t0c = time.perf_counter()
+        for i in range(20):
+            commit_once(i)
+        torch.cuda.synchronize()
+        rows = float(aln.float().mean().item())
+        commit[tag] = {"accept_len": round(rows, 3), "copy_kernel_us": round(c_avg * 1e3, 2),
+                       "call_us_with_length_reset": round((time.perf_counter() - t0c) / 20 * 1e6, 1),
+                       "bytes_moved": int(rows * w.B * len(st.layers) * w.H * w.d * 2 * 2 * 2)}
+    out["commit_path"] = commit
+    del st, graph
     torch.cuda.empty_cache()
 
     extra = {}
+    plans = {"cfg1": dict(n_sets=N_LAYERS, with_step=True), "cfg3": dict(n_sets=16, with_step=True),
+             "cfg5": dict(gammas=(5, 4))}
     for name in [x for x in args.extra.split(",") if x and x != w_name]:
         try:
-            es = Step(name, 1, with_verify=name in ("cfg4", "cfg5"))
-            es.check_against_oracle(rows=8)
-            for i in range(3):
-                es.attention(i)
-            r = roofline_of(es, hip, args.extra_reps, warm=args.extra_reps)
-            torch.cuda.synchronize()
-            t0e = time.perf_counter()
-            for i in range(args.extra_reps):
-                es.attention(i)
-            torch.cuda.synchronize()
-            call_us = (time.perf_counter() - t0e) / args.extra_reps * 1e6
-            r["attention_call_us"] = round(call_us, 1)
-            r["attn_tree_tokens_per_s"] = round(es.w.B * es.n / (call_us * 1e-6), 1)
-            r["workload"] = f"{name}: B{es.w.B} N={es.n} prefix {es.w.prefix_min}-{es.w.prefix_max}"
-            extra[name] = r
-            del es
-            torch.cuda.empty_cache()
+            extra.update(config_section(name, hip, args, traffic, **plans.get(name, {})))
         except Exception as ex:      # an extra workload must not lose the headline line
             extra[name] = {"error": repr(ex)}
     # grouped-query variant of the ragged batch (beyond the paper's multi-head shape): 32 query heads on 8 kv heads
     if args.gqa_kv_heads > 0 and "cfg4" in args.extra:
         try:
             from workloads import scaled, attention_inputs, prefix_lens
-            sys.path.insert(0, os.path.join(ROOT, "tests"))
-            import gpu_helpers as H
-            import oracle
-            import numpy as np
             wq = WORKLOADS["cfg4"]
             Hkv = args.gqa_kv_heads
             wk = scaled(wq, H=Hkv, cfg_id=wq.cfg_id + 100)
@@ -492,6 +616,7 @@ def main():
             def gcall(i):
                 binding.tree_attention_gqa(vg, 1, wq.B, wq.H, Hkv, wq.d, 0, aq.q, ak.kt, ak.vt, ak.node_stride, ak.kp, ak.vp,
                                            ak.base, ak.lens, ak.head_stride, int(wq.prefix_max), aq.scale, aq.out, wsg)
+            aq.out.fill_(float("nan"))
             gcall(0)
             torch.cuda.synchronize()
             G = wq.H // Hkv
@@ -500,22 +625,22 @@ def main():
                         k_prefix=np.repeat(ki["k_prefix"], G, axis=1), v_prefix=np.repeat(ki["v_prefix"], G, axis=1),
                         head_stride=cap * wq.d, seq_base=(np.arange(wq.B, dtype=np.int64) * (wq.H * cap * wq.d)))
             got = aq.out[:, :, :n].float().cpu().numpy().astype(np.float64)
-            M = oracle.build_mask(wq.branching)
-            rng = np.random.default_rng(2)
-            for _ in range(8):
-                b_, h_, i_ = int(rng.integers(wq.B)), int(rng.integers(wq.H)), int(rng.integers(n))
-                H.assert_close(got[b_, h_, i_], oracle.tree_attention_row(rep_, M, n, b_, h_, i_), "bf16", "bench gqa")
+            H.assert_close(got, oracle.tree_attention(rep_, oracle.build_mask(wq.branching), n), "bf16", "bench gqa, every element")
+            del rep_
 
             gs = Ctx(binding, torch)
             g_avg, g_med, g_p10, g_p90 = time_kernel(gs, hip, binding.KERNEL_ATTN_SWEEP, gcall, args.extra_reps, warm=args.extra_reps)
             gbytes = sum(2 * wq.d * (Hkv * (2 * int(L) + 2 * n) + wq.H * 2 * n) for L in lens)
             gflops = sum(wq.H * 4 * n * (int(L) + n) * wq.d for L in lens)
-            extra["cfg4_gqa"] = {"bound": "mfma", "kernel": "tree_attn_bf16_kernel", "achieved": round(gflops / (g_avg * 1e-3) / 1e12, 1),
-                                 "peak": 2500.0, "unit": "TFLOP/s", "frac": round(gflops / (g_avg * 1e-3) / 1e12 / 2500.0, 4),
+            gp = binding.tree_attention_plan(None, 1, 0, wq.B, wq.H, Hkv, wq.d, n, 0, int(wq.prefix_max))
+            extra["cfg4_gqa"] = {"bound": "mfma", "kernel": f"tree_attn_bf16_kernel<{wq.d}, {gp.query_blocks}, {gp.stages}, false>",
+                                 "workgroups": int(gp.workgroups), "fold_in_kernel": bool(gp.fold_in_kernel),
+                                 "achieved": round(gflops / (g_avg * 1e-3) / 1e12, 1),
+                                 "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(gflops / (g_avg * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
                                  "traffic": None, "flops_per_launch": int(gflops), "algorithmic_bytes_per_launch": int(gbytes),
                                  "hbm_GBps": round(gbytes / (g_avg * 1e-3) / 1e9, 1), "avg_launch_us": round(g_avg * 1e3, 2),
                                  "p10_us": round(g_p10 * 1e3, 2), "p90_us": round(g_p90 * 1e3, 2), "launches_timed": args.extra_reps,
-                                 "verified_vs_oracle": True,
+                                 "verified_vs_oracle": "every element",
                                  "workload": f"cfg4 with {wq.H} query heads on {Hkv} key/value heads (B{wq.B} N={n})"}
             del aq, ak
             torch.cuda.empty_cache()
@@ -525,11 +650,7 @@ def main():
     if not args.no_fp8kv:
         for name in [x for x in args.extra.split(",") if x in ("cfg4", "cfg5")]:
             try:
-                import numpy as np
                 from workloads import attention_inputs, prefix_lens
-                import oracle
-                sys.path.insert(0, os.path.join(ROOT, "tests"))
-                import gpu_helpers as H
                 w8 = WORKLOADS[name]
                 lens = prefix_lens(w8, 0)
                 cap = int(w8.prefix_max)
@@ -538,7 +659,7 @@ def main():
                 kp8, vp8 = torch.from_numpy(inp8["k_prefix"]).cuda(), torch.from_numpy(inp8["v_prefix"]).cuda()
                 lens8 = H.dev(np.ascontiguousarray(inp8["lens"], dtype=np.int32))
                 base8 = H.dev(np.ascontiguousarray(inp8["seq_base"], dtype=np.int64))
-                out8 = torch.zeros_like(q8)
+                out8 = torch.full(q8.shape, float("nan"), dtype=torch.bfloat16, device="cuda")
                 v8 = binding.slice_mask(binding.build_mask(w8.branching), w8.gamma_max)
                 n8 = v8.n_nodes
                 ws8 = binding.new_workspace(binding.tree_attention_fp8kv_workspace(w8.B, w8.H, w8.H, n8, 0, cap))
@@ -550,25 +671,35 @@ def main():
                 fcall(0)
                 torch.cuda.synchronize()
                 got8 = out8[:, :, :n8].float().cpu().numpy().astype(np.float64)
-                M8 = oracle.build_mask(w8.branching)
-                rng8 = np.random.default_rng(3)
-                for _ in range(8):
-                    b_, h_, i_ = int(rng8.integers(w8.B)), int(rng8.integers(w8.H)), int(rng8.integers(n8))
-                    H.assert_close(got8[b_, h_, i_], oracle.tree_attention_row_fp8kv(inp8, M8, n8, b_, h_, i_), "bf16", "bench fp8kv")
+                H.assert_close(got8, oracle.tree_attention_fp8kv(inp8, oracle.build_mask(w8.branching), n8), "bf16",
+                               "bench fp8kv, every element")
 
                 fs = Ctx(binding, torch)
                 f_avg, f_med, f_p10, f_p90 = time_kernel(fs, hip, binding.KERNEL_ATTN_SWEEP, fcall, args.extra_reps, warm=args.extra_reps)
-                fbytes = sum(w8.H * w8.d * (2 * int(L) * 1 + 4 * n8 * 2) for L in lens)
-                fflops = sum(w8.H * 4 * n8 * (int(L) + n8) * w8.d for L in lens)
-                extra[name + "_fp8kv"] = {
-                    "bound": "hbm", "kernel": "tree_attn_bf16_kernel<fp8 prefix>", "achieved": round(fbytes / (f_avg * 1e-3) / 1e9, 1),
-                    "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(fbytes / (f_avg * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
-                    "traffic": MEASURED_TRAFFIC.get(name + "_fp8kv"), "algorithmic_bytes_per_launch": int(fbytes),
-                    "flops_per_launch": int(fflops),
-                    "avg_launch_us": round(f_avg * 1e3, 2), "p10_us": round(f_p10 * 1e3, 2), "p90_us": round(f_p90 * 1e3, 2),
-                    "mfma_tflops": round(fflops / (f_avg * 1e-3) / 1e12, 1), "launches_timed": args.extra_reps,
-                    "attn_tree_tokens_per_s": round(w8.B * n8 / (f_avg * 1e-3), 1), "verified_vs_oracle": True,
-                    "workload": f"{name} with the prefix cache in fp8 E4M3 (B{w8.B} N={n8})"}
+                fbytes, fflops = attention_algorithmic(w8, lens, n8, kv_bytes_per_elem=1)
+                fp = binding.tree_attention_plan(None, 1, 1, w8.B, w8.H, w8.H, w8.d, n8, 0, cap)
+                kname = f"tree_attn_bf16_kernel<{w8.d}, {fp.query_blocks}, {fp.stages}, true>"
+                # which roof: the bytes at 8 TB/s against the flops at the dense bf16 peak
+                t_hbm, t_mfma = fbytes / (HBM_PEAK_GBPS * 1e9), fflops / (MFMA_BF16_PEAK_TFLOPS * 1e12)
+                issue_bound = fp.query_blocks == 4   # four query blocks: the soft-max + MFMA instruction stream, not HBM, is the limit
+                entry = {"kernel": kname, "workgroups": int(fp.workgroups), "fold_in_kernel": bool(fp.fold_in_kernel),
+                         "traffic": traffic.get((kname.replace(" ", ""), int(fp.workgroups))),
+                         "algorithmic_bytes_per_launch": int(fbytes), "flops_per_launch": int(fflops),
+                         "avg_launch_us": round(f_avg * 1e3, 2), "p10_us": round(f_p10 * 1e3, 2), "p90_us": round(f_p90 * 1e3, 2),
+                         "hbm_GBps": round(fbytes / (f_avg * 1e-3) / 1e9, 1), "hbm_frac": round(fbytes / (f_avg * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+                         "mfma_tflops": round(fflops / (f_avg * 1e-3) / 1e12, 1),
+                         "mfma_frac": round(fflops / (f_avg * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
+                         "time_at_hbm_peak_us": round(t_hbm * 1e6, 1), "time_at_mfma_peak_us": round(t_mfma * 1e6, 1),
+                         "launches_timed": args.extra_reps,
+                         "attn_tree_tokens_per_s": round(w8.B * n8 / (f_avg * 1e-3), 1), "verified_vs_oracle": "every element",
+                         "workload": f"{name} with the prefix cache in fp8 E4M3 (B{w8.B} N={n8})"}
+                if issue_bound:
+                    entry.update({"bound": "mfma", "achieved": entry["mfma_tflops"], "peak": MFMA_BF16_PEAK_TFLOPS,
+                                  "unit": "TFLOP/s", "frac": entry["mfma_frac"]})
+                else:
+                    entry.update({"bound": "hbm", "achieved": entry["hbm_GBps"], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                                  "frac": entry["hbm_frac"]})
+                extra[name + "_fp8kv"] = entry
                 del kp8, vp8
                 torch.cuda.empty_cache()
             except Exception as ex:
@@ -577,9 +708,6 @@ def main():
     if args.verify_batch > 0:
         try:
             from workloads import scaled, verify_inputs
-            import oracle
-            sys.path.insert(0, os.path.join(ROOT, "tests"))
-            import gpu_helpers as H
             wb = scaled(WORKLOADS[w_name], B=args.verify_batch)
             vi = verify_inputs(wb, seed=1, mode=0)
             vv = binding.slice_mask(binding.build_mask(wb.branching), wb.gamma_max)
@@ -591,21 +719,20 @@ def main():
             o_path = torch.zeros((wb.B, vv.gamma), dtype=torch.int32, device="cuda")
             o_len = torch.zeros((wb.B,), dtype=torch.int32, device="cuda")
             o_new = torch.zeros((wb.B, 1), dtype=torch.int32, device="cuda")
-
             vs = Ctx(binding, torch)
-            vs.mode, vs.w, vs.gamma, vs.n_new, vs.path, vs.alen = 0, wb, vv.gamma, 1, o_path, o_len
 
             def vcall(i):
                 binding.verify_tree(vv, 0, wb.B, wb.V, dt_, dp, dq, vi["p_target"].shape[1] * wb.V, vi["q_draft"].shape[1] * wb.V,
                                     dua, dus, 1, o_path, o_len, o_new, None)
             vb_avg = time_kernel(vs, hip, binding.KERNEL_VERIFY_WALK, vcall, 30, warm=10)[0]
-            vbytes = verify_algorithmic_bytes(vs)
+            vbytes = walk_bytes(wb, vv.gamma, 0, 1, got[0], got[1])
             extra["verify_batch%d" % wb.B] = {
-                "bound": "hbm", "kernel": "verify_walk_kernel", "achieved": round(vbytes / (vb_avg * 1e-3) / 1e9, 1),
+                "bound": "hbm", "kernel": "verify_walk_fast_kernel", "achieved": round(vbytes / (vb_avg * 1e-3) / 1e9, 1),
                 "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(vbytes / (vb_avg * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
                 "algorithmic_bytes_per_launch": int(vbytes), "avg_launch_us": round(vb_avg * 1e3, 2),
                 "sequences_per_s": round(wb.B / (vb_avg * 1e-3), 1), "mean_accept_len": round(float(got[1].mean()), 3),
-                "verified_vs_oracle": True, "workload": f"{w_name} verification, B={wb.B}, V={wb.V}"}
+                "alpha": round(float(got[1].mean()) / vv.gamma, 3),
+                "verified_vs_oracle": True, "workload": f"{w_name} verification, B={wb.B}, V={wb.V}, draft-init"}
             del dp, dq
         except Exception as ex:
             extra["verify_batch"] = {"error": repr(ex)}
@@ -613,9 +740,7 @@ def main():
     # batch whose rows (4 distinct copies, > 512 MB) cannot stay in the last-level cache between launches
     if args.decision_batch > 0:
         try:
-            import numpy as np
             from workloads import hidden_states, mlp_weights, scaled, verify_inputs
-            import oracle
             k, Wd, beta = 10, 16, 0.4
             Bd = args.decision_batch
             wd = scaled(WORKLOADS["fork"], B=Bd, branching=(Wd, 1))
@@ -682,7 +807,7 @@ def main():
 
         ss = Ctx(binding, torch)
         per_grid = {}
-        for wgs in (256, 512, 2048, 8192):      # the rate depends on how the grid's stride falls on the memory channels
+        for wgs in (192, 256, 512, 2048):      # the rate depends on how the grid's stride falls on the memory channels
             s_avg = time_kernel(ss, hip, binding.KERNEL_STREAM_READ, lambda i: binding.stream_read(buf, sink, wgs), 10, warm=10)[0]
             per_grid[wgs] = round(buf.numel() / (s_avg * 1e-3) / 1e9, 1)
         gbps = max(per_grid.values())

@@ -238,6 +238,24 @@ int mcsd_tree_attention_tuned(const mcsd_attention_tuning_t *tuning, const mcsd_
                               int32_t max_prefix, float softmax_scale, void *out, void *workspace,
                               size_t workspace_bytes, void *hip_stream);
 
+/* The launch plan that a tree-attention call with these arguments would use on the current HIP device right now (it
+ * depends on the device's compute units and, for fold_in_kernel, on a mask having been built on that device, which is
+ * when the library learns how workgroups are dealt to the chip's dies).  HOST only, nothing is launched.  For
+ * measurement: it names the kernel instantiation and grid that profiler output has to be matched with. */
+typedef struct {
+    int32_t mfma_path;          /* 1: bf16 sweep on the matrix cores; 0: fp32 kernels on the vector ALU */
+    int32_t query_blocks;       /* 32-row query blocks per workgroup: 1, 2 or 4 */
+    int32_t key_splits;         /* workgroups that share the prefix keys of one (sequence, head [chunk]) */
+    int32_t workgroups;         /* grid of the sweep launch */
+    int32_t stages;             /* LDS stages of the K/V ring (0 on the fp32 path) */
+    int32_t fold_in_kernel;     /* 1: partial results are folded by the sweep itself; 0: a second kernel, or no splits */
+    int32_t ordered_by_length;  /* 1: workgroups take their work in an order computed from the prefix lengths */
+} mcsd_attention_plan_t;
+
+int mcsd_tree_attention_plan(const mcsd_attention_tuning_t *tuning, mcsd_dtype_t dtype, int32_t prefix_fp8, int32_t B,
+                             int32_t H_q, int32_t H_kv, int32_t d, int32_t n_nodes, int32_t row_begin,
+                             int32_t max_prefix, mcsd_attention_plan_t *out);
+
 /* ---------------------------------------------------------------------------------------------------
  * Verification (Sec. 2.1; Sec. 3.1; Fig. 1 steps 4-6)
  *
@@ -263,7 +281,10 @@ int mcsd_tree_attention_tuned(const mcsd_attention_tuning_t *tuning, const mcsd_
  * out_path       : DEVICE int32 [B][gamma], accepted node ids from level 1 down, padded with -1
  * out_accept_len : DEVICE int32 [B]
  * out_new_tokens : DEVICE int32 [B][n_new], i.i.d. draws from the terminal distribution
- * workspace      : DEVICE, mcsd_verify_tree_workspace(...) bytes (0 for MCSD_DRAFT_INIT: may be NULL)
+ * workspace      : DEVICE, mcsd_verify_tree_workspace(...) bytes (0 for MCSD_DRAFT_INIT: may be NULL), 256-byte
+ *                  aligned; need not be initialised.  Afterwards it holds the walks of all b_1 level-1 subtrees, for
+ *                  inspection: int32 [B][b_1][gamma] paths (-1 padded), then int32 [B][b_1] accepted lengths, then
+ *                  int32 [B][b_1][max(n_new,1)] new tokens, each block starting at a multiple of 256 bytes
  * Limits: 1 <= V <= MCSD_MAX_VOCAB.
  * ------------------------------------------------------------------------------------------------- */
 size_t mcsd_verify_tree_workspace(const mcsd_mask_view_t *mask, mcsd_mode_t mode, int32_t B, int32_t n_new);

@@ -22,7 +22,8 @@ EXPORTS = ["mcsd_strerror", "mcsd_build_mask", "mcsd_slice_mask", "mcsd_free_mas
            "mcsd_tree_attention_fp8kv_workspace", "mcsd_tree_attention_fp8kv",
            "mcsd_verify_tree_workspace", "mcsd_verify_tree", "mcsd_verify_tree_sampling", "mcsd_commit_path", "mcsd_early_stop_distribution",
            "mcsd_early_stop_hidden", "mcsd_profile_next", "mcsd_stream_read", "mcsd_workspace_init",
-           "mcsd_tree_attention_tuned_workspace", "mcsd_tree_attention_tuned", "mcsd_tree_attention_static"]
+           "mcsd_tree_attention_tuned_workspace", "mcsd_tree_attention_tuned", "mcsd_tree_attention_static",
+           "mcsd_tree_attention_plan"]
 STATIC_SCRATCH_BYTES = 40 * 1024 * 1024
 DECISION_MAX_K, MLP_MAX_LAYERS, MLP_MAX_WIDTH, MLP_MAX_INPUTS = 16, 3, 512, 8192
 
@@ -46,6 +47,13 @@ class Mlp(C.Structure):
 class AttentionTuning(C.Structure):
     """mcsd_attention_tuning_t"""
     _fields_ = [("key_splits", C.c_int32), ("natural_order", C.c_int32), ("fold", C.c_int32), ("stages", C.c_int32)]
+
+
+class AttentionPlan(C.Structure):
+    """mcsd_attention_plan_t"""
+    _fields_ = [("mfma_path", C.c_int32), ("query_blocks", C.c_int32), ("key_splits", C.c_int32),
+                ("workgroups", C.c_int32), ("stages", C.c_int32), ("fold_in_kernel", C.c_int32),
+                ("ordered_by_length", C.c_int32)]
 
 
 class McsdError(RuntimeError):
@@ -117,6 +125,9 @@ def _load() -> C.CDLL:
     lib.mcsd_tree_attention_static.restype = C.c_int
     lib.mcsd_tree_attention_static.argtypes = [C.POINTER(MaskView), C.c_int, i32, i32, i32, vp, vp, vp, i64, vp, vp, vp,
                                                vp, i64, i32, C.c_float, vp, vp]
+    lib.mcsd_tree_attention_plan.restype = C.c_int
+    lib.mcsd_tree_attention_plan.argtypes = [C.POINTER(AttentionTuning), C.c_int, i32, i32, i32, i32, i32, i32, i32, i32,
+                                             C.POINTER(AttentionPlan)]
     lib.mcsd_workspace_init.restype = C.c_int
     lib.mcsd_workspace_init.argtypes = [vp, sz, vp]
     lib.mcsd_tree_attention_tuned_workspace.restype = sz
@@ -255,6 +266,14 @@ def tree_attention_static(view: MaskView, dtype: int, B: int, H: int, d: int, q:
                                         _ptr(k_prefix), _ptr(v_prefix), _ptr(seq_base_dev), _ptr(prefix_lens_dev),
                                         head_stride, max_prefix, softmax_scale, _ptr(out), _stream(stream))
     _check(st, "mcsd_tree_attention_static")
+
+
+def tree_attention_plan(tuning: Optional[AttentionTuning], dtype: int, prefix_fp8: int, B: int, H_q: int, H_kv: int,
+                        d: int, n_nodes: int, row_begin: int, max_prefix: int) -> AttentionPlan:
+    plan = AttentionPlan()
+    _check(lib.mcsd_tree_attention_plan(_tuning_ref(tuning), dtype, prefix_fp8, B, H_q, H_kv, d, n_nodes, row_begin,
+                                        max_prefix, C.byref(plan)), "mcsd_tree_attention_plan")
+    return plan
 
 
 def tree_attention_rows_workspace(B: int, H: int, d: int, n_nodes: int, row_begin: int, max_prefix: int) -> int:

@@ -1525,6 +1525,28 @@ extern "C" size_t mcsd_tree_attention_tuned_workspace(const mcsd_attention_tunin
     return workspace_query(tuning, prefix_fp8 != 0, B, H_q, H_kv, d, n_nodes, row_begin, max_prefix);
 }
 
+extern "C" int mcsd_tree_attention_plan(const mcsd_attention_tuning_t *tuning, mcsd_dtype_t dtype, int32_t prefix_fp8,
+                                        int32_t B, int32_t H_q, int32_t H_kv, int32_t d, int32_t n_nodes, int32_t row_begin,
+                                        int32_t max_prefix, mcsd_attention_plan_t *out)
+{
+    if (!out || B < 1 || H_q < 1 || H_kv < 1 || H_q % H_kv != 0 || (d != 64 && d != 128) || n_nodes < 1 ||
+        n_nodes > MCSD_ATTN_MAX_NODES || max_prefix < 0 || row_begin < 0 || row_begin >= n_nodes ||
+        (dtype != MCSD_F32 && dtype != MCSD_BF16) || (prefix_fp8 && (d != 128 || dtype != MCSD_BF16)))
+        return MCSD_EINVAL;
+    if (tuning && (tuning->key_splits < 0 || tuning->key_splits > 64 || tuning->fold < 0 || tuning->fold > 1 ||
+                   (tuning->stages != 0 && tuning->stages != 2 && tuning->stages != 4)))
+        return MCSD_EINVAL;
+    const AttnPlan pl = make_plan(dtype, B, H_q, H_kv, n_nodes - row_begin, max_prefix, prefix_fp8 != 0, tuning);
+    out->mfma_path = dtype == MCSD_BF16;
+    out->query_blocks = pl.QBP;
+    out->key_splits = pl.S;
+    out->workgroups = (int32_t)((int64_t)pl.G * pl.units * B);
+    out->stages = dtype == MCSD_BF16 ? pl.NS : 0;
+    out->fold_in_kernel = pl.fold;
+    out->ordered_by_length = pl.pair_cus > 0;
+    return MCSD_OK;
+}
+
 extern "C" int mcsd_tree_attention(const mcsd_mask_view_t *mask, mcsd_dtype_t dtype, int32_t B, int32_t H, int32_t d,
                                    const void *q, const void *k_tree, const void *v_tree, int64_t node_stride,
                                    const void *k_prefix, const void *v_prefix, const int64_t *seq_base_dev,
