@@ -397,6 +397,81 @@ def config_section(name, hip, args, traffic, gammas=(None,), n_sets=1, with_step
     return out
 
 
+def dynamic_section(binding, torch, iterations):
+    """One iteration of the dynamic setting (Sec. 3.2, 3.3; width 16, depth 5 of Sec. 4.1) on the fork-shaped tree:
+    per level the draft model's attention for the newest rows (the shape of a 68M Llama draft: 2 layers, 12 heads of
+    64) and the stop decision, whose flag the host reads; at the decided draft length the target's 32 attention layers,
+    verification and update.  One HIP graph per level and one per draft length.  The iteration as the device decides
+    it is checked against the same sequence composed from the oracle; the time per iteration is reported for every
+    draft length (levels forced, flags still read)."""
+    import numpy as np
+    import oracle
+    import gpu_helpers as H
+    from workloads import WORKLOADS, scaled
+    w = WORKLOADS["fork"]
+    wd = scaled(w, H=12, d=64, cfg_id=w.cfg_id + 200)
+    seed, out_bias = 1, 0.8                   # the stand-in decision model's outputs straddle beta at level 2 with this bias
+    it = H.DynamicIteration(binding, w, wd, 2, N_LAYERS, seed, out_bias)
+    levels, targets = it.capture()
+    gamma, flags = it.run(lambda g: levels[g].replay(), lambda g: targets[g].replay())
+    got = it.snapshot(gamma)
+    # ---- the oracle's side of the same iteration ----
+    vi, off, V = it.vi, it.off, w.V
+    want_gamma = it.D
+    for g in range(1, it.D):
+        rows = vi["q_draft"][:, 1 + off[g - 1]:1 + off[g]]
+        pr = oracle.mlp(it.ws_host, it.bs_host, oracle.decision_features(rows.reshape(-1, V), it.K)).reshape(w.B, it.W)
+        st = oracle.early_stop(pr, it.BETA)
+        assert np.abs(pr - it.BETA).min() > 1e-5 and np.array_equal(flags[g - 1], st), f"stop decision of level {g} differs from the oracle"
+        if st.all():
+            want_gamma = g
+            break
+    assert gamma == want_gamma, "the device stopped drafting at another level than the oracle"
+    n = off[gamma]
+    M = oracle.build_mask(w.branching)
+    H.assert_close(got["draft_out"][0].astype(np.float64), oracle.tree_attention(it.draft_host[0], M, n), "bf16", "dynamic: draft layer 0")
+    H.assert_close(got["target_out"][0].astype(np.float64), oracle.tree_attention(it.target_host[0], M, n), "bf16", "dynamic: target layer 0")
+    tokens = np.ascontiguousarray(vi["tokens"][:, :n])
+    want = oracle.verify_tree(0, w.branching[:gamma], tokens, np.ascontiguousarray(vi["p_target"][:, :1 + n]),
+                              np.ascontiguousarray(vi["q_draft"][:, :1 + off[gamma - 1]]),
+                              np.ascontiguousarray(vi["u_accept"][:, :n]), vi["u_sample"])
+    assert all(np.array_equal(got[k], x) for k, x in zip(("path", "alen", "new"), want)), "dynamic: verification differs from the oracle"
+    kp, vp, new_lens = oracle.commit_path(it.target_host[0], gamma, n, want[0], want[1])
+    assert np.array_equal(got["caches"][0][0].view(kp.dtype), kp) and np.array_equal(got["caches"][0][1].view(vp.dtype), vp) \
+        and np.array_equal(got["lens"], new_lens), "dynamic: caches after the update differ from the oracle"
+    want_ids, want_n = oracle.commit_ids(gamma, tokens, want[0], want[1], want[2], 1)
+    assert np.array_equal(got["ids"], want_ids) and np.array_equal(got["n_ids"], want_n)
+    # ---- time per iteration by draft length ----
+    by_gamma = {}
+    lf, tf = (lambda g: levels[g].replay()), (lambda g: targets[g].replay())
+    for g in range(1, it.D + 1):
+        for _ in range(5):
+            it.run(lf, tf, force_gamma=g, caches=False)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(iterations):
+            it.run(lf, tf, force_gamma=g, caches=False)
+        torch.cuda.synchronize()
+        t_all = (time.perf_counter() - t0) / iterations
+        t0 = time.perf_counter()
+        for _ in range(iterations):
+            targets[g].replay()
+        torch.cuda.synchronize()
+        t_target = (time.perf_counter() - t0) / iterations
+        by_gamma[f"gamma{g}"] = {"tree_tokens": off[g], "ms_per_iteration": round(t_all * 1e3, 4),
+                                 "of_which_target_step_ms": round(t_target * 1e3, 4),
+                                 "draft_levels_and_decisions_ms": round((t_all - t_target) * 1e3, 4),
+                                 "tree_tokens_per_s": round(w.B * off[g] / t_all, 1)}
+    return {"workload": f"fork: B{w.B} H{w.H} d{w.d} bf16 prefix {w.prefix_max} tree {w.branching} V={V}; draft attention "
+                        f"2 layers x {wd.H} heads of {wd.d}; decision model top-{it.K} + entropy -> 64 -> 1, beta {it.BETA}",
+            "decided_on_device": {"gamma": int(gamma), "stop_flags_by_level": [int(f[0]) for f in flags],
+                                  "accept_len": int(got["alen"][0]), "verified_vs_oracle":
+                                  "stop flags, one draft and one target layer in full, verification, updated cache, ids"},
+            "launch": "one HIP graph per level (draft attention + decision), one per draft length (32 target layers + "
+                      "verification + update); the host reads the 4-byte stop flag after each level",
+            "iterations_timed": iterations, "by_draft_length": by_gamma}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -415,6 +490,8 @@ def main():
                     help="sequences of the batched verification section (0 skips it)")
     ap.add_argument("--decision-batch", type=int, default=64,
                     help="trees per call in the early-stop decision-model section (0 = skip)")
+    ap.add_argument("--dynamic-iterations", type=int, default=50,
+                    help="timed iterations per draft length of the dynamic-setting section on the fork-shaped tree (0 skips it)")
     ap.add_argument("--no-fp8kv", action="store_true", help="skip the fp8 prefix-cache variants of cfg4 / cfg5")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--eager", action="store_true", help="launch the step's kernels one by one instead of replaying a HIP graph")
@@ -799,6 +876,12 @@ def main():
                 "workload": f"{Bd} trees of width {Wd}, hidden width {hw[0]}, MLP {'-'.join(map(str, hw))} (latency-bound)"}
         except Exception as ex:
             extra["early_stop"] = {"error": repr(ex)}
+    if args.dynamic_iterations > 0:
+        try:
+            out["dynamic_iteration"] = dynamic_section(binding, torch, args.dynamic_iterations)
+        except Exception as ex:
+            out["dynamic_iteration"] = {"error": repr(ex)}
+        torch.cuda.empty_cache()
     # yardstick: what the HBM of this machine delivers to a plain read-only streaming kernel (4 GiB buffer)
     try:
         buf = torch.empty(4 << 30, dtype=torch.uint8, device="cuda")
