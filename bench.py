@@ -371,6 +371,10 @@ def config_section(name, hip, args, traffic, gammas=(None,), n_sets=1, with_step
         reps = args.extra_reps if es.alg_bytes > 1e8 else args.kernel_reps
         r = roofline_of(es, hip, reps, traffic, warm=reps)
         torch.cuda.synchronize()
+        # The same launch out of a short idle period: the figures above are sustained ones (the chip lowers its clocks
+        # under the combined load of the matrix cores and the memory stream); this one shows what that costs.
+        time.sleep(0.05)
+        r["launch_after_idle_us"] = round(time_kernel(es, hip, es.binding.KERNEL_ATTN_SWEEP, lambda i: es.attention(i), 3)[0] * 1e3, 2)
         t0e = time.perf_counter()
         for i in range(reps):
             es.attention(i)
@@ -707,6 +711,9 @@ def main():
 
             gs = Ctx(binding, torch)
             g_avg, g_med, g_p10, g_p90 = time_kernel(gs, hip, binding.KERNEL_ATTN_SWEEP, gcall, args.extra_reps, warm=args.extra_reps)
+            torch.cuda.synchronize()
+            time.sleep(0.05)
+            g_idle = time_kernel(gs, hip, binding.KERNEL_ATTN_SWEEP, gcall, 3)[0]
             gbytes = sum(2 * wq.d * (Hkv * (2 * int(L) + 2 * n) + wq.H * 2 * n) for L in lens)
             gflops = sum(wq.H * 4 * n * (int(L) + n) * wq.d for L in lens)
             gp = binding.tree_attention_plan(None, 1, 0, wq.B, wq.H, Hkv, wq.d, n, 0, int(wq.prefix_max))
@@ -717,6 +724,7 @@ def main():
                                  "traffic": None, "flops_per_launch": int(gflops), "algorithmic_bytes_per_launch": int(gbytes),
                                  "hbm_GBps": round(gbytes / (g_avg * 1e-3) / 1e9, 1), "avg_launch_us": round(g_avg * 1e3, 2),
                                  "p10_us": round(g_p10 * 1e3, 2), "p90_us": round(g_p90 * 1e3, 2), "launches_timed": args.extra_reps,
+                                 "launch_after_idle_us": round(g_idle * 1e3, 2),
                                  "verified_vs_oracle": "every element",
                                  "workload": f"cfg4 with {wq.H} query heads on {Hkv} key/value heads (B{wq.B} N={n})"}
             del aq, ak
@@ -753,6 +761,9 @@ def main():
 
                 fs = Ctx(binding, torch)
                 f_avg, f_med, f_p10, f_p90 = time_kernel(fs, hip, binding.KERNEL_ATTN_SWEEP, fcall, args.extra_reps, warm=args.extra_reps)
+                torch.cuda.synchronize()
+                time.sleep(0.05)
+                f_idle = time_kernel(fs, hip, binding.KERNEL_ATTN_SWEEP, fcall, 3)[0]
                 fbytes, fflops = attention_algorithmic(w8, lens, n8, kv_bytes_per_elem=1)
                 fp = binding.tree_attention_plan(None, 1, 1, w8.B, w8.H, w8.H, w8.d, n8, 0, cap)
                 kname = f"tree_attn_bf16_kernel<{w8.d}, {fp.query_blocks}, {fp.stages}, true>"
@@ -767,7 +778,7 @@ def main():
                          "mfma_tflops": round(fflops / (f_avg * 1e-3) / 1e12, 1),
                          "mfma_frac": round(fflops / (f_avg * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
                          "time_at_hbm_peak_us": round(t_hbm * 1e6, 1), "time_at_mfma_peak_us": round(t_mfma * 1e6, 1),
-                         "launches_timed": args.extra_reps,
+                         "launches_timed": args.extra_reps, "launch_after_idle_us": round(f_idle * 1e3, 2),
                          "attn_tree_tokens_per_s": round(w8.B * n8 / (f_avg * 1e-3), 1), "verified_vs_oracle": "every element",
                          "workload": f"{name} with the prefix cache in fp8 E4M3 (B{w8.B} N={n8})"}
                 if issue_bound:
@@ -901,6 +912,28 @@ def main():
         del buf
     except Exception as ex:
         out["stream_read_probe"] = {"error": repr(ex)}
+    # the other yardstick: what the matrix cores of this machine sustain in a plain library GEMM (bf16, 8192^3, fp32
+    # accumulation) launched back to back -- the datasheet's dense peak assumes clocks that a loaded chip does not hold
+    try:
+        n = 8192
+        ga = torch.randn(n, n, device="cuda", dtype=torch.bfloat16)
+        gb = torch.randn(n, n, device="cuda", dtype=torch.bfloat16)
+        gc = torch.empty(n, n, device="cuda", dtype=torch.bfloat16)
+        for _ in range(20):
+            torch.matmul(ga, gb, out=gc)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(50):
+            torch.matmul(ga, gb, out=gc)
+        torch.cuda.synchronize()
+        tf = 2.0 * n ** 3 / ((time.perf_counter() - t0) / 50) / 1e12
+        out["gemm_probe"] = {"TFLOP/s": round(tf, 1), "frac_of_peak": round(tf / MFMA_BF16_PEAK_TFLOPS, 4),
+                             "what": f"library bf16 GEMM {n}^3, 50 launches back to back"}
+        for r in [v for v in extra.values() if v.get("bound") == "mfma"]:
+            r["frac_of_gemm_probe"] = round(r["achieved"] / tf, 4)
+        del ga, gb, gc
+    except Exception as ex:
+        out["gemm_probe"] = {"error": repr(ex)}
     if extra:
         out["other_workloads"] = extra
     print(json.dumps(out), flush=True)

@@ -12,7 +12,8 @@
 // and the exponentiated scores are already in the register layout of the B operand of O^T += V^T * P^T.
 // V^T operands come from the row-major V tile through the LDS transpose load (ds_read_b64_tr_b16).
 // Wavefronts that share a query block split each tile's keys (key groups) and are merged through LDS at the
-// end; key splits across workgroups write partial results that a small second kernel folds.
+// end; key splits across workgroups write partial results, which the workgroup of the (sequence, head) that arrives
+// last folds at the end of the same kernel (a small second kernel when the splits do not share one die's L2).
 // The tree's own keys are extra tiles whose scores are masked with the packed bitmask slice.
 //
 // fp32 path: split / online-softmax structure on the vector ALU (small reference-precision shapes).
@@ -137,7 +138,7 @@ AttnPlan make_plan(int dtype, int B, int Hq, int Hkv, int n_rows, int max_prefix
     const long tiles_max = (max_prefix + pl.T - 1) / pl.T;
     // Key splits: enough workgroups for two per compute unit, at least four tiles per split (five with four query
     // blocks, whose partial result is twice the bytes), at most 8 splits: every split costs a partial result of n
-    // rows that is written, written back and folded by the second kernel.
+    // rows that is written, read back and folded.
     long S = (512 + bh - 1) / bh;
     // (the vector-ALU path is slow per tile: split it all the way)
     const long min_tiles = dtype == MCSD_BF16 ? (pl.QBP == 4 ? 5 : 4) : 1;
@@ -936,8 +937,7 @@ void tree_attn_bf16_kernel(const AttnParams p)
         return;
     }
 
-    // ---- key splits: every split writes (O, m, l) in register-fragment order (fully coalesced); a small second
-    // kernel folds them (a kernel boundary is the cheapest device-wide hand-over for this little data) ----
+    // ---- key splits: every split writes (O, m, l) in register-fragment order (fully coalesced) ----
     if (kg == 0 && qrow < p.n) {                           // padded query rows are never read back
         float *po = p.part_o + ((bh * p.SP + slot_id) * (int64_t)(QBP * 32 * D)) + qb * 32 * D;
 #pragma unroll
