@@ -260,10 +260,29 @@ def roofline_of(st, hip, reps, traffic, warm=0):
             "mfma_tflops": round(st.alg_flops / (avg * 1e-3) / 1e12, 1), "launches_timed": reps}
 
 
+_FLUSH = None
+
+
+def flush_caches(torch, i):
+    """Overwrites 512 MB (twice the last-level cache), so that the next kernel finds none of its inputs in a cache."""
+    global _FLUSH
+    if _FLUSH is None:
+        _FLUSH = torch.empty(512 << 20, dtype=torch.uint8, device="cuda")
+    _FLUSH.fill_(i & 1)
+
+
 def verify_section(st, hip, reps):
-    """The verification call of a Step as it stands: kernel time, the vocabulary bytes its walks need, acceptance."""
+    """The verification call of a Step as it stands: kernel time, the vocabulary bytes its walks need, acceptance.
+    The probability rows of one call (a few MB) would stay in the last-level cache between launches, so the figure
+    set against the HBM peak is timed with the caches overwritten before every launch; the time with the rows still
+    cached is reported beside it."""
     b, torch = st.binding, st.torch
-    v_avg = time_kernel(st, hip, b.KERNEL_VERIFY_WALK, lambda i: st.verify(), reps, warm=8)[0]
+    v_warm = time_kernel(st, hip, b.KERNEL_VERIFY_WALK, lambda i: st.verify(), reps, warm=8)[0]
+
+    def cold(i):
+        flush_caches(torch, i)
+        st.verify()
+    v_avg = time_kernel(st, hip, b.KERNEL_VERIFY_WALK, cold, min(reps, 24), warm=2)[0]
     torch.cuda.synchronize()
     paths, lens = st.walks()
     vb = walk_bytes(st.w, st.gamma, st.mode, st.n_new, paths, lens)
@@ -273,7 +292,7 @@ def verify_section(st, hip, reps):
             "mode": "target-init" if st.mode else "draft-init", "walks": int(len(lens)),
             "achieved": round(vb / (v_avg * 1e-3) / 1e9, 2), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
             "frac": round(vb / (v_avg * 1e-3) / 1e9 / HBM_PEAK_GBPS, 5), "algorithmic_bytes_per_launch": int(vb),
-            "avg_launch_us": round(v_avg * 1e3, 2),
+            "avg_launch_us": round(v_avg * 1e3, 2), "rows_still_cached_launch_us": round(v_warm * 1e3, 2),
             "verify_tree_tokens_per_s": round(st.w.B * st.n / (v_avg * 1e-3), 1),
             "mean_accept_len": round(float(alen.mean()), 3),
             "alpha": round(float((alen.mean() - (1 if st.mode else 0)) / tested), 3) if tested > 0 else None}
@@ -566,7 +585,10 @@ def main():
     per_seed = []
     for s, vi in enumerate(seed_inputs):
         st.set_verify_inputs(s, vi)
-        t = time_kernel(st, hip, binding.KERNEL_VERIFY_WALK, lambda i: st.verify(), 16, warm=4)[0]
+        def cold_verify(i):
+            flush_caches(torch, i)
+            st.verify()
+        t = time_kernel(st, hip, binding.KERNEL_VERIFY_WALK, cold_verify, 8, warm=1)[0]
         torch.cuda.synchronize()
         al = st.alen.cpu().numpy()
         per_seed.append((t * 1e3, int(np.minimum(al + 1, st.gamma).sum()), float(al.mean())))
@@ -610,7 +632,10 @@ def main():
                                    vi2["u_accept"], vi2["u_sample"], replacement=False)
         got2 = (o2[0].cpu().numpy(), o2[1].cpu().numpy(), o2[2].cpu().numpy()[:, :st.n_new])
         assert all(np.array_equal(a, b) for a, b in zip(got2, want2)), "without-replacement verification differs from the oracle"
-        v2_avg = time_kernel(st, hip, binding.KERNEL_VERIFY_WALK, v2call, args.kernel_reps)[0]
+        def v2cold(i):
+            flush_caches(torch, i)
+            v2call(i)
+        v2_avg = time_kernel(st, hip, binding.KERNEL_VERIFY_WALK, v2cold, 24, warm=2)[0]
         out["kernels_us"]["verify_walk_without_replacement"] = round(v2_avg * 1e3, 2)
         out["verify_without_replacement"] = {"avg_launch_us": round(v2_avg * 1e3, 2), "verified_vs_oracle": True,
                                              "mean_accept_len": round(float(want2[1].mean()), 3)}
@@ -812,12 +837,18 @@ def main():
             def vcall(i):
                 binding.verify_tree(vv, 0, wb.B, wb.V, dt_, dp, dq, vi["p_target"].shape[1] * wb.V, vi["q_draft"].shape[1] * wb.V,
                                     dua, dus, 1, o_path, o_len, o_new, None)
-            vb_avg = time_kernel(vs, hip, binding.KERNEL_VERIFY_WALK, vcall, 30, warm=10)[0]
+            vb_warm = time_kernel(vs, hip, binding.KERNEL_VERIFY_WALK, vcall, 30, warm=10)[0]
+
+            def vcall_cold(i):       # the 39 MB of rows this call reads would otherwise come from the last-level cache
+                flush_caches(torch, i)
+                vcall(i)
+            vb_avg = time_kernel(vs, hip, binding.KERNEL_VERIFY_WALK, vcall_cold, 24, warm=2)[0]
             vbytes = walk_bytes(wb, vv.gamma, 0, 1, got[0], got[1])
             extra["verify_batch%d" % wb.B] = {
                 "bound": "hbm", "kernel": "verify_walk_fast_kernel", "achieved": round(vbytes / (vb_avg * 1e-3) / 1e9, 1),
                 "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(vbytes / (vb_avg * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
                 "algorithmic_bytes_per_launch": int(vbytes), "avg_launch_us": round(vb_avg * 1e3, 2),
+                "rows_still_cached_launch_us": round(vb_warm * 1e3, 2),
                 "sequences_per_s": round(wb.B / (vb_avg * 1e-3), 1), "mean_accept_len": round(float(got[1].mean()), 3),
                 "alpha": round(float(got[1].mean()) / vv.gamma, 3),
                 "verified_vs_oracle": True, "workload": f"{w_name} verification, B={wb.B}, V={wb.V}, draft-init"}

@@ -198,11 +198,11 @@ int mcsd_tree_attention_fp8kv(const mcsd_mask_view_t *mask, int32_t B, int32_t H
  * device array of MCSD_STATIC_SCRATCH_BYTES inside the library (one copy per GPU, held until the process ends; its
  * address is looked up on the first call on a device, which also enqueues one small fill kernel on the stream).
  * The call allocates and frees nothing.  Shapes that need more than the array holds are MCSD_EUNSUPPORTED and nothing
- * is enqueued (the five headline configurations need 0 to 34.2 MB; larger batches of long prefixes under wide trees
+ * is enqueued (the five headline configurations need 0 to 17.4 MB; larger batches of long prefixes under wide trees
  * need more and must bring a workspace).  All calls on one GPU share the array: calls that overlap in time on one GPU,
  * on whatever streams, race on it and must be ordered by the caller.
  * ------------------------------------------------------------------------------------------------- */
-enum { MCSD_STATIC_SCRATCH_BYTES = 40 * 1024 * 1024 };
+enum { MCSD_STATIC_SCRATCH_BYTES = 24 * 1024 * 1024 };
 
 int mcsd_tree_attention_static(const mcsd_mask_view_t *mask, mcsd_dtype_t dtype, int32_t B, int32_t H, int32_t d,
                                const void *q, const void *k_tree, const void *v_tree, int64_t node_stride,

@@ -24,7 +24,7 @@ EXPORTS = ["mcsd_strerror", "mcsd_build_mask", "mcsd_slice_mask", "mcsd_free_mas
            "mcsd_early_stop_hidden", "mcsd_profile_next", "mcsd_stream_read", "mcsd_workspace_init",
            "mcsd_tree_attention_tuned_workspace", "mcsd_tree_attention_tuned", "mcsd_tree_attention_static",
            "mcsd_tree_attention_plan"]
-STATIC_SCRATCH_BYTES = 40 * 1024 * 1024
+STATIC_SCRATCH_BYTES = 24 * 1024 * 1024
 DECISION_MAX_K, MLP_MAX_LAYERS, MLP_MAX_WIDTH, MLP_MAX_INPUTS = 16, 3, 512, 8192
 
 

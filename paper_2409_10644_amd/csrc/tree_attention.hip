@@ -61,7 +61,7 @@ struct AttnParams {
     int32_t G;        // workgroups per (b,h): S, plus one for the tree's own keys when the bf16 sweep splits the prefix
     int32_t tps;      // tiles per split (bf16 sweep): split s owns tiles [s*tps, (s+1)*tps) of every sequence
     int32_t SP;       // partial results per (b,h) (== G)
-    float *part_o;    // [B*H][SP][n][D]
+    float *part_o;    // [B*H][SP][n][D]; the bf16 sweep keeps its partial O there as bf16 (see the end of the sweep kernel)
     float *part_m;    // [B*H][SP][n]   reference maximum of the raw scores
     float *part_l;    // [B*H][SP][n]   sum of exp2((s - m) * c)
 };
@@ -491,11 +491,12 @@ __device__ inline void attn_tile(const unsigned char *stage, const LaneAddr la, 
 // kg, kg + KG, ..  ro / rm / rl describe the unit's partial O (fragment order), maxima and denominators and end after
 // the last partial result in use: a load beyond it returns zero without touching memory, so nothing below branches
 // on the number of partial results and all loads of a round are in flight together.
-// A round: NSLOT partial results x two of the lane's float4 positions (j = 2 jp, 2 jp + 1) of a column block.  The
-// rounds of a column block are (jp 0, first group), [(jp 0, second group),] (jp 1, ...): an accumulator lives across
-// the groups of one jp and its result is stored after every round (with two groups the first store of a position is
-// overwritten by the complete one: same lane, same address, program order).  The loads of the next round are issued
-// before this one is added up (two register buffers); a round beyond the last loads from beyond the end, i.e. nothing.
+// A round: NSLOT partial results x the lane's two 16-byte chunks (jp = 0, 1: eight bf16 each = its float4 positions
+// j = 2 jp, 2 jp + 1) of a column block.  The rounds of a column block are (first group), [(second group)]: an
+// accumulator lives across the groups and its result is stored after every round (with two groups the first store
+// of a position is overwritten by the complete one: same lane, same address, program order).  The loads of the next
+// round are issued before this one is added up (two register buffers); a round beyond the last loads from beyond the
+// end, i.e. nothing, and is not added up.
 // Partial results are added in slot order whoever arrived last, so the result is reproducible.
 // Nothing here may spill: a workgroup's scratch memory is cold at this point, every first touch a trip to HBM (a
 // variant that spilled its weights took 9.7 us for five partial results, against 3).
@@ -506,7 +507,7 @@ __device__ __attribute__((always_inline)) inline void fold_partials(const __amdg
 {
     constexpr int CB = D / 32;
     constexpr int NW = NSLOT == 8 ? FOLD_MAX_PARTIALS : NSLOT;      // partial results this variant can hold
-    constexpr int SLOT_BYTES = QBP * 32 * D * 4;
+    constexpr int SLOT_BYTES = QBP * 32 * D * 2;
     float wgt[NW], lw[NW];
 #pragma unroll
     for (int i = 0; i < NW; ++i) {
@@ -514,16 +515,16 @@ __device__ __attribute__((always_inline)) inline void fold_partials(const __amdg
         lw[i] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rl, (i * QBP * 32 + ln) * 4, 0, 1));
     }
     const int ngrp = NSLOT == 8 && n_active > NSLOT ? 2 : 1;
-    const int rounds = ((CB - kg + KG - 1) / KG) * 2 * ngrp;        // even
+    const int rounds = ((CB - kg + KG - 1) / KG) * ngrp;
     typedef u32x4_t Round[NSLOT][2];
     auto issue = [&](Round &buf, int r) {
-        const int grp = r % ngrp, jp = (r / ngrp) & 1, cb = kg + (r / (2 * ngrp)) * KG;
-        int off = (((cb * 4 + jp * 2) * 2 + g) * 32 + ln) * 16 + grp * NSLOT * SLOT_BYTES;
+        const int grp = r % ngrp, cb = kg + (r / ngrp) * KG;
+        int off = ((cb * 4 + g) * 32 + ln) * 16 + grp * NSLOT * SLOT_BYTES;
         if (r >= rounds) off = 0x40000000;                          // (uniform select) beyond every workspace
 #pragma unroll
         for (int i = 0; i < NSLOT; ++i)
 #pragma unroll
-            for (int j = 0; j < 2; ++j) buf[i][j] = __builtin_amdgcn_raw_buffer_load_b128(ro, off + j * 1024 + i * SLOT_BYTES, 0, 1);
+            for (int jp = 0; jp < 2; ++jp) buf[i][jp] = __builtin_amdgcn_raw_buffer_load_b128(ro, off + jp * 1024 + i * SLOT_BYTES, 0, 1);
     };
     Round bufA, bufB;
     issue(bufA, 0);
@@ -545,9 +546,9 @@ __device__ __attribute__((always_inline)) inline void fold_partials(const __amdg
         for (int q4 = 0; q4 < NW / 4; ++q4)
             wlds[q4 * 256] = (f32x4_t){wgt[4 * q4], wgt[4 * q4 + 1], wgt[4 * q4 + 2], wgt[4 * q4 + 3]};
     }
-    f32x4_t acc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
+    f32x4_t acc[4] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
     auto add_up = [&](Round &buf, int r) {
-        const int grp = r % ngrp, jp = (r / ngrp) & 1, cb = kg + (r / (2 * ngrp)) * KG;
+        const int grp = r % ngrp, cb = kg + (r / ngrp) * KG;
         float w[NSLOT];
         if constexpr (NSLOT == 8) {
             const f32x4_t wa = wlds[(2 * grp) * 256], wb = wlds[(2 * grp + 1) * 256];
@@ -558,14 +559,18 @@ __device__ __attribute__((always_inline)) inline void fold_partials(const __amdg
             for (int i = 0; i < NSLOT; ++i) w[i] = wgt[i];
         }
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
+        for (int j = 0; j < 4; ++j) {                               // the lane's float4 position j of this column block
             if (grp == 0) acc[j] = (f32x4_t){0.f, 0.f, 0.f, 0.f};   // a new position starts from zero (a select)
 #pragma unroll
-            for (int i = 0; i < NSLOT; ++i) acc[j] += w[i] * __builtin_bit_cast(f32x4_t, buf[i][j]);   // slot order
+            for (int i = 0; i < NSLOT; ++i) {                       // slot order
+                const unsigned d0 = buf[i][j >> 1][2 * (j & 1)], d1 = buf[i][j >> 1][2 * (j & 1) + 1];   // four bf16: exact as fp32 bit patterns
+                const u32x4_t bits = {d0 << 16, d0 & 0xffff0000u, d1 << 16, d1 & 0xffff0000u};
+                acc[j] += w[i] * __builtin_bit_cast(f32x4_t, bits);
+            }
             bf16x4_t v;
 #pragma unroll
             for (int e = 0; e < 4; ++e) v[e] = (__bf16)(acc[j][e] * inv);
-            *(bf16x4_t *)(orow + cb * 32 + 8 * (2 * jp + j) + 4 * g) = v;
+            *(bf16x4_t *)(orow + cb * 32 + 8 * j + 4 * g) = v;
         }
     };
 #pragma unroll 1
@@ -576,7 +581,7 @@ __device__ __attribute__((always_inline)) inline void fold_partials(const __amdg
         __builtin_amdgcn_sched_barrier(0);
         issue(bufA, r + 2);
         __builtin_amdgcn_sched_barrier(0);
-        add_up(bufB, r + 1);
+        if (r + 1 < rounds) add_up(bufB, r + 1);                    // (uniform)
         __builtin_amdgcn_sched_barrier(0);
     }
 }
@@ -939,15 +944,18 @@ void tree_attn_bf16_kernel(const AttnParams p)
 
     // ---- key splits: every split writes (O, m, l) in register-fragment order (fully coalesced) ----
     if (kg == 0 && qrow < p.n) {                           // padded query rows are never read back
-        float *po = p.part_o + ((bh * p.SP + slot_id) * (int64_t)(QBP * 32 * D)) + qb * 32 * D;
+        // O goes out rounded to bf16, the precision the output itself has (one more rounding of 2^-9 relative to the
+        // partial's own magnitude; maxima and denominators stay fp32): half the bytes to write, acknowledge and fold.
+        // A lane's 16-byte chunk (cb, jp) holds its accumulator registers 8 jp .. 8 jp + 7 of column block cb.
+        __bf16 *po = (__bf16 *)p.part_o + ((bh * p.SP + slot_id) * (int64_t)(QBP * 32 * D)) + qb * 32 * D;
 #pragma unroll
         for (int cb = 0; cb < C::CB; ++cb)
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                f32x4_t v;
+            for (int jp = 0; jp < 2; ++jp) {
+                bf16x8_t v;
 #pragma unroll
-                for (int e = 0; e < 4; ++e) v[e] = qs.o[cb][4 * j + e];
-                *(f32x4_t *)(po + (((cb * 4 + j) * 2 + g) * 32 + ln) * 4) = v;
+                for (int e = 0; e < 8; ++e) v[e] = (__bf16)qs.o[cb][8 * jp + e];
+                *(bf16x8_t *)(po + (((cb * 2 + jp) * 2 + g) * 32 + ln) * 8) = v;
             }
         if (g == 0) {
             const int64_t prow = (bh * p.SP + slot_id) * (QBP * 32) + qb * 32 + ln;
@@ -1002,7 +1010,7 @@ void tree_attn_bf16_kernel(const AttnParams p)
     // all partial results read back in slot order, its own included: the result does not depend on who came last.
     // Loads go through buffer descriptors that end after the last partial result in use (see fold_partials).
     const __amdgpu_buffer_rsrc_t ro = __builtin_amdgcn_make_buffer_rsrc(
-        (void *)(p.part_o + (bh * p.SP) * (int64_t)(QBP * 32 * D) + qb * 32 * D), 0, (int)(n_active * QBP * 32 * D * 4), 0x00027000);
+        (void *)((__bf16 *)p.part_o + (bh * p.SP) * (int64_t)(QBP * 32 * D) + qb * 32 * D), 0, (int)(n_active * QBP * 32 * D * 2), 0x00027000);
     const __amdgpu_buffer_rsrc_t rm = __builtin_amdgcn_make_buffer_rsrc(
         (void *)(p.part_m + bh * p.SP * (QBP * 32) + qb * 32), 0, (int)(n_active * QBP * 32 * 4), 0x00027000);
     const __amdgpu_buffer_rsrc_t rl = __builtin_amdgcn_make_buffer_rsrc(
@@ -1052,7 +1060,9 @@ __global__ __launch_bounds__(256) void tree_attn_merge_bf16_kernel(const AttnPar
                 const int64_t prow = (bh * p.SP + s0 + i) * (QBP * 32) + lrow;
                 m[i] = p.part_m[prow];
                 l[i] = p.part_l[prow];
-                o[i] = *(const f32x4_t *)(p.part_o + ((bh * p.SP + s0 + i) * (int64_t)(QBP * 32 * D)) + qb * 32 * D + pos * 4);
+                const bf16x4_t ob = *(const bf16x4_t *)((const __bf16 *)p.part_o + ((bh * p.SP + s0 + i) * (int64_t)(QBP * 32 * D)) +
+                                                        qb * 32 * D + ((((f >> 2) * 2 + ((f >> 1) & 1)) * 2 + g) * 32 + ln) * 8 + (f & 1) * 4);
+                o[i] = (f32x4_t){(float)ob[0], (float)ob[1], (float)ob[2], (float)ob[3]};
             }
         }
         float Mn = M;
@@ -1271,7 +1281,7 @@ size_t workspace_bytes_for(const AttnPlan &pl, int dtype, int B, int d, int n)
 {
     if (pl.S == 1) return 0;
     const size_t rows = partial_rows(pl, dtype, B, n);
-    return WS_HEADER + WS_CTR_BYTES + 2 * align256(rows * sizeof(float)) + align256(rows * d * sizeof(float));
+    return WS_HEADER + WS_CTR_BYTES + 2 * align256(rows * sizeof(float)) + align256(rows * d * (dtype == MCSD_BF16 ? 2 : sizeof(float)));
 }
 
 // Prepares a workspace: tag word, zero counters.  One thread per 16 bytes of the header and counter area.

@@ -57,7 +57,7 @@ def test_the_same_call_repeated_gives_the_same_bits(binding, H):
 
 
 def test_shapes_beyond_the_array_are_rejected_before_any_launch(binding, H):
-    w = scaled(WORKLOADS["cfg5"], B=12, prefix_min=64, prefix_max=64, cfg_id=98)     # the plan is made from max_prefix
+    w = scaled(WORKLOADS["cfg5"], B=14, prefix_min=64, prefix_max=64, cfg_id=98)     # the plan is made from max_prefix
     ad = H.AttnDevice(attention_inputs(w, seed=0))
     v = binding.slice_mask(binding.build_mask(w.branching), w.gamma_max)
     assert binding.tree_attention_workspace(ad.B, ad.H, ad.d, v.n_nodes, 16384) > binding.STATIC_SCRATCH_BYTES
