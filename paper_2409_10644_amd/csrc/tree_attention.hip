@@ -1019,6 +1019,7 @@ void tree_attn_bf16_kernel(const AttnParams p)
     // as few slots per round as hold the partial results: a load beyond the end still costs its turn in the L1
     if (n_active <= 3) fold_partials<D, QBP, C::KG, 3>(ro, rm, rl, n_active, kg, g, ln, cm, orow, (f32x4_t *)ring + tid);
     else if (n_active <= 5) fold_partials<D, QBP, C::KG, 5>(ro, rm, rl, n_active, kg, g, ln, cm, orow, (f32x4_t *)ring + tid);
+    else if (n_active <= 7) fold_partials<D, QBP, C::KG, 7>(ro, rm, rl, n_active, kg, g, ln, cm, orow, (f32x4_t *)ring + tid);
     else fold_partials<D, QBP, C::KG, 8>(ro, rm, rl, n_active, kg, g, ln, cm, orow, (f32x4_t *)ring + tid);
 }
 
