@@ -523,6 +523,8 @@ def main():
     ap.add_argument("--key-splits", type=int, default=0,
                     help="measurement sweeps: key splits of the headline workload's attention (0 = the library's plan)")
     ap.add_argument("--stages", type=int, default=0, help="measurement sweeps: LDS stages of the bf16 K/V ring (0 = the library's plan)")
+    ap.add_argument("--tree-keys", type=int, default=0,
+                    help="measurement sweeps: which workgroup takes the tree's own keys (0 = the library's plan, 1 own, 2 first split, 3 last split)")
     ap.add_argument("--fold-kernel", action="store_true",
                     help="measurement sweeps: fold the key splits' partial results in a second kernel")
     ap.add_argument("--traffic-calibration", action="store_true",
@@ -557,8 +559,9 @@ def main():
     kv_bytes = w.B * w.H * w.prefix_max * w.d * (2 if w.dtype == "bf16" else 4) * 2
     n_sets = N_LAYERS if kv_bytes * N_LAYERS <= (8 << 30) else max(1, min(N_LAYERS, (2 << 30) // kv_bytes))
     tuning = None
-    if args.key_splits or args.fold_kernel or args.stages:
-        tuning = binding.AttentionTuning(key_splits=args.key_splits, fold=1 if args.fold_kernel else 0, stages=args.stages)
+    if args.key_splits or args.fold_kernel or args.stages or args.tree_keys:
+        tuning = binding.AttentionTuning(key_splits=args.key_splits, fold=1 if args.fold_kernel else 0, stages=args.stages,
+                                         tree_keys=args.tree_keys)
     # the verification draw of the timed step: a typical one (see pick_verify_seed), not whatever seed 0 gives
     v_seed, seed_inputs, seed_lens = pick_verify_seed(w, w.gamma_max, w.mode)
     st = Step(w_name, n_sets, tuning=tuning, verify_seed=v_seed)
@@ -687,9 +690,10 @@ def main():
         for i in range(20):
             commit_once(i)
         torch.cuda.synchronize()
+        call_us = (time.perf_counter() - t0c) / 20 * 1e6
         rows = float(aln.float().mean().item())
         commit[tag] = {"accept_len": round(rows, 3), "copy_kernel_us": round(c_avg * 1e3, 2),
-                       "call_us_with_length_reset": round((time.perf_counter() - t0c) / 20 * 1e6, 1),
+                       "call_us_with_length_reset": round(call_us, 1),
                        "bytes_moved": int(rows * w.B * len(st.layers) * w.H * w.d * 2 * 2 * 2)}
     out["commit_path"] = commit
     del st, graph

@@ -224,6 +224,8 @@ typedef struct {
     int32_t fold;           /* 0: the library chooses; 1: always fold the key splits' partial results in a second kernel */
     int32_t stages;         /* 0: the library chooses; 2 or 4: LDS stages of the bf16 sweep's K/V ring (4 needs a compute
                                unit per workgroup and trees of more than 32 rows; ignored where it cannot apply) */
+    int32_t tree_keys;      /* which workgroup of a (sequence, head) with split keys takes the tree's own keys: 0: the
+                               library chooses; 1: one of their own; 2: the first split; 3: the last split that has keys */
 } mcsd_attention_tuning_t;
 
 size_t mcsd_tree_attention_tuned_workspace(const mcsd_attention_tuning_t *tuning, int32_t prefix_fp8, int32_t B,

@@ -46,7 +46,8 @@ class Mlp(C.Structure):
 
 class AttentionTuning(C.Structure):
     """mcsd_attention_tuning_t"""
-    _fields_ = [("key_splits", C.c_int32), ("natural_order", C.c_int32), ("fold", C.c_int32), ("stages", C.c_int32)]
+    _fields_ = [("key_splits", C.c_int32), ("natural_order", C.c_int32), ("fold", C.c_int32), ("stages", C.c_int32),
+                ("tree_keys", C.c_int32)]
 
 
 class AttentionPlan(C.Structure):

@@ -50,6 +50,7 @@ struct AttnParams {
     int32_t pair_cus; // > 0: compute units; the grid has more workgroups than that and no separate tree workgroup (see the kernel)
     int32_t xcc;      // accelerator dies the hardware deals workgroup ids to round-robin (>= 1)
     int32_t fold;     // 1: the workgroup of a (sequence, unit) that finishes last folds the partial results itself
+    int32_t tree_last; // 1 (no separate tree workgroup, no pairing): the last split that has keys takes the tree's keys, else split 0
     unsigned long long *ctr;   // fold == 1: arrival counter of unit u at ctr[u * CTR_STRIDE], zero before and after every launch
     const uint32_t *ws_tag;    // fold == 1: first word of the workspace, WS_TAG once prepared
     int32_t row0;     // first query row: rows row0 .. n-1 are computed (keys are always all n tree nodes)
@@ -85,6 +86,7 @@ struct AttnPlan {
     int NS;    // LDS stages of the bf16 sweep
     int xcc;   // dies the workgroup ids are dealt to (1 when unknown: no renumbering)
     int pair_cus;  // see AttnParams
+    int tree_last; // see AttnParams
     int fold;  // 1: folded inside the sweep kernel through the L2 its workgroups share
 };
 
@@ -159,12 +161,17 @@ AttnPlan make_plan(int dtype, int B, int Hq, int Hkv, int n_rows, int max_prefix
     // resident at once (two per compute unit): the hardware dispatcher does not rebalance long workgroups that
     // start behind short ones.
     pl.G = (dtype == MCSD_BF16 && S > 1 && bh * (S + 1) <= 512) ? (int)S + 1 : (int)S;
+    pl.tree_last = 0;
+    if (tune && dtype == MCSD_BF16 && S > 1 && tune->tree_keys != 0) {
+        pl.G = tune->tree_keys == 1 ? (int)S + 1 : (int)S;
+        pl.tree_last = tune->tree_keys == 3;
+    }
     int n_cus, n_xcc;
     device_shape(n_cus, n_xcc);
     // Ragged grids larger than the chip are ordered by length inside the kernel (see there)
     pl.pair_cus = 0;
     if (dtype == MCSD_BF16 && pl.G == pl.S && (long)B * pl.S <= 256 && n_cus > 0 && bh * pl.S > n_cus &&
-        !(tune && tune->natural_order))
+        !(tune && tune->natural_order) && !pl.tree_last)
         pl.pair_cus = n_cus;
     // bf16 tiles: two stages and two workgroups per compute unit.  Four stages (64-key tiles only: a 128-key tile is
     // 64 KB) exist for measurement: on launches that have a compute unit per workgroup anyway three tiles in flight
@@ -648,12 +655,12 @@ void tree_attn_bf16_kernel(const AttnParams p)
     const int tiles_b = (L + C::T - 1) / C::T;
     const int tps = p.tps;                                  // fixed per call: short sequences use fewer splits
     const bool sep = p.G > p.S;                             // the tree's own keys have a workgroup of their own
-    const bool tree_wg = sep ? s == p.S : s == 0;
+    const int np = (tiles_b + tps - 1) / tps;               // prefix splits that have keys for this sequence (<= S)
+    const bool tree_wg = sep ? s == p.S : s == (p.tree_last ? max(np, 1) - 1 : 0);
     const int t0 = (sep && tree_wg) ? tiles_b : min(s * tps, tiles_b), t1 = min(t0 + tps, tiles_b);
     const int n_tree_tiles = tree_wg ? (p.n + C::T - 1) / C::T : 0;
     const int n_pre = t1 - t0;
     if (n_pre + n_tree_tiles == 0) return;                  // this split has no keys
-    const int np = (tiles_b + tps - 1) / tps;               // prefix splits that have keys for this sequence (<= S)
     const int n_active = sep ? np + 1 : max(1, np);         // partial results of this sequence: slots 0 .. n_active-1
     const int slot_id = (sep && tree_wg) ? np : s;
     // leading tiles of this split that are full (only the sequence's last tile can be ragged)
@@ -1375,6 +1382,7 @@ int attention_call(const mcsd_attention_tuning_t *tune, const mcsd_mask_view_t *
     if (B < 1 || H < 1 || B > 65535 || H > 65535 || max_prefix < 0) return MCSD_EINVAL;
     if (max_prefix > 0 && (!k_prefix || !v_prefix)) return MCSD_EINVAL;
     if (tune && (tune->key_splits < 0 || tune->key_splits > 64 || tune->fold < 0 || tune->fold > 1 ||
+                 tune->tree_keys < 0 || tune->tree_keys > 3 ||
                  (tune->stages != 0 && tune->stages != 2 && tune->stages != 4)))
         return MCSD_EINVAL;
     const int32_t n = mask->n_nodes;
@@ -1407,6 +1415,7 @@ int attention_call(const mcsd_attention_tuning_t *tune, const mcsd_mask_view_t *
     p.v_scale = f8 ? v_scale : 1.f;
     p.S = pl.S; p.G = pl.G; p.SP = pl.G;
     p.pair_cus = pl.pair_cus;
+    p.tree_last = pl.tree_last;
     p.xcc = pl.xcc;
     p.fold = pl.fold;
     p.tps = (int32_t)((((int64_t)max_prefix + pl.T - 1) / pl.T + pl.S - 1) / pl.S);
@@ -1545,6 +1554,7 @@ extern "C" int mcsd_tree_attention_plan(const mcsd_attention_tuning_t *tuning, m
         (dtype != MCSD_F32 && dtype != MCSD_BF16) || (prefix_fp8 && (d != 128 || dtype != MCSD_BF16)))
         return MCSD_EINVAL;
     if (tuning && (tuning->key_splits < 0 || tuning->key_splits > 64 || tuning->fold < 0 || tuning->fold > 1 ||
+                   tuning->tree_keys < 0 || tuning->tree_keys > 3 ||
                    (tuning->stages != 0 && tuning->stages != 2 && tuning->stages != 4)))
         return MCSD_EINVAL;
     const AttnPlan pl = make_plan(dtype, B, H_q, H_kv, n_nodes - row_begin, max_prefix, prefix_fp8 != 0, tuning);

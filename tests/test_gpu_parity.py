@@ -337,6 +337,21 @@ def test_every_split_count_folds_to_the_same_attention(binding, oracle, H, split
     assert np.array_equal(got, again), "the second call on the same workspace differs"
 
 
+@pytest.mark.parametrize("tree_keys", [1, 2, 3])
+@pytest.mark.parametrize("splits", [2, 3, 6, 7])
+def test_the_trees_own_keys_may_go_to_any_workgroup(binding, oracle, H, splits, tree_keys):
+    """The tree's keys with a workgroup of their own, with the first split, or with the last split that has keys
+    (ragged batch: a different split per sequence; one sequence without any prefix)."""
+    w = scaled(WORKLOADS["cfg2"], B=4, H=8, cfg_id=68)
+    inp = attention_inputs(w, seed=3, lens=(1024, 0, 130, 577))
+    ad = H.AttnDevice(inp)
+    v = binding.slice_mask(binding.build_mask(w.branching), w.gamma_max)
+    tuning = binding.AttentionTuning(key_splits=splits, tree_keys=tree_keys)
+    ad.out.fill_(float("nan"))
+    got = _tuned_attention(binding, v, ad, tuning)
+    H.assert_close(got, oracle.tree_attention(inp, oracle.build_mask(w.branching), v.n_nodes), "bf16", f"{splits} splits, tree keys {tree_keys}")
+
+
 @pytest.mark.parametrize("B,Hh,lens", [(1, 8, (1000,)), (3, 8, (0, 70, 700)), (2, 12, (513, 64)), (1, 3, (900,)), (5, 7, (300,) * 5)])
 def test_folds_for_head_counts_that_do_and_do_not_divide_over_the_dies(binding, oracle, H, B, Hh, lens):
     """The in-kernel fold needs all workgroups of a (sequence, head) on one die; with head counts that do not divide
@@ -375,7 +390,7 @@ def test_tuning_out_of_range_is_rejected(binding, H):
     ad = H.AttnDevice(attention_inputs(w, seed=0))
     v = binding.slice_mask(binding.build_mask(w.branching), w.gamma_max)
     ws = binding.new_workspace(1 << 24)
-    for bad in (binding.AttentionTuning(key_splits=65), binding.AttentionTuning(key_splits=-1), binding.AttentionTuning(fold=2)):
+    for bad in (binding.AttentionTuning(key_splits=65), binding.AttentionTuning(key_splits=-1), binding.AttentionTuning(tree_keys=4), binding.AttentionTuning(fold=2)):
         with pytest.raises(binding.McsdError) as e:
             _tuned_attention(binding, v, ad, bad, ws)
         assert e.value.status == binding.MCSD_EINVAL
