@@ -105,8 +105,10 @@ void mcsd_free_mask(mcsd_mask_t *mask);
  * k_prefix, v_prefix     : DEVICE; element (b,h,j,c) at seq_base[b] + h*head_stride + j*d + c.
  * seq_base_dev           : DEVICE int64 [B], element offsets.   prefix_lens_dev: DEVICE int32 [B], each in
  *                          0..max_prefix (larger values are clamped to max_prefix).
- * dtype                  : element type of q/k/v/out.  MCSD_BF16: bf16 in, fp32 accumulate on MFMA, bf16 out.
- *                          MCSD_F32: fp32 end to end on the vector ALU.
+ * dtype                  : element type of q/k/v/out.  MCSD_BF16: bf16 in, fp32 accumulate on MFMA, bf16 out
+ *                          (when the keys of a (sequence, head) are split over workgroups, each workgroup's
+ *                          unnormalised partial output is exchanged as bf16 with fp32 maxima and denominators: one
+ *                          more rounding of the output's own precision).  MCSD_F32: fp32 end to end on the vector ALU.
  * Limits: d in {64, 128}; 1 <= n_nodes <= MCSD_ATTN_MAX_NODES; softmax_scale finite and > 0; all tensor
  * base addresses 16-byte aligned; node_stride*d and head_stride and seq_base multiples of 8 elements.
  * workspace: DEVICE, at least mcsd_tree_attention_workspace(...) bytes (0 when the keys are not split: then it may
