@@ -87,6 +87,7 @@ struct AttnPlan {
     int xcc;   // dies the workgroup ids are dealt to (1 when unknown: no renumbering)
     int pair_cus;  // see AttnParams
     int tree_last; // see AttnParams
+    long grid_units; // (sequence, unit) slots of the grid: B * units, rounded up to a multiple of the dies where that lets the fold run in the kernel
     int fold;  // 1: folded inside the sweep kernel through the L2 its workgroups share
 };
 
@@ -182,8 +183,15 @@ AttnPlan make_plan(int dtype, int B, int Hq, int Hkv, int n_rows, int max_prefix
     pl.xcc = n_xcc > 0 ? n_xcc : 8;        // unknown: the renumbering is then only a guess that may help locality
     // The fold runs inside the sweep when all workgroups of one (sequence, unit) share a die's L2: the dealing of
     // workgroup ids to dies is known, and the kernel's numbering keeps a unit's workgroups at one id modulo dies.
-    const long total = bh * pl.G;
-    bool same_die = n_xcc == 1 || (n_xcc > 1 && total % n_xcc == 0 && bh % n_xcc == 0);
+    // A number of (sequence, unit) pairs that is no multiple of the dies is rounded up: the workgroups of the slots
+    // beyond the last pair leave at once, and every real pair's workgroups still share a die.
+    pl.grid_units = bh;
+    bool same_die = n_xcc == 1;
+    if (n_xcc > 1 && pl.pair_cus == 0) {
+        same_die = true;
+        if (dtype == MCSD_BF16 && pl.S > 1) pl.grid_units = (bh + n_xcc - 1) / n_xcc * n_xcc;
+        else same_die = bh % n_xcc == 0;
+    }
     if (pl.pair_cus > 0) same_die = n_xcc == 1 || (n_xcc > 1 && pl.units % n_xcc == 0 && pl.pair_cus % n_xcc == 0);
     pl.fold = dtype == MCSD_BF16 && pl.S > 1 && same_die && pl.G <= FOLD_MAX_PARTIALS &&
               (size_t)bh * CTR_STRIDE * sizeof(unsigned long long) <= WS_CTR_BYTES && !(tune && tune->fold == 1);
@@ -644,6 +652,7 @@ void tree_attn_bf16_kernel(const AttnParams p)
         s = cls % p.S;
         bhi = (cls / p.S) * p.H + r % p.H;
     }
+    if (bhi >= p.B * p.H) return;                            // a slot of a grid rounded up to whole dies
     const int h = bhi % p.H, b = bhi / p.H;
 
     const int g = lane >> 5, ln = lane & 31;
@@ -1302,7 +1311,7 @@ __global__ __launch_bounds__(256) void workspace_init_kernel(uint4 *ws)
 template <int D, int QBP, int NS, bool F8 = false>
 void launch_sweep(const AttnParams &p, const AttnPlan &pl, hipStream_t st)
 {
-    const dim3 grid((unsigned)((size_t)pl.G * p.H * p.B));
+    const dim3 grid((unsigned)((size_t)pl.G * pl.grid_units));
     mcsd_launch(MCSD_KERNEL_ATTN_SWEEP, tree_attn_bf16_kernel<D, QBP, NS, F8>, grid, dim3(SweepCfg<D, QBP, NS, F8>::THREADS), st, p);
 }
 
@@ -1399,7 +1408,7 @@ int attention_call(const mcsd_attention_tuning_t *tune, const mcsd_mask_view_t *
     if (((node_stride * d) & 7) || (head_stride & (f8 ? 15 : 7))) return MCSD_EINVAL;   // 16-byte rows and heads
 
     const AttnPlan pl = make_plan(dtype, B, H_q, H_kv, n - row_begin, max_prefix, f8, tune);
-    if ((int64_t)pl.G * pl.units * B > 0x7fffffff) return MCSD_EUNSUPPORTED;           // one-dimensional grid
+    if ((int64_t)pl.G * pl.grid_units > 0x7fffffff) return MCSD_EUNSUPPORTED;           // one-dimensional grid
     const size_t need = workspace_bytes_for(pl, dtype, B, d, n);
     if (need > 0 && (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 255))) return MCSD_EWORKSPACE;
 
@@ -1561,7 +1570,7 @@ extern "C" int mcsd_tree_attention_plan(const mcsd_attention_tuning_t *tuning, m
     out->mfma_path = dtype == MCSD_BF16;
     out->query_blocks = pl.QBP;
     out->key_splits = pl.S;
-    out->workgroups = (int32_t)((int64_t)pl.G * pl.units * B);
+    out->workgroups = (int32_t)((int64_t)pl.G * (dtype == MCSD_BF16 ? pl.grid_units : (long)pl.units * B));
     out->stages = dtype == MCSD_BF16 ? pl.NS : 0;
     out->fold_in_kernel = pl.fold;
     out->ordered_by_length = pl.pair_cus > 0;
