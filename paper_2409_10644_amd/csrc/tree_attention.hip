@@ -139,14 +139,17 @@ AttnPlan make_plan(int dtype, int B, int Hq, int Hkv, int n_rows, int max_prefix
     }
     const long bh = (long)B * pl.units;
     const long tiles_max = (max_prefix + pl.T - 1) / pl.T;
-    // Key splits: enough workgroups for two per compute unit, at least four tiles per split (five with four query
-    // blocks, whose partial result is twice the bytes), at most 8 splits: every split costs a partial result of n
-    // rows that is written, read back and folded.
+    // Key splits: enough workgroups for two per compute unit, at least four tiles per split (two of the 128-key
+    // tiles of a single query block: the same bytes), at most 8 splits (6 with four query blocks, whose partial result
+    // is twice the bytes: six splits and the tree's workgroup are what the seven-slot fold takes in one pass): every
+    // split costs a partial result of n rows that is written, read back and folded.  Measured: one query block, 1024
+    // keys: 14.3 -> 11.3 us per call with four splits instead of two; four query blocks, 1024 keys: 15.2 -> 13.2 us
+    // with four instead of three; 2048 keys: 16.9 us with six, 17.8 us with seven.
     long S = (512 + bh - 1) / bh;
     // (the vector-ALU path is slow per tile: split it all the way)
-    const long min_tiles = dtype == MCSD_BF16 ? (pl.QBP == 4 ? 5 : 4) : 1;
+    const long min_tiles = dtype == MCSD_BF16 ? (pl.QBP == 1 ? 2 : 4) : 1;
     if (S > tiles_max / min_tiles) S = tiles_max / min_tiles;
-    if (dtype == MCSD_BF16 && S > 8) S = 8;
+    if (dtype == MCSD_BF16 && S > (pl.QBP == 4 ? 6 : 8)) S = pl.QBP == 4 ? 6 : 8;
     if (S < 1) S = 1;
     if (S > 64) S = 64;
     // One split less when the streaming workgroups alone would have a compute unit each (256) but not together with
