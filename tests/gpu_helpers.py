@@ -119,6 +119,7 @@ class DynamicIteration:
         i32 = dict(dtype=torch.int32, device="cuda")
         self.prob = torch.zeros((w.B, self.W), dtype=torch.float32, device="cuda")
         self.stop = torch.zeros((w.B,), **i32)
+        self.stop_host = torch.zeros((w.B,), dtype=torch.int32, pin_memory=True)   # where the host reads the decision
         self.path = {g: torch.full((w.B, g), -9, **i32) for g in levels}
         self.ids = {g: torch.full((w.B, g + 1), -9, **i32) for g in levels}
         self.alen, self.new, self.n_ids = torch.full((w.B,), -9, **i32), torch.full((w.B, 1), -9, **i32), torch.full((w.B,), -9, **i32)
@@ -191,7 +192,9 @@ class DynamicIteration:
         for g in range(1, gamma + 1):
             level_fn(g)
             if g < self.D:
-                flags.append(self.stop.cpu().numpy().copy())          # synchronises: the decision the loop waits for
+                self.stop_host.copy_(self.stop, non_blocking=True)    # the decision the loop waits for
+                torch.cuda.current_stream().synchronize()
+                flags.append(self.stop_host.numpy().copy())
                 if force_gamma is None and bool(flags[-1].all()):
                     gamma = g
                     break
