@@ -690,6 +690,9 @@ def main():
         out["cpu_baseline"] = cpu_baseline(st, t_attn_cpu)
     # the draft side of the loop: attention for the newest level only, a fresh slice of the mask per level
     lvl = {}
+    lvl_ws = binding.new_workspace(max(binding.tree_attention_rows_workspace(w.B, w.H, w.d, binding.slice_mask(st.mask, g).n_nodes,
+                                                                           int(binding.slice_mask(st.mask, g).level_off_host[g - 1]), st.cap)
+                                       for g in range(1, st.gamma + 1)))
     for g in range(1, st.gamma + 1):
         vg = binding.slice_mask(st.mask, g)
         rb = int(vg.level_off_host[g - 1])
@@ -697,7 +700,7 @@ def main():
         def level_call(i, vg=vg, rb=rb):
             a = st.layers[i % len(st.layers)]
             binding.tree_attention_rows(vg, a.code, w.B, w.H, w.d, rb, a.q, a.kt, a.vt, a.node_stride, a.kp, a.vp, a.base,
-                                        a.lens, a.head_stride, st.cap, a.scale, a.out, st.ws)
+                                        a.lens, a.head_stride, st.cap, a.scale, a.out, lvl_ws)
         for i in range(8):
             level_call(i)
         torch.cuda.synchronize()

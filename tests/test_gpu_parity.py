@@ -337,6 +337,24 @@ def test_every_split_count_folds_to_the_same_attention(binding, oracle, H, split
     assert np.array_equal(got, again), "the second call on the same workspace differs"
 
 
+@pytest.mark.parametrize("splits", [1, 2, 3])
+@pytest.mark.parametrize("d", [128, 64])
+@pytest.mark.parametrize("branching", [(8, 2, 2, 1, 1), (4, 2, 2, 2), (3, 2, 2, 1, 1, 1, 1, 1)])
+def test_the_four_stage_ring_matches_the_oracle(binding, oracle, H, branching, d, splits):
+    """stages = 4: the four-stage ring of the bf16 sweep (a measurement option), for two and four query blocks and both
+    head dimensions.  Prefix lengths from no full tile to more tiles than stages, with and without a ragged last
+    tile, in one ragged batch; every element against the oracle."""
+    lens = (0, 63, 64, 65, 128, 200, 256, 321, 384, 449, 512, 600, 1024, 1087)
+    w = scaled(WORKLOADS["cfg5"], B=len(lens), H=2, d=d, branching=branching, prefix_min=0, prefix_max=max(lens), cfg_id=69)
+    inp = attention_inputs(w, seed=7, lens=lens)
+    ad = H.AttnDevice(inp)
+    v = binding.slice_mask(binding.build_mask(branching), len(branching))
+    tuning = binding.AttentionTuning(key_splits=splits, stages=4)
+    ad.out.fill_(float("nan"))
+    got = _tuned_attention(binding, v, ad, tuning)
+    H.assert_close(got, oracle.tree_attention(inp, oracle.build_mask(branching), v.n_nodes), "bf16", f"stages 4, {splits} splits, d {d}")
+
+
 @pytest.mark.parametrize("tree_keys", [1, 2, 3])
 @pytest.mark.parametrize("splits", [2, 3, 6, 7])
 def test_the_trees_own_keys_may_go_to_any_workgroup(binding, oracle, H, splits, tree_keys):
