@@ -73,11 +73,12 @@ def test_steady_state_loops_wait_for_memory_once_per_tile(sweep_asm):
         else:
             # four-stage ring, four tiles per trip; a step waits for all loads but those of the two, one or zero tiles
             # requested after its own (three alternative instructions), right before its barrier, and nowhere else
-            # (the longest backward branch that spans exactly the ring's four barriers: block placement can add
-            # backward jumps from the kernel's epilogue that are no loops)
+            # (of the backward branches that span exactly the ring's four barriers the one with the fewest waits, the
+            # longest of those: block placement adds backward jumps from the kernel's epilogue whose spans hold the
+            # loop plus the waits before and after it; a wait the compiler added inside the loop is in every span)
             four = [x for x in loops if sum("s_barrier" in y.split(";")[0] for y in x) == 4]
             assert four, f"{name}: no four-tile loop found"
-            loop = max(four, key=len)
+            loop = min(four, key=lambda x: (sum("vmcnt" in y.split(";")[0] for y in x), -len(x)))
             code = [x.split(";")[0] for x in loop if x.split(";")[0].strip() and not x.strip().startswith(".")]
             wait_at = [i for i, x in enumerate(code) if "vmcnt" in x]
             barrier_at = [i for i, x in enumerate(code) if "s_barrier" in x]
