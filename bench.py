@@ -1014,6 +1014,33 @@ def main():
         del ga, gb, gc
     except Exception as ex:
         out["gemm_probe"] = {"error": repr(ex)}
+    # how far this machine overlaps the inner loop's matrix instructions with its vector work (no memory traffic):
+    # the arrangement the sweep relies on (two wavefronts per SIMD, free-running) against the alternatives
+    try:
+        n_wg = torch.cuda.get_device_properties(0).multi_processor_count
+        pout = torch.empty(n_wg * 512, dtype=torch.float32, device="cuda")
+        iters = 2000
+        names = ["one_per_simd_phases_in_turn", "two_per_simd_free_running", "two_per_simd_alternating_under_barriers",
+                 "one_per_simd_software_pipelined", "two_per_simd_software_pipelined"]
+        res = {}
+        for sched, nm in enumerate(names):
+            for _ in range(3):
+                binding.issue_probe(sched, n_wg, iters, pout)
+            e0, e1 = hip.event(), hip.event()
+            hip.record(e0)
+            for _ in range(10):
+                binding.issue_probe(sched, n_wg, iters, pout)
+            hip.record(e1)
+            ms = hip.elapsed_ms(e0, e1) / 10
+            hip.destroy(e0)
+            hip.destroy(e1)
+            blocks = iters * (1 if sched in (0, 3) else 2)            # 32-key blocks per SIMD and launch
+            res[nm] = {"ns_per_block": round(ms * 1e6 / blocks, 1), "mfma_pipe_busy": round(blocks * 16 * 32 / 2.4e9 / (ms * 1e-3), 3)}
+        out["issue_probe"] = {"what": "arithmetic of the sweep's inner loop for one 32-key block (16 MFMA 32x32x16 + soft-max of 16 "
+                                      "scores per lane), no memory traffic, one workgroup per compute unit; mfma_pipe_busy assumes 32 "
+                                      "cycles per MFMA at 2.4 GHz", **res}
+    except Exception as ex:
+        out["issue_probe"] = {"error": repr(ex)}
     if extra:
         out["other_workloads"] = extra
     print(json.dumps(out), flush=True)

@@ -417,6 +417,16 @@ int mcsd_profile_next(mcsd_kernel_t kernel, void *start_event, void *stop_event)
  * workgroups of 256 lanes, 0 for the default of 1024. */
 int mcsd_stream_read(const void *src_dev, size_t bytes, void *sink_dev, int32_t workgroups, void *hip_stream);
 
+/* Measurement aid (not part of the method).  Runs the arithmetic of the tree-attention inner loop for one 32-key block
+ * per iteration (16 MFMA 32x32x16 bf16 + maximum, 16 exponentials and bf16 packing per lane) with no memory traffic,
+ * one workgroup per compute unit, under one of five arrangements of matrix and vector phases:
+ *   0 one wavefront per SIMD, phases one after the other;  1 two per SIMD, free-running;  2 two per SIMD, alternating
+ *   under workgroup barriers;  3 one per SIMD, software-pipelined within the wavefront;  4 two per SIMD, both pipelined.
+ * Timed by the caller (events on the stream), it shows how far this machine overlaps matrix instructions with the
+ * vector work of the same and of another wavefront.  out_dev: DEVICE, workgroups * 512 floats, overwritten.
+ * iterations: even, 2 .. 2^20.  workgroups: 1 .. 65535. */
+int mcsd_issue_probe(int32_t schedule, int32_t workgroups, int32_t iterations, void *out_dev, void *hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

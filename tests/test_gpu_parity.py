@@ -859,3 +859,22 @@ def test_ragged_batches_with_more_workgroups_than_compute_units(binding, oracle,
     got = H.run_attention(binding, v, ad, max_prefix=640, fill=float("nan"))
     # the output started as NaN: every row of every (sequence, head) was written, and with the right values
     H.assert_close(got, oracle.tree_attention(inp, oracle.build_mask(br), v.n_nodes), "bf16", f"B{B} H{Hh}")
+
+
+# ------------------------------------------------------------------------------------------------
+# measurement aids
+def test_issue_probe_runs_every_schedule_and_rejects_bad_arguments(binding):
+    """The matrix / vector overlap probe (a measurement aid): every schedule runs to completion and writes finite
+    values; arguments outside the documented ranges are refused before anything is launched."""
+    out = torch.full((4 * 512,), float("nan"), dtype=torch.float32, device="cuda")
+    for schedule in range(5):
+        out.fill_(float("nan"))
+        binding.issue_probe(schedule, 4, 16, out)
+        torch.cuda.synchronize()
+        lanes = out.view(4, 512)[:, :256] if schedule in (0, 3) else out.view(4, 512)    # one wavefront per SIMD: the upper half retires at once
+        assert bool(torch.isfinite(lanes).all()), schedule
+    for bad in ((5, 4, 16), (-1, 4, 16), (0, 0, 16), (0, 4, 15), (0, 4, 0), (0, 70000, 16)):
+        with pytest.raises(binding.McsdError) as e:
+            binding.issue_probe(*bad, out)
+        assert e.value.status == binding.MCSD_EINVAL
+
