@@ -370,6 +370,27 @@ def test_the_trees_own_keys_may_go_to_any_workgroup(binding, oracle, H, splits, 
     H.assert_close(got, oracle.tree_attention(inp, oracle.build_mask(w.branching), v.n_nodes), "bf16", f"{splits} splits, tree keys {tree_keys}")
 
 
+@pytest.mark.parametrize("B,Hh,d,lens", [(1, 32, 128, (1024,)), (1, 12, 64, (1024,)), (5, 8, 128, (1024, 0, 130, 577, 900))])
+def test_two_hundred_calls_on_one_workspace_give_the_same_bits(binding, H, B, Hh, d, lens):
+    """The fold inside the sweep hands the partial results over through arrival counters that every call must leave
+    at zero, and whichever workgroup arrives last folds: 200 back-to-back calls on one workspace, without the host
+    in between, must all give the bits of the first (whole head counts, one that is rounded up to whole dies, a ragged
+    batch)."""
+    w = scaled(WORKLOADS["cfg2"], B=B, H=Hh, d=d, cfg_id=70)
+    ad = H.AttnDevice(attention_inputs(w, seed=1, lens=lens))
+    v = binding.slice_mask(binding.build_mask(w.branching), w.gamma_max)
+    ws = binding.new_workspace(binding.tree_attention_workspace(ad.B, ad.H, ad.d, v.n_nodes, ad.max_prefix))
+    outs = []
+    for i in range(200):
+        ad.out.fill_(float("nan"))
+        binding.tree_attention(v, ad.code, ad.B, ad.H, ad.d, ad.q, ad.kt, ad.vt, ad.node_stride, ad.kp, ad.vp, ad.base, ad.lens,
+                               ad.head_stride, ad.max_prefix, ad.scale, ad.out, ws)
+        outs.append(ad.out[:, :, :v.n_nodes].clone())
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(outs[0].float()).all())
+    assert all(torch.equal(o.view(torch.int16), outs[0].view(torch.int16)) for o in outs[1:])
+
+
 @pytest.mark.parametrize("B,Hh,lens", [(1, 8, (1000,)), (3, 8, (0, 70, 700)), (2, 12, (513, 64)), (1, 3, (900,)), (5, 7, (300,) * 5)])
 def test_folds_for_head_counts_that_do_and_do_not_divide_over_the_dies(binding, oracle, H, B, Hh, lens):
     """The in-kernel fold needs all workgroups of a (sequence, head) on one die; with head counts that do not divide
