@@ -1041,6 +1041,26 @@ def main():
                                       "cycles per MFMA at 2.4 GHz", **res}
     except Exception as ex:
         out["issue_probe"] = {"error": repr(ex)}
+    # where the workgroups of a sweep-shaped grid run: dies by id, and which ids share a compute unit
+    try:
+        n_cu = torch.cuda.get_device_properties(0).multi_processor_count
+        pl_out = torch.zeros(2 * 2 * n_cu, dtype=torch.int32, device="cuda")
+        stats = []
+        for _ in range(5):
+            binding.placement_probe(2 * n_cu, 20000, pl_out)
+            torch.cuda.synchronize()
+            a = pl_out.cpu().numpy().astype(np.int64).reshape(2 * n_cu, 2)
+            die, cu = a[:, 0], (a[:, 0] << 16) | (a[:, 1] & 0xff00)      # compute unit = (die, shader engine, array, cu)
+            n_die = int(die.max()) + 1
+            stats.append((n_die, float(np.mean(die == (die[0] + np.arange(2 * n_cu)) % n_die)), float(np.mean(cu[:n_cu] == cu[n_cu:])),
+                          int(len(set(cu.tolist())))))
+        out["placement_probe"] = {"workgroups": 2 * n_cu, "launches": len(stats), "dies": stats[0][0],
+                                  "ids_dealt_round_robin_to_dies": round(min(s[1] for s in stats), 4),
+                                  "pairs_i_and_i_plus_cus_on_one_compute_unit": round(min(s[2] for s in stats), 4),
+                                  "distinct_compute_units": min(s[3] for s in stats),
+                                  "what": "minimum over the launches; a grid of two sweep-shaped workgroups per compute unit"}
+    except Exception as ex:
+        out["placement_probe"] = {"error": repr(ex)}
     if extra:
         out["other_workloads"] = extra
     print(json.dumps(out), flush=True)

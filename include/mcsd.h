@@ -427,6 +427,14 @@ int mcsd_stream_read(const void *src_dev, size_t bytes, void *sink_dev, int32_t 
  * iterations: even, 2 .. 2^20.  workgroups: 1 .. 65535. */
 int mcsd_issue_probe(int32_t schedule, int32_t workgroups, int32_t iterations, void *out_dev, void *hip_stream);
 
+/* Measurement aid (not part of the method).  Launches `workgroups` workgroups shaped like the bf16 sweep's (256 lanes,
+ * 66 KiB of LDS: two per compute unit), keeps each busy for `spin` (0 .. 2^20) steps of a dependent multiply-add chain
+ * so that the grid is resident together, and writes two words per workgroup to out_dev (DEVICE, workgroups * 2
+ * uint32): the die it ran on (XCC_ID) and its hardware id word (HW_ID: compute unit in bits 8-11, shader array in
+ * bit 12, shader engine in bits 13-15).  Shows how workgroup ids are dealt to dies and which ids share a compute
+ * unit, the two facts the sweep's workgroup numbering is built on (nothing but speed depends on the second). */
+int mcsd_placement_probe(int32_t workgroups, int32_t spin, void *out_dev, void *hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

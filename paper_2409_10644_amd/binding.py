@@ -21,7 +21,7 @@ EXPORTS = ["mcsd_strerror", "mcsd_build_mask", "mcsd_slice_mask", "mcsd_free_mas
            "mcsd_tree_attention_gqa_workspace", "mcsd_tree_attention_gqa",
            "mcsd_tree_attention_fp8kv_workspace", "mcsd_tree_attention_fp8kv",
            "mcsd_verify_tree_workspace", "mcsd_verify_tree", "mcsd_verify_tree_sampling", "mcsd_commit_path", "mcsd_early_stop_distribution",
-           "mcsd_early_stop_hidden", "mcsd_profile_next", "mcsd_stream_read", "mcsd_issue_probe", "mcsd_workspace_init",
+           "mcsd_early_stop_hidden", "mcsd_profile_next", "mcsd_stream_read", "mcsd_issue_probe", "mcsd_placement_probe", "mcsd_workspace_init",
            "mcsd_tree_attention_tuned_workspace", "mcsd_tree_attention_tuned", "mcsd_tree_attention_static",
            "mcsd_tree_attention_plan"]
 STATIC_SCRATCH_BYTES = 24 * 1024 * 1024
@@ -125,6 +125,8 @@ def _load() -> C.CDLL:
     lib.mcsd_stream_read.argtypes = [vp, C.c_size_t, vp, i32, vp]
     lib.mcsd_issue_probe.restype = C.c_int
     lib.mcsd_issue_probe.argtypes = [i32, i32, i32, vp, vp]
+    lib.mcsd_placement_probe.restype = C.c_int
+    lib.mcsd_placement_probe.argtypes = [i32, i32, vp, vp]
     lib.mcsd_tree_attention_static.restype = C.c_int
     lib.mcsd_tree_attention_static.argtypes = [C.POINTER(MaskView), C.c_int, i32, i32, i32, vp, vp, vp, i64, vp, vp, vp,
                                                vp, i64, i32, C.c_float, vp, vp]
@@ -413,6 +415,10 @@ def early_stop_hidden(mlp: Mlp, B: int, W: int, hidden: torch.Tensor, batch_stri
 def stream_read(src: torch.Tensor, sink: torch.Tensor, workgroups: int = 0, stream=None) -> None:
     _check(lib.mcsd_stream_read(_ptr(src), src.numel() * src.element_size(), _ptr(sink), workgroups, _stream(stream)),
            "mcsd_stream_read")
+
+
+def placement_probe(workgroups: int, spin: int, out: torch.Tensor, stream=None) -> None:
+    _check(lib.mcsd_placement_probe(workgroups, spin, _ptr(out), _stream(stream)), "mcsd_placement_probe")
 
 
 def issue_probe(schedule: int, workgroups: int, iterations: int, out: torch.Tensor, stream=None) -> None:

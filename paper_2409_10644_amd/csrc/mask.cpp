@@ -52,7 +52,9 @@ static void probe_xcc_once(int device)
             for (int i = 0; i < XCC_PROBE_WGS; ++i) mx = host[i] > mx ? host[i] : mx;
             const int n = mx + 1;
             ok = (n == 1 || n == 2 || n == 4 || n == 8) && (rep == 0 || n == dies);
-            for (int i = 0; i < XCC_PROBE_WGS && ok; ++i) ok = host[i] == i % n;
+            // round-robin from whichever die is next: what the kernels rely on is that ids congruent modulo the number
+            // of dies share a die
+            for (int i = 0; i < XCC_PROBE_WGS && ok; ++i) ok = host[i] == (host[0] + i) % n;
             dies = n;
         }
         if (ok) result = dies;

@@ -169,7 +169,35 @@ hipError_t launch_issue_probe(float *out, int workgroups, int iterations, hipStr
     return hipGetLastError();
 }
 
+// Third measurement aid: where the workgroups of a sweep-shaped grid run.  256 lanes and 66 KiB of LDS per workgroup
+// (two fit a compute unit, like the bf16 sweep's); every workgroup stays for `spin` iterations of a dependent
+// arithmetic chain so that the whole grid is resident at once, then writes its die (XCC_ID) and its HW_ID word.
+__global__ __launch_bounds__(256) void placement_probe_kernel(uint32_t *out, int spin)
+{
+    extern __shared__ unsigned char place_lds[];
+    unsigned xcc, hw;
+    asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(xcc));
+    asm volatile("s_getreg_b32 %0, hwreg(HW_REG_HW_ID)" : "=s"(hw));
+    float v = (float)threadIdx.x;
+    for (int i = 0; i < spin; ++i) v = fmaf(v, 1.0000001f, 0.5f);
+    if (threadIdx.x == 0) {
+        out[2 * blockIdx.x] = xcc & 15u;
+        out[2 * blockIdx.x + 1] = hw;
+        if (v == -1.f) place_lds[0] = 1;                     // (keeps the chain and the LDS allocation alive)
+    }
+}
+
 }  // namespace
+
+extern "C" int mcsd_placement_probe(int32_t workgroups, int32_t spin, void *out_dev, void *hip_stream)
+{
+    if (!out_dev || workgroups < 1 || workgroups > 65535 || spin < 0 || spin > (1 << 20)) return MCSD_EINVAL;
+    const size_t lds = 66 * 1024;
+    hipError_t e = hipFuncSetAttribute((const void *)placement_probe_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return mcsd_hip_status(e);
+    hipLaunchKernelGGL(placement_probe_kernel, dim3(workgroups), dim3(256), lds, (hipStream_t)hip_stream, (uint32_t *)out_dev, spin);
+    return mcsd_hip_status(hipGetLastError());
+}
 
 extern "C" int mcsd_issue_probe(int32_t schedule, int32_t workgroups, int32_t iterations, void *out_dev, void *hip_stream)
 {

@@ -899,3 +899,18 @@ def test_issue_probe_runs_every_schedule_and_rejects_bad_arguments(binding):
             binding.issue_probe(*bad, out)
         assert e.value.status == binding.MCSD_EINVAL
 
+
+def test_placement_probe_reports_dies_and_compute_units(binding):
+    """The placement probe (a measurement aid): ids congruent modulo the number of dies share a die, which is what
+    the fold inside the sweep relies on (the library checks it itself before planning that fold)."""
+    n = 64
+    out = torch.full((2 * n,), -1, dtype=torch.int32, device="cuda")
+    binding.placement_probe(n, 1000, out)
+    torch.cuda.synchronize()
+    die = out.cpu().numpy().reshape(n, 2)[:, 0]
+    n_die = int(die.max()) + 1
+    assert n_die in (1, 2, 4, 8) and (die >= 0).all()
+    assert all(die[i] == die[i % n_die] for i in range(n))
+    with pytest.raises(binding.McsdError):
+        binding.placement_probe(0, 0, out)
+
