@@ -13,8 +13,8 @@ McsdProfileSlot g_mcsd_profile[6];      // static storage: both atomics of every
 // a launch deals its workgroups to the dies round-robin by workgroup id.  The tree-attention sweep folds the
 // partial results of its key splits through the L2 when the workgroups of one (sequence, head) sit on one die,
 // so the dealing is checked once per device, here, on the hardware: every workgroup of a small launch reports the
-// id of its die.  Result: the number of dies when workgroup i runs on die i % dies for all i, else 0 (the sweep
-// then leaves the fold to its second kernel).
+// id of its die.  Result: the number of dies when workgroup i runs on die (first + i) % dies for all i, whichever die
+// the launch started with, else 0 (the sweep then leaves the fold to its second kernel).
 // ---------------------------------------------------------------------------------------------------
 namespace {
 constexpr int XCC_PROBE_WGS = 256;
