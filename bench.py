@@ -656,8 +656,12 @@ def main():
                    "untimed_steps_before": n_ramp, "verified_vs_oracle": True, "verify_seed": v_seed,
                    "mean_accept_len": round(alpha, 3)},
         "roofline": roof,
+        # verify_walk: caches overwritten before the launch; verify_walk_in_step: what the walk adds to the replayed
+        # step, i.e. the step minus its 32 sweeps timed the same way (replays of a graph, launch gap included in both)
         "kernels_us": {"attn_sweep": roof["avg_launch_us"], "attn_merge": round(m_avg * 1e3, 2),
-                       "verify_walk": vsec["avg_launch_us"]},
+                       "verify_walk": vsec["avg_launch_us"],
+                       "verify_walk_in_step": round(ms_per_step * 1e3 - N_LAYERS * roof["avg_launch_us"], 2)
+                       if launch == "hip-graph" and roof.get("timed", "").startswith("one HIP event pair around") else None},
         "verify_roofline": vsec,
     }
     # the same verification for candidates drawn without replacement (a scheme next to the paper's), same shapes
